@@ -1,0 +1,132 @@
+#!/usr/bin/env python3
+"""Benchmark of the VADUSA speculative decode step on one MI355X.
+
+One "step" = one vadusa_step: tree expansion, tree-masked forward of all tree
+nodes through every layer, acceptance, KV compaction and the draft heads for the
+next step.  Workload: the 12-layer d=1024 bf16 decoder at batch 1 with a 64-node
+tree (64 text + 225 prompt tokens, then one whole 750-step generation with
+random-init draft heads, i.e. one committed token per step, L = 289 -> 1039).
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(m, B, M, L_mean):
+    """Bytes one step must move: every weight once, every committed KV row once, tree KV written once."""
+    s = 2 if m.dtype == "bf16" else 4
+    d, F, V1 = m.d_model, m.d_ffn, m.n_logits
+    w_layers = m.n_layers * (3 * d * d + d * d + 2 * d * F) * s
+    w_out = V1 * d * s
+    w_draft = m.n_draft_heads * (d * d + V1 * d) * s
+    kv_pos = m.n_layers * 2 * d * s
+    return w_layers + w_out + w_draft + B * L_mean * kv_pos + B * M * kv_pos
+
+
+def cpu_baseline(wl, W, text, prompt, tree, budget_s=15.0):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
+    from oracle import vadusa_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    model = O.Model(wl.model, W)
+    sts = [O.prefill(model, t, p) for t, p in zip(text, prompt)]
+    n, t0 = 0, time.perf_counter()
+    while True:
+        for st in sts:
+            O.step(model, st, tree, 1, ignore_eos=True)
+        n += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or n >= 200:
+            break
+    return {"value": len(sts) * tree.n_nodes * n / el, "unit": "tree tokens/s", "cores": int(cores),
+            "kind": "oracle", "us_per_step": el / n * 1e6,
+            "sample": f"{n} oracle steps (numpy fp64) from L={len(text[0]) + len(prompt[0])} after an untimed oracle prefill"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=750)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="valle_b1")
+    ap.add_argument("--tau", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the step shards over sequences, "
+              "see DESIGN.md, but no multi-GPU path is built)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from synth import PRESETS, make_weights, make_tokens, make_tree
+    from paper_2410_21951_amd import Vadusa, TreeArrays
+    wl = PRESETS[a.workload]
+    m = wl.model
+    torch.cuda.set_device(0)
+    W = make_weights(m, wl.seed)
+    text, prompt = make_tokens(wl)
+    tree = make_tree(wl.tree_nodes, wl.topk_caps)
+    tarr = TreeArrays(tree.parent, tree.rank)
+    dev = Vadusa(m, max_batch=wl.batch, max_tree_nodes=wl.tree_nodes, ignore_eos=True)
+    dev.load_weights(W)
+    B, M = wl.batch, wl.tree_nodes
+    L0 = [len(t) + len(p) for t, p in zip(text, prompt)]
+    seg = min(wl.n_generate, (m.max_positions - M - max(L0)) // (m.n_draft_heads + 1) if False else wl.n_generate)
+
+    dev.prefill(text, prompt)
+    for _ in range(a.warmup):
+        dev.step(tarr, a.tau, sync=False)
+    torch.cuda.synchronize()
+
+    total_ms, done, L_sum = 0.0, 0, 0.0
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    while done < a.steps:
+        k = min(seg, a.steps - done)
+        dev.prefill(text, prompt)                 # untimed: back to L = L0
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(k):
+            dev.step(tarr, a.tau, sync=False)
+        ev1.record()
+        torch.cuda.synchronize()
+        total_ms += ev0.elapsed_time(ev1)
+        n_out = [len(dev.read_output(b)) for b in range(B)]
+        # mean committed length over the segment (linear growth from L0 to L0 + n_out)
+        L_sum += k * (np.mean(L0) + np.mean(n_out) / 2.0)
+        done += k
+    ms_step = total_ms / a.steps
+    L_mean = L_sum / a.steps
+    nbytes = algorithmic_bytes(m, B, M, L_mean)
+    achieved = nbytes / (ms_step * 1e-3) / 1e9
+    out = {
+        "metric": "verified_tree_tokens_per_s", "value": B * M / (ms_step * 1e-3), "unit": "tree tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
+        "us_per_step": ms_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": m.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {m.n_layers}L d={m.d_model} {m.dtype}, batch {B}, {M}-node tree, "
+                               f"tau={a.tau}, L {int(np.mean(L0))}->{int(np.mean(L0) + np.mean(n_out))}",
+                   "mean_committed_per_step": float(np.mean(n_out)) / min(seg, a.steps)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "whole step (all launches of one vadusa_step)",
+                     "algorithmic_bytes_per_step": nbytes},
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, W, text, prompt, tree)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -161,6 +161,7 @@ class SeqState:
     L: int                         # committed positions
     root: int                      # base head's next token (t_{k+1,0})
     draft_logits: List[np.ndarray]  # per draft head, logits from the last accepted position
+    root_logits: Optional[np.ndarray] = None   # the base-head row the root was taken from
     finished: bool = False
     emitted: List[int] = field(default_factory=list)
 
@@ -175,7 +176,8 @@ def prefill(model, text, prompt):
     V = np.zeros_like(K)
     K[:, :L], V[:, :L] = f["K"], f["V"]
     root = int(top_k(f["logits"][-1], 1)[0])
-    return SeqState(K=K, V=V, L=L, root=root, draft_logits=draft_heads(model, f["h"][-1]))
+    return SeqState(K=K, V=V, L=L, root=root, draft_logits=draft_heads(model, f["h"][-1]),
+                    root_logits=f["logits"][-1])
 
 
 def draft_lists(model, st, tree):
@@ -291,6 +293,7 @@ def step(model, st, tree, tau, draft_override=None, ignore_eos=False):
     st.L += n
     last = path[-1]
     st.root = int(top_k(logits[last], 1)[0])          # prediction of the last accepted token
+    st.root_logits = logits[last]
     st.draft_logits = draft_heads(model, h[last])     # new drafts from that position
     st.emitted += accepted
     return dict(accepted=accepted, path=path, tok=tok, logits=logits, lists=lists,

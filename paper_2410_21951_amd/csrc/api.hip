@@ -1,0 +1,651 @@
+// C ABI of libvadusa: argument checks, arena layout, weight loading and the
+// order in which the kernels of a prefill / verification / compaction run.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "common.h"
+
+// ---------------------------------------------------------------------------
+// small host helpers
+// ---------------------------------------------------------------------------
+static void set_msg(char* msg, size_t n, const char* fmt, ...) {
+    if (!msg || !n) return;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(msg, n, fmt, ap);
+    va_end(ap);
+}
+
+static int fail(vadusa_ctx* c, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c) c->err = buf;
+    return code;
+}
+
+#define HIP_TRY(c, call)                                                                   \
+    do {                                                                                   \
+        hipError_t e_ = (call);                                                            \
+        if (e_ != hipSuccess)                                                              \
+            return fail((c), VADUSA_EHIP, "%s failed: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static int pad16(int n) { return (n + 15) / 16 * 16; }
+
+extern "C" int vadusa_config_check(const vadusa_config* c, char* msg, size_t n) {
+    if (!c) { set_msg(msg, n, "config is null"); return VADUSA_EINVAL; }
+#define BAD(code, ...) do { set_msg(msg, n, __VA_ARGS__); return code; } while (0)
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->d_ffn < 1 || c->speech_vocab < 1 ||
+        c->text_vocab < 1 || c->max_positions < 2 || c->max_batch < 1 || c->max_tree_nodes < 1)
+        BAD(VADUSA_EINVAL, "sizes must be positive");
+    if (c->reserved != 0) BAD(VADUSA_EINVAL, "reserved must be 0");
+    if (c->dtype != 0 && c->dtype != 1) BAD(VADUSA_EINVAL, "dtype must be 0 (fp32) or 1 (bf16)");
+    if (c->ignore_eos != 0 && c->ignore_eos != 1) BAD(VADUSA_EINVAL, "ignore_eos must be 0 or 1");
+    if (c->head_dim != 64) BAD(VADUSA_ESHAPE, "head_dim must be 64 (got %d)", c->head_dim);
+    if (c->d_model != c->n_heads * c->head_dim) BAD(VADUSA_ESHAPE, "d_model must equal n_heads * head_dim");
+    if (c->d_ffn % 64) BAD(VADUSA_ESHAPE, "d_ffn must be a multiple of 64");
+    if (c->n_draft_heads < 1 || c->n_draft_heads > VADUSA_MAX_DRAFT_HEADS)
+        BAD(VADUSA_ESHAPE, "n_draft_heads must be 1..%d", VADUSA_MAX_DRAFT_HEADS);
+    if (c->max_tree_nodes > VADUSA_MAX_TREE_NODES)
+        BAD(VADUSA_ESHAPE, "max_tree_nodes must be <= %d", VADUSA_MAX_TREE_NODES);
+    if (c->max_positions <= c->max_tree_nodes)
+        BAD(VADUSA_ESHAPE, "max_positions must exceed max_tree_nodes");
+    if ((int64_t)c->max_batch * c->max_tree_nodes > (1 << 20)) BAD(VADUSA_ESHAPE, "max_batch * max_tree_nodes too large");
+#undef BAD
+    return VADUSA_OK;
+}
+
+// Depth of every node, or an error.  Checks the ordering rules of vadusa.h.
+static int tree_depths(const vadusa_config* c, const vadusa_tree_spec* t, std::vector<int32_t>* depth,
+                       char* msg, size_t n) {
+#define BAD(...) do { set_msg(msg, n, __VA_ARGS__); return VADUSA_EINVAL; } while (0)
+    if (!t || !t->parent || !t->rank) BAD("tree or its arrays are null");
+    const int M = t->n_nodes;
+    if (M < 1 || M > c->max_tree_nodes) BAD("n_nodes %d outside 1..max_tree_nodes (%d)", M, c->max_tree_nodes);
+    if (t->parent[0] != -1) BAD("parent[0] must be -1");
+    depth->assign(M, 0);
+    std::vector<std::vector<int32_t>> path(M);
+    for (int i = 1; i < M; ++i) {
+        const int p = t->parent[i];
+        if (p < 0 || p >= i) BAD("parent[%d] = %d must be in [0, %d)", i, p, i);
+        (*depth)[i] = (*depth)[p] + 1;
+        if ((*depth)[i] > c->n_draft_heads) BAD("node %d is deeper than the number of draft heads", i);
+        if (t->rank[i] < 0 || t->rank[i] >= VADUSA_MAX_TOPK) BAD("rank[%d] = %d outside [0, %d)", i, t->rank[i], VADUSA_MAX_TOPK);
+        path[i] = path[p];
+        path[i].push_back(t->rank[i]);
+        // canonical order: (depth, rank path) strictly increasing; also rules out equal siblings
+        const bool deeper = (*depth)[i] > (*depth)[i - 1];
+        if (!deeper && !((*depth)[i] == (*depth)[i - 1] && path[i - 1] < path[i]))
+            BAD("node %d breaks the canonical (depth, rank path) order", i);
+    }
+#undef BAD
+    return VADUSA_OK;
+}
+
+extern "C" int vadusa_tree_check(const vadusa_config* c, const vadusa_tree_spec* t, char* msg, size_t n) {
+    int rc = vadusa_config_check(c, msg, n);
+    if (rc) return rc;
+    std::vector<int32_t> depth;
+    return tree_depths(c, t, &depth, msg, n);
+}
+
+// ---------------------------------------------------------------------------
+// Arena layout.  With base == nullptr only the total size is computed.
+// ---------------------------------------------------------------------------
+struct Carver {
+    char* base;
+    size_t off = 0;
+    void* take(size_t bytes) {
+        off = align_up(off, 256);
+        void* p = base ? base + off : nullptr;
+        off += bytes;
+        return p;
+    }
+};
+
+struct WeightSlot { void* dev; size_t rows, cols; bool is_matrix; };   // blob order
+
+static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vector<LayerW>* layers,
+                     std::vector<DraftW>* draft, std::vector<WeightSlot>* slots, size_t* staging_floats) {
+    Carver cv{base};
+    const size_t e = c.dtype ? 2 : 4;
+    const size_t d = c.d_model, F = c.d_ffn, V1 = c.speech_vocab + 1, Hh = c.n_draft_heads;
+    const size_t R = (size_t)c.max_batch * c.max_tree_nodes, B = c.max_batch, P = c.max_positions;
+    DevState st{};
+    std::vector<LayerW> lw(c.n_layers);
+    std::vector<DraftW> dw(Hh);
+    std::vector<WeightSlot> sl;
+    size_t biggest = std::max(R * std::max(d, V1), P * d);
+    auto mat = [&](const void** dst, size_t rows, size_t cols) {
+        *dst = cv.take((size_t)pad16((int)rows) * cols * e);
+        sl.push_back({(void*)*dst, rows, cols, true});
+        biggest = std::max(biggest, rows * cols);
+    };
+    auto vec = [&](const float** dst, size_t n) {
+        *dst = (const float*)cv.take(n * 4);
+        sl.push_back({(void*)*dst, 1, n, false});
+    };
+    mat(&st.E_text, c.text_vocab, d);
+    mat(&st.E_speech, V1, d);
+    mat(&st.P, P, d);
+    for (int l = 0; l < c.n_layers; ++l) {
+        LayerW& w = lw[l];
+        vec(&w.ln1_g, d); vec(&w.ln1_b, d);
+        mat(&w.Wqkv, 3 * d, d); vec(&w.bqkv, 3 * d);
+        mat(&w.Wo, d, d); vec(&w.bo, d);
+        vec(&w.ln2_g, d); vec(&w.ln2_b, d);
+        mat(&w.W1, F, d); vec(&w.b1, F);
+        mat(&w.W2, d, F); vec(&w.b2, d);
+    }
+    vec(&st.lnf_g, d); vec(&st.lnf_b, d);
+    mat(&st.W_out, V1, d);
+    for (size_t i = 0; i < Hh; ++i) {
+        mat(&dw[i].W1, d, d); vec(&dw[i].b1, d); mat(&dw[i].W2, V1, d);
+    }
+    const size_t kv = (size_t)c.n_layers * B * c.n_heads * P * 64 * e;
+    st.Kc = cv.take(kv);
+    st.Vc = cv.take(kv);
+    st.x = (float*)cv.take(R * d * 4);
+    st.xn = cv.take(R * d * e);
+    st.q = cv.take(R * d * e);
+    st.att = cv.take(R * d * e);
+    st.hid = cv.take(R * F * e);
+    st.hn = cv.take(R * d * e);
+    st.logits = (float*)cv.take(R * V1 * 4);
+    st.hbest = cv.take(B * d * e);
+    st.rdraft = cv.take(Hh * B * d * e);
+    st.zdraft = (float*)cv.take(Hh * B * V1 * 4);
+    auto ints = [&](size_t n) { return (int32_t*)cv.take(n * 4); };
+    st.L = ints(B); st.root = ints(B); st.finished = ints(B);
+    st.draft_topk = ints(B * Hh * VADUSA_MAX_TOPK);
+    st.tok = ints(R); st.n_rows = ints(B); st.edge_ok = ints(R);
+    st.path = ints(B * (VADUSA_MAX_DRAFT_HEADS + 2));
+    st.out_tok = ints(B * P); st.n_out = ints(B);
+    st.acc_tok = ints(B * (VADUSA_MAX_DRAFT_HEADS + 1)); st.acc_len = ints(B);
+    st.chunk_tok = ints(R);
+    st.override_topk = ints(B * Hh * VADUSA_MAX_TOPK);
+    for (int t = 0; t < 2; ++t) {
+        st.t_parent[t] = ints(VADUSA_MAX_TREE_NODES);
+        st.t_depth[t] = ints(VADUSA_MAX_TREE_NODES);
+        st.t_rank[t] = ints(VADUSA_MAX_TREE_NODES);
+        st.t_mask[t] = (uint32_t*)cv.take(VADUSA_MAX_TREE_NODES * MASK_WORDS * 4);
+    }
+    st.staging = (float*)cv.take(biggest * 4);
+    if (s) *s = st;
+    if (layers) *layers = lw;
+    if (draft) *draft = dw;
+    if (slots) *slots = sl;
+    if (staging_floats) *staging_floats = biggest;
+    return align_up(cv.off, 256);
+}
+
+extern "C" size_t vadusa_arena_bytes(const vadusa_config* c) {
+    if (vadusa_config_check(c, nullptr, 0)) return 0;
+    return layout(*c, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+}
+
+extern "C" size_t vadusa_blob_floats(const vadusa_config* c) {
+    if (vadusa_config_check(c, nullptr, 0)) return 0;
+    std::vector<WeightSlot> sl;
+    layout(*c, nullptr, nullptr, nullptr, nullptr, &sl, nullptr);
+    size_t n = 0;
+    for (auto& w : sl) n += w.rows * w.cols;
+    return n;
+}
+
+// ---------------------------------------------------------------------------
+// life cycle
+// ---------------------------------------------------------------------------
+static Dims make_dims(const vadusa_ctx* c, int B, int M) {
+    Dims D;
+    D.Ly = c->cfg.n_layers; D.d = c->cfg.d_model; D.nH = c->cfg.n_heads; D.F = c->cfg.d_ffn;
+    D.V1 = c->cfg.speech_vocab + 1; D.Hh = c->cfg.n_draft_heads; D.maxpos = c->cfg.max_positions;
+    D.Bmax = c->cfg.max_batch; D.Mmax = c->cfg.max_tree_nodes; D.B = B; D.M = M;
+    return D;
+}
+
+extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena_bytes, void* hip_stream,
+                             vadusa_ctx** out) {
+    if (!out) return VADUSA_EINVAL;
+    *out = nullptr;
+    char msg[256];
+    int rc = vadusa_config_check(cfg, msg, sizeof msg);
+    if (rc) return rc;
+    const size_t need = vadusa_arena_bytes(cfg);
+    if (!arena || arena_bytes < need || ((uintptr_t)arena & 255)) return VADUSA_EINVAL;
+    vadusa_ctx* c = new (std::nothrow) vadusa_ctx();
+    if (!c) return VADUSA_EINVAL;
+    c->cfg = *cfg;
+    c->stream = (hipStream_t)hip_stream;
+    c->arena = (char*)arena;
+    c->arena_bytes = arena_bytes;
+    c->elem = cfg->dtype ? 2 : 4;
+    c->state = 0;
+    c->batch = 0;
+    c->M = 0;
+    layout(*cfg, c->arena, &c->s, &c->layers, &c->draft, nullptr, &c->staging_floats);
+    c->L_ub.assign(cfg->max_batch, 0);
+    c->pending.assign(cfg->max_batch, 0);
+    // causal table for prefill chunks: row n sees rows 0..n; positions are consecutive
+    const int Mm = VADUSA_MAX_TREE_NODES;
+    std::vector<int32_t> par(Mm), dep(Mm), rk(Mm, 0);
+    std::vector<uint32_t> mask((size_t)Mm * MASK_WORDS, 0);
+    for (int n = 0; n < Mm; ++n) {
+        par[n] = n - 1; dep[n] = n;
+        for (int m = 0; m <= n; ++m) mask[(size_t)n * MASK_WORDS + (m >> 5)] |= 1u << (m & 31);
+    }
+    hipError_t e = hipMemcpy(c->s.t_parent[1], par.data(), Mm * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->s.t_depth[1], dep.data(), Mm * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->s.t_rank[1], rk.data(), Mm * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->s.t_mask[1], mask.data(), mask.size() * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { delete c; return VADUSA_EHIP; }
+    *out = c;
+    return VADUSA_OK;
+}
+
+extern "C" void vadusa_destroy(vadusa_ctx* c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->stream);
+    delete c;
+}
+
+extern "C" const char* vadusa_last_error(const vadusa_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+extern "C" int vadusa_load_weights(vadusa_ctx* c, const float* blob, size_t n_floats, int on_device) {
+    if (!c) return VADUSA_EINVAL;
+    if (!blob) return fail(c, VADUSA_EINVAL, "blob is null");
+    if (n_floats != vadusa_blob_floats(&c->cfg))
+        return fail(c, VADUSA_EINVAL, "blob has %zu floats, expected %zu", n_floats, vadusa_blob_floats(&c->cfg));
+    std::vector<WeightSlot> sl;
+    layout(c->cfg, c->arena, nullptr, nullptr, nullptr, &sl, nullptr);
+    size_t off = 0;
+    for (auto& w : sl) {
+        const size_t n = w.rows * w.cols;
+        void* dst = w.dev;
+        const float* src = blob + off;
+        if (!on_device) {
+            if (w.is_matrix) {
+                HIP_TRY(c, hipMemcpyAsync(c->s.staging, src, n * 4, hipMemcpyHostToDevice, c->stream));
+                src = c->s.staging;
+            } else {
+                HIP_TRY(c, hipMemcpyAsync(dst, src, n * 4, hipMemcpyHostToDevice, c->stream));
+            }
+        } else if (!w.is_matrix) {
+            HIP_TRY(c, hipMemcpyAsync(dst, src, n * 4, hipMemcpyDeviceToDevice, c->stream));
+        }
+        if (w.is_matrix) {
+            const size_t padded = (size_t)pad16((int)w.rows) * w.cols;
+            if (padded > n)
+                HIP_TRY(c, hipMemsetAsync((char*)dst + n * c->elem, 0, (padded - n) * c->elem, c->stream));
+            launch_convert(src, dst, n, c->cfg.dtype, c->stream);
+        }
+        off += n;
+    }
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipGetLastError());
+    c->state = 1;
+    return VADUSA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// forward of B x M rows through the decoder (Sec. 2.1 tree attention; the
+// prefill uses the same path with a causal chunk as the "tree")
+// ---------------------------------------------------------------------------
+static void forward(vadusa_ctx* c, const Dims& D, int table, int prefill_mode, bool want_logits) {
+    const int dt = c->cfg.dtype;
+    const DevState& s = c->s;
+    hipStream_t st = c->stream;
+    const int R = D.B * D.M;
+    const size_t kv_layer = (size_t)D.Bmax * D.nH * D.maxpos * 64 * c->elem;
+    launch_embed(D, s, dt, prefill_mode, table, st);
+    for (int l = 0; l < D.Ly; ++l) {
+        const LayerW& w = c->layers[l];
+        launch_layernorm(s.x, w.ln1_g, w.ln1_b, s.xn, R, D.d, dt, st);
+        GemmArgs a{};
+        a.X = s.xn; a.W = w.Wqkv; a.bias = w.bqkv; a.R = R; a.K = D.d; a.N = 3 * D.d; a.epi = EPI_QKV;
+        a.out = s.q; a.Kc = (char*)s.Kc + l * kv_layer; a.Vc = (char*)s.Vc + l * kv_layer;
+        a.L = s.L; a.M = D.M; a.nH = D.nH; a.maxpos = D.maxpos; a.d = D.d;
+        launch_gemm_simple(a, dt, st);
+        launch_attn_simple(D, s, l, table, dt, st);
+        GemmArgs o{};
+        o.X = s.att; o.W = w.Wo; o.bias = w.bo; o.R = R; o.K = D.d; o.N = D.d; o.epi = EPI_RESID; o.outf = s.x;
+        launch_gemm_simple(o, dt, st);
+        launch_layernorm(s.x, w.ln2_g, w.ln2_b, s.xn, R, D.d, dt, st);
+        GemmArgs f1{};
+        f1.X = s.xn; f1.W = w.W1; f1.bias = w.b1; f1.R = R; f1.K = D.d; f1.N = D.F; f1.epi = EPI_GELU; f1.out = s.hid;
+        launch_gemm_simple(f1, dt, st);
+        GemmArgs f2{};
+        f2.X = s.hid; f2.W = w.W2; f2.bias = w.b2; f2.R = R; f2.K = D.F; f2.N = D.d; f2.epi = EPI_RESID; f2.outf = s.x;
+        launch_gemm_simple(f2, dt, st);
+    }
+    if (want_logits) {
+        launch_layernorm(s.x, s.lnf_g, s.lnf_b, s.hn, R, D.d, dt, st);
+        GemmArgs h{};
+        h.X = s.hn; h.W = s.W_out; h.bias = nullptr; h.R = R; h.K = D.d; h.N = D.V1; h.epi = EPI_F32; h.outf = s.logits;
+        launch_gemm_simple(h, dt, st);
+    }
+}
+
+// Draft heads on the hidden state of the last accepted node (Sec. 2.1,
+// Sec. 3.1.1): z_i = W2_i (h + SiLU(W1_i h + b1_i)), then the top-k lists.
+static void draft_heads(vadusa_ctx* c, const Dims& D, int seq0, int nseq) {
+    const int dt = c->cfg.dtype;
+    const DevState& s = c->s;
+    for (int i = 0; i < D.Hh; ++i) {
+        char* r = (char*)s.rdraft + ((size_t)i * D.Bmax + seq0) * D.d * c->elem;
+        GemmArgs a{};
+        a.X = (char*)s.hbest + (size_t)seq0 * D.d * c->elem; a.W = c->draft[i].W1; a.bias = c->draft[i].b1;
+        a.R = nseq; a.K = D.d; a.N = D.d; a.epi = EPI_SILU_RESID; a.out = r;
+        launch_gemm_simple(a, dt, c->stream);
+        GemmArgs z{};
+        z.X = r; z.W = c->draft[i].W2; z.bias = nullptr; z.R = nseq; z.K = D.d; z.N = D.V1; z.epi = EPI_F32;
+        z.outf = s.zdraft + ((size_t)i * D.Bmax + seq0) * D.V1;
+        launch_gemm_simple(z, dt, c->stream);
+    }
+    launch_topk(D, s, seq0, nseq, c->stream);
+}
+
+// ---------------------------------------------------------------------------
+// prefill
+// ---------------------------------------------------------------------------
+extern "C" int vadusa_prefill(vadusa_ctx* c, int32_t batch, const int32_t* text_tok, const int32_t* text_len,
+                              const int32_t* prompt_tok, const int32_t* prompt_len, int32_t* first_root) {
+    if (!c) return VADUSA_EINVAL;
+    if (c->state < 1) return fail(c, VADUSA_ESTATE, "weights not loaded");
+    if (batch < 1 || batch > c->cfg.max_batch) return fail(c, VADUSA_EINVAL, "batch %d outside 1..%d", batch, c->cfg.max_batch);
+    if (!text_len || !prompt_len) return fail(c, VADUSA_EINVAL, "length arrays are null");
+    const int Mc = c->cfg.max_tree_nodes;
+    std::vector<std::vector<int32_t>> seqs(batch);
+    size_t to = 0, po = 0;
+    int max_chunks = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int tl = text_len[b], pl = prompt_len[b];
+        if (tl < 0 || pl < 0 || tl + pl < 1) return fail(c, VADUSA_EINVAL, "sequence %d is empty or has a negative length", b);
+        if ((tl && !text_tok) || (pl && !prompt_tok)) return fail(c, VADUSA_EINVAL, "token array is null");
+        if (tl + pl + Mc > c->cfg.max_positions)
+            return fail(c, VADUSA_EKVFULL, "sequence %d: %d tokens + %d tree rows exceed max_positions %d", b, tl + pl, Mc, c->cfg.max_positions);
+        for (int i = 0; i < tl; ++i) {
+            const int t = text_tok[to + i];
+            if (t < 0 || t >= c->cfg.text_vocab) return fail(c, VADUSA_EINVAL, "text token %d out of range", t);
+            seqs[b].push_back(-t - 1);
+        }
+        for (int i = 0; i < pl; ++i) {
+            const int t = prompt_tok[po + i];
+            if (t < 0 || t > c->cfg.speech_vocab) return fail(c, VADUSA_EINVAL, "speech token %d out of range", t);
+            seqs[b].push_back(t);
+        }
+        to += tl; po += pl;
+        max_chunks = std::max(max_chunks, (tl + pl + Mc - 1) / Mc);
+    }
+    const DevState& s = c->s;
+    const size_t B = batch;
+    // reset the decoding state
+    HIP_TRY(c, hipMemsetAsync(s.L, 0, B * 4, c->stream));
+    HIP_TRY(c, hipMemsetAsync(s.finished, 0, B * 4, c->stream));
+    HIP_TRY(c, hipMemsetAsync(s.n_out, 0, B * 4, c->stream));
+    HIP_TRY(c, hipMemsetAsync(s.path, 0, B * (VADUSA_MAX_DRAFT_HEADS + 2) * 4, c->stream));
+    const Dims D = make_dims(c, batch, Mc);
+    // chunks are right-aligned so that every sequence ends in the last chunk
+    std::vector<std::vector<int32_t>> keep;   // host buffers stay alive until the final sync
+    for (int ch = 0; ch < max_chunks; ++ch) {
+        keep.emplace_back((size_t)batch * Mc, 0);
+        keep.emplace_back(batch, 0);
+        std::vector<int32_t>& ctok = keep[keep.size() - 2];
+        std::vector<int32_t>& rows = keep[keep.size() - 1];
+        for (int b = 0; b < batch; ++b) {
+            const int total = (int)seqs[b].size();
+            const int nch = (total + Mc - 1) / Mc;
+            const int first = total - (nch - 1) * Mc;       // size of the sequence's first chunk
+            const int k = ch - (max_chunks - nch);           // chunk index within the sequence
+            if (k < 0) continue;
+            const int begin = k == 0 ? 0 : first + (k - 1) * Mc;
+            const int cnt = k == 0 ? first : Mc;
+            rows[b] = cnt;
+            for (int i = 0; i < cnt; ++i) ctok[(size_t)b * Mc + i] = seqs[b][begin + i];
+        }
+        HIP_TRY(c, hipMemcpyAsync(s.chunk_tok, ctok.data(), ctok.size() * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(s.n_rows, rows.data(), rows.size() * 4, hipMemcpyHostToDevice, c->stream));
+        const bool last = ch == max_chunks - 1;
+        forward(c, D, 1, 1, last);
+        if (!last) launch_advance(s, batch, c->stream);
+    }
+    launch_finalize(D, s, 0, batch, 1, c->cfg.ignore_eos, c->cfg.dtype, c->stream);
+    draft_heads(c, D, 0, batch);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipGetLastError());
+    if (first_root) HIP_TRY(c, hipMemcpy(first_root, s.root, B * 4, hipMemcpyDeviceToHost));
+    c->batch = batch;
+    c->state = 2;
+    for (int b = 0; b < batch; ++b) { c->L_ub[b] = (int)seqs[b].size(); c->pending[b] = 0; }
+    return VADUSA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// verification
+// ---------------------------------------------------------------------------
+static int upload_tree(vadusa_ctx* c, const vadusa_tree_spec* t, const std::vector<int32_t>& depth) {
+    const int M = t->n_nodes;
+    const bool same = (int)c->tree_parent.size() == M &&
+                      !memcmp(c->tree_parent.data(), t->parent, M * 4) &&
+                      !memcmp(c->tree_rank.data() + 1, t->rank + 1, (M - 1) * 4);
+    if (same) return VADUSA_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));   // earlier uploads from these vectors are done
+    c->tree_parent.assign(t->parent, t->parent + M);
+    c->tree_rank.assign(t->rank, t->rank + M);
+    c->tree_rank[0] = 0;
+    c->tree_depth = depth;
+    std::vector<uint32_t> mask((size_t)M * MASK_WORDS, 0);
+    for (int n = 0; n < M; ++n)
+        for (int m = n; m >= 0; m = t->parent[m]) mask[(size_t)n * MASK_WORDS + (m >> 5)] |= 1u << (m & 31);
+    const DevState& s = c->s;
+    HIP_TRY(c, hipMemcpy(s.t_parent[0], c->tree_parent.data(), M * 4, hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemcpy(s.t_depth[0], c->tree_depth.data(), M * 4, hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemcpy(s.t_rank[0], c->tree_rank.data(), M * 4, hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemcpy(s.t_mask[0], mask.data(), mask.size() * 4, hipMemcpyHostToDevice));
+    return VADUSA_OK;
+}
+
+extern "C" int vadusa_verify(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau, const int32_t* draft_override) {
+    if (!c) return VADUSA_EINVAL;
+    if (c->state != 2) return fail(c, VADUSA_ESTATE, c->state == 3 ? "a verification is still waiting for vadusa_kv_compact" : "prefill first");
+    if (tau < 1) return fail(c, VADUSA_EINVAL, "tau must be >= 1 (got %d)", tau);
+    char msg[256];
+    std::vector<int32_t> depth;
+    int rc = tree_depths(&c->cfg, tree, &depth, msg, sizeof msg);
+    if (rc) return fail(c, rc, "%s", msg);
+    const int M = tree->n_nodes, B = c->batch;
+    const DevState& s = c->s;
+    // capacity: rows L .. L+M-1 are written by this forward
+    bool maybe_full = false;
+    for (int b = 0; b < B; ++b) maybe_full |= c->L_ub[b] + M > c->cfg.max_positions;
+    if (maybe_full) {
+        std::vector<int32_t> L(B), fin(B);
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        HIP_TRY(c, hipMemcpy(L.data(), s.L, B * 4, hipMemcpyDeviceToHost));
+        HIP_TRY(c, hipMemcpy(fin.data(), s.finished, B * 4, hipMemcpyDeviceToHost));
+        for (int b = 0; b < B; ++b) {
+            c->L_ub[b] = L[b];
+            if (!fin[b] && L[b] + M > c->cfg.max_positions)
+                return fail(c, VADUSA_EKVFULL, "sequence %d: L = %d plus %d tree rows exceeds max_positions %d", b, L[b], M, c->cfg.max_positions);
+        }
+    }
+    rc = upload_tree(c, tree, depth);
+    if (rc) return rc;
+    if (draft_override) {
+        for (size_t i = 0; i < (size_t)B * c->cfg.n_draft_heads * VADUSA_MAX_TOPK; ++i)
+            if (draft_override[i] < 0 || draft_override[i] > c->cfg.speech_vocab)
+                return fail(c, VADUSA_EINVAL, "draft_override holds a token outside the vocabulary");
+        HIP_TRY(c, hipMemcpyAsync(s.draft_topk, draft_override, (size_t)B * c->cfg.n_draft_heads * VADUSA_MAX_TOPK * 4,
+                                  hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipStreamSynchronize(c->stream));   // the caller's buffer is not kept
+    }
+    const Dims D = make_dims(c, B, M);
+    forward(c, D, 0, 0, true);
+    launch_accept(D, s, tau, c->cfg.ignore_eos, c->stream);
+    HIP_TRY(c, hipGetLastError());
+    c->M = M;
+    c->state = 3;
+    for (int b = 0; b < B; ++b) c->pending[b] = 1;
+    return VADUSA_OK;
+}
+
+extern "C" int vadusa_kv_compact(vadusa_ctx* c, int32_t seq, const int32_t* path_nodes, int32_t n) {
+    if (!c) return VADUSA_EINVAL;
+    if (c->state != 3) return fail(c, VADUSA_ESTATE, "no verification is pending");
+    const int B = c->batch;
+    if (seq < -1 || seq >= B) return fail(c, VADUSA_EINVAL, "seq %d outside -1..%d", seq, B - 1);
+    if (seq == -1 && (path_nodes || n)) return fail(c, VADUSA_EINVAL, "seq = -1 takes no explicit path");
+    if ((path_nodes == nullptr) != (n == 0)) return fail(c, VADUSA_EINVAL, "path_nodes and n must both be given or both be empty");
+    const DevState& s = c->s;
+    const Dims D = make_dims(c, B, c->M);
+    int seq0 = 0, nseq = B;
+    if (seq >= 0) {
+        if (!c->pending[seq]) return fail(c, VADUSA_ESTATE, "sequence %d has no pending verification", seq);
+        seq0 = seq; nseq = 1;
+        if (path_nodes) {
+            if (n < 1 || n > c->cfg.n_draft_heads + 1) return fail(c, VADUSA_EINVAL, "path length %d outside 1..%d", n, c->cfg.n_draft_heads + 1);
+            if (path_nodes[0] != 0) return fail(c, VADUSA_EINVAL, "a path starts at node 0");
+            for (int j = 1; j < n; ++j)
+                if (path_nodes[j] < 1 || path_nodes[j] >= c->M || c->tree_parent[path_nodes[j]] != path_nodes[j - 1])
+                    return fail(c, VADUSA_EINVAL, "path_nodes[%d] is not a child of path_nodes[%d]", j, j - 1);
+            int32_t buf[VADUSA_MAX_DRAFT_HEADS + 2] = {0};
+            buf[0] = n;
+            memcpy(buf + 1, path_nodes, n * 4);
+            HIP_TRY(c, hipMemcpyAsync(s.path + (size_t)seq * (VADUSA_MAX_DRAFT_HEADS + 2), buf, sizeof buf,
+                                      hipMemcpyHostToDevice, c->stream));
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+        }
+    }
+    launch_commit_kv(D, s, seq0, nseq, c->cfg.dtype, c->stream);
+    launch_finalize(D, s, seq0, nseq, 0, c->cfg.ignore_eos, c->cfg.dtype, c->stream);
+    draft_heads(c, D, seq0, nseq);
+    HIP_TRY(c, hipGetLastError());
+    bool any = false;
+    for (int b = 0; b < B; ++b) {
+        if (b >= seq0 && b < seq0 + nseq && c->pending[b]) {
+            c->pending[b] = 0;
+            c->L_ub[b] += (path_nodes ? n : std::min(c->cfg.n_draft_heads + 1, c->M));
+        }
+        any |= c->pending[b] != 0;
+    }
+    if (!any) c->state = 2;
+    return VADUSA_OK;
+}
+
+extern "C" int vadusa_step(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau, const int32_t* draft_override,
+                           int32_t* accepted_tok, int32_t* accepted_len) {
+    if (!c) return VADUSA_EINVAL;
+    if ((accepted_tok == nullptr) != (accepted_len == nullptr))
+        return fail(c, VADUSA_EINVAL, "accepted_tok and accepted_len must both be given or both be null");
+    int rc = vadusa_verify(c, tree, tau, draft_override);
+    if (rc) return rc;
+    rc = vadusa_kv_compact(c, -1, nullptr, 0);
+    if (rc) return rc;
+    if (accepted_tok) {
+        const int B = c->batch, W = VADUSA_MAX_DRAFT_HEADS + 1, Hh1 = c->cfg.n_draft_heads + 1;
+        std::vector<int32_t> tok((size_t)B * W), len(B), L(B);
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        HIP_TRY(c, hipMemcpy(tok.data(), c->s.acc_tok, tok.size() * 4, hipMemcpyDeviceToHost));
+        HIP_TRY(c, hipMemcpy(len.data(), c->s.acc_len, B * 4, hipMemcpyDeviceToHost));
+        HIP_TRY(c, hipMemcpy(L.data(), c->s.L, B * 4, hipMemcpyDeviceToHost));
+        for (int b = 0; b < B; ++b) {
+            accepted_len[b] = len[b];
+            for (int j = 0; j < Hh1; ++j) accepted_tok[(size_t)b * Hh1 + j] = j < len[b] ? tok[(size_t)b * W + j] : -1;
+            c->L_ub[b] = L[b];
+        }
+    }
+    return VADUSA_OK;
+}
+
+extern "C" int vadusa_read_output(vadusa_ctx* c, int32_t seq, int32_t* tok, int32_t capacity, int32_t* n_out) {
+    if (!c) return VADUSA_EINVAL;
+    if (c->state < 2) return fail(c, VADUSA_ESTATE, "prefill first");
+    if (seq < 0 || seq >= c->batch || !n_out) return fail(c, VADUSA_EINVAL, "bad seq or null n_out");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    int32_t n = 0;
+    HIP_TRY(c, hipMemcpy(&n, c->s.n_out + seq, 4, hipMemcpyDeviceToHost));
+    *n_out = n;
+    if (tok) {
+        const int m = std::min(n, capacity);
+        if (m > 0) HIP_TRY(c, hipMemcpy(tok, c->s.out_tok + (size_t)seq * c->cfg.max_positions, (size_t)m * 4, hipMemcpyDeviceToHost));
+    }
+    return VADUSA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// inspection
+// ---------------------------------------------------------------------------
+extern "C" int vadusa_debug_read(vadusa_ctx* c, int32_t what, void* host, size_t bytes) {
+    if (!c || !host) return VADUSA_EINVAL;
+    if (c->state < 2) return fail(c, VADUSA_ESTATE, "prefill first");
+    const DevState& s = c->s;
+    const size_t B = c->batch, M = c->M, d = c->cfg.d_model, V1 = c->cfg.speech_vocab + 1, Hh = c->cfg.n_draft_heads;
+    const size_t Bmax = c->cfg.max_batch;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const void* src = nullptr;
+    size_t need = 0;
+    switch (what) {
+    case VADUSA_DBG_LOGITS: src = s.logits; need = B * M * V1 * 4; break;
+    case VADUSA_DBG_TREE_TOK: src = s.tok; need = B * M * 4; break;
+    case VADUSA_DBG_DRAFT_TOPK: src = s.draft_topk; need = B * Hh * VADUSA_MAX_TOPK * 4; break;
+    case VADUSA_DBG_KV_LEN: src = s.L; need = B * 4; break;
+    case VADUSA_DBG_ROOT: src = s.root; need = B * 4; break;
+    case VADUSA_DBG_EDGE_OK: src = s.edge_ok; need = B * M * 4; break;
+    case VADUSA_DBG_FINISHED: src = s.finished; need = B * 4; break;
+    case VADUSA_DBG_H_NODES: {
+        need = B * M * d * 4;
+        if (bytes != need) return fail(c, VADUSA_EINVAL, "expected %zu bytes", need);
+        launch_to_float(s.hn, s.staging, B * M * d, c->cfg.dtype, c->stream);
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        HIP_TRY(c, hipMemcpy(host, s.staging, need, hipMemcpyDeviceToHost));
+        return VADUSA_OK;
+    }
+    case VADUSA_DBG_PATH: {
+        need = B * (Hh + 2) * 4;
+        if (bytes != need) return fail(c, VADUSA_EINVAL, "expected %zu bytes", need);
+        std::vector<int32_t> tmp(B * (VADUSA_MAX_DRAFT_HEADS + 2));
+        HIP_TRY(c, hipMemcpy(tmp.data(), s.path, tmp.size() * 4, hipMemcpyDeviceToHost));
+        int32_t* o = (int32_t*)host;
+        for (size_t b = 0; b < B; ++b)
+            for (size_t j = 0; j < Hh + 2; ++j) o[b * (Hh + 2) + j] = tmp[b * (VADUSA_MAX_DRAFT_HEADS + 2) + j];
+        return VADUSA_OK;
+    }
+    case VADUSA_DBG_DRAFT_LOGITS: {
+        need = B * Hh * V1 * 4;
+        if (bytes != need) return fail(c, VADUSA_EINVAL, "expected %zu bytes", need);
+        float* o = (float*)host;
+        for (size_t b = 0; b < B; ++b)
+            for (size_t i = 0; i < Hh; ++i)
+                HIP_TRY(c, hipMemcpy(o + (b * Hh + i) * V1, s.zdraft + (i * Bmax + b) * V1, V1 * 4, hipMemcpyDeviceToHost));
+        return VADUSA_OK;
+    }
+    default: return fail(c, VADUSA_EINVAL, "unknown item %d", what);
+    }
+    if (bytes != need) return fail(c, VADUSA_EINVAL, "expected %zu bytes, got %zu", need, bytes);
+    if (need) HIP_TRY(c, hipMemcpy(host, src, need, hipMemcpyDeviceToHost));
+    return VADUSA_OK;
+}
+
+extern "C" int vadusa_debug_read_kv(vadusa_ctx* c, int32_t layer, int32_t seq, int32_t which, int32_t pos0,
+                                    int32_t npos, float* host) {
+    if (!c || !host) return VADUSA_EINVAL;
+    if (c->state < 2) return fail(c, VADUSA_ESTATE, "prefill first");
+    if (layer < 0 || layer >= c->cfg.n_layers || seq < 0 || seq >= c->cfg.max_batch || (which != 0 && which != 1) ||
+        pos0 < 0 || npos < 1 || pos0 + npos > c->cfg.max_positions)
+        return fail(c, VADUSA_EINVAL, "bad layer / seq / range");
+    const Dims D = make_dims(c, c->batch, c->M);
+    const size_t kv_layer = (size_t)D.Bmax * D.nH * D.maxpos * 64 * c->elem;
+    const char* base = (const char*)(which ? c->s.Vc : c->s.Kc) + layer * kv_layer;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    launch_read_kv(D, base, seq, pos0, npos, c->s.staging, c->cfg.dtype, c->stream);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(host, c->s.staging, (size_t)npos * D.d * 4, hipMemcpyDeviceToHost));
+    return VADUSA_OK;
+}

@@ -1,0 +1,144 @@
+// Internal declarations shared by the HIP translation units of libvadusa.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "vadusa.h"
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+#define MASK_WORDS (VADUSA_MAX_TREE_NODES / 32)
+#define LN_EPS 1e-5f
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);   // round to nearest, ties to even
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float ldf(const float* p) { return *p; }
+__device__ __forceinline__ float ldf(const bf16_t* p) { return bf2f(*p); }
+__device__ __forceinline__ void stf(float* p, float v) { *p = v; }
+__device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f2bf(v); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// Shapes that every kernel needs (passed by value).
+struct Dims {
+    int Ly, d, nH, F, V1, Hh, maxpos, Bmax, Mmax;   // model / capacity
+    int B, M;                                        // current batch, rows per sequence
+};
+
+// Pointers to one layer's parameters on the device.
+struct LayerW {
+    const float *ln1_g, *ln1_b, *bqkv, *bo, *ln2_g, *ln2_b, *b1, *b2;
+    const void *Wqkv, *Wo, *W1, *W2;   // element type follows the context dtype
+};
+struct DraftW {
+    const void* W1; const float* b1; const void* W2;
+};
+
+// Decoding state and scratch on the device (all inside the caller's arena).
+struct DevState {
+    // model
+    const void *E_text, *E_speech, *P;
+    const float *lnf_g, *lnf_b;
+    const void* W_out;
+    // KV cache, element type = dtype: [Ly][Bmax][nH][maxpos][64]
+    void *Kc, *Vc;
+    // activations
+    float* x;        // [R][d]  residual stream
+    void* xn;        // [R][d]  LayerNorm output
+    void* q;         // [R][d]
+    void* att;       // [R][d]
+    void* hid;       // [R][F]
+    void* hn;        // [R][d]  final-LayerNorm'd node states
+    float* logits;   // [R][V1]
+    void* hbest;     // [Bmax][d]
+    void* rdraft;    // [Hh][Bmax][d]
+    float* zdraft;   // [Bmax][Hh][V1]
+    // integer state
+    int32_t *L, *root, *finished, *draft_topk /*[Bmax][Hh][MAX_TOPK]*/;
+    int32_t *tok /*[R]*/, *n_rows /*[Bmax]*/, *edge_ok /*[R]*/, *path /*[Bmax][MAX_DRAFT_HEADS+2]*/;
+    int32_t *out_tok /*[Bmax][maxpos]*/, *n_out /*[Bmax]*/;
+    int32_t *acc_tok /*[Bmax][MAX_DRAFT_HEADS+1]*/, *acc_len /*[Bmax]*/;
+    int32_t *chunk_tok /*[R]*/, *override_topk /*[Bmax][Hh][MAX_TOPK]*/;
+    // tree tables (index 0: current tree, 1: causal chunk used by prefill)
+    int32_t *t_parent[2], *t_depth[2], *t_rank[2];
+    uint32_t* t_mask[2];   // [Mmax][MASK_WORDS]
+    float* staging;        // weight conversion staging
+};
+
+struct vadusa_ctx {
+    vadusa_config cfg;
+    hipStream_t stream;
+    char* arena;
+    size_t arena_bytes;
+    DevState s;
+    std::vector<LayerW> layers;
+    std::vector<DraftW> draft;
+    size_t elem;                 // bytes per stored element (4 or 2)
+    int state;                   // 0 created, 1 weights loaded, 2 ready, 3 verification pending
+    int batch;                   // current batch
+    int M;                       // nodes of the pending / last verification
+    std::vector<int32_t> L_ub;   // host upper bound of each sequence's committed length
+    std::vector<char> pending;   // per sequence: verification waits for compaction
+    std::vector<int32_t> tree_parent, tree_rank, tree_depth;   // last uploaded tree
+    size_t staging_floats;
+    std::string err;
+};
+
+// Epilogues of the linear-map kernels.
+enum {
+    EPI_STORE = 0,      // out[r][n] = acc + bias              (stored in the context dtype)
+    EPI_GELU = 1,       // out[r][n] = gelu(acc + bias)
+    EPI_RESID = 2,      // x[r][n] += acc + bias               (fp32 residual stream)
+    EPI_F32 = 3,        // outf[r][n] = acc (+ bias if given)
+    EPI_SILU_RESID = 4, // out[r][n] = in[r][n] + silu(acc + bias)   (needs N == K)
+    EPI_QKV = 5         // n < d: q[r][n]; else key / value rows of the KV cache at L[b] + node
+};
+
+struct GemmArgs {
+    const void* X;      // [R][K] context dtype
+    const void* W;      // [N][K] context dtype (layout depends on the kernel)
+    const float* bias;  // [N] or null
+    int R, K, N;
+    int epi;
+    void* out;          // context dtype, [R][N]
+    float* outf;        // fp32 target (EPI_RESID: x, EPI_F32: logits)
+    // EPI_QKV
+    void *Kc, *Vc;      // layer base of the cache
+    const int32_t* L;
+    int M, nH, maxpos, d;
+};
+
+// ---- launch wrappers (each enqueues on `st`, no synchronisation) ----
+void launch_embed(const Dims& D, const DevState& s, int dtype, int prefill_mode, int table, hipStream_t st);
+void launch_layernorm(const float* x, const float* g, const float* b, void* out, int R, int d, int dtype, hipStream_t st);
+void launch_gemm_simple(const GemmArgs& a, int dtype, hipStream_t st);
+void launch_attn_simple(const Dims& D, const DevState& s, int layer, int table, int dtype, hipStream_t st);
+void launch_accept(const Dims& D, const DevState& s, int tau, int ignore_eos, hipStream_t st);
+void launch_commit_kv(const Dims& D, const DevState& s, int seq0, int nseq, int dtype, hipStream_t st);
+void launch_finalize(const Dims& D, const DevState& s, int seq0, int nseq, int prefill_mode, int ignore_eos, int dtype, hipStream_t st);
+void launch_topk(const Dims& D, const DevState& s, int seq0, int nseq, hipStream_t st);
+void launch_convert(const float* src, void* dst, size_t n, int dtype, hipStream_t st);
+void launch_advance(const DevState& s, int B, hipStream_t st);
+void launch_read_kv(const Dims& D, const void* cache_layer, int seq, int pos0, int npos, float* out, int dtype, hipStream_t st);
+void launch_to_float(const void* src, float* dst, size_t n, int dtype, hipStream_t st);

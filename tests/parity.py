@@ -1,0 +1,205 @@
+"""Lockstep comparison of the HIP library with the CPU oracle.
+
+Protocol (per step, both sides on identical state):
+  * roots and the draft lists' used entries must agree; logits of every tree
+    node must agree within the relative-L2 tolerance; edge decisions, the chosen
+    path and the committed state must agree;
+  * a differing *decision* is tolerated only when the oracle's own margin for
+    that decision (gap between the two logits that decide it) is <= MARGIN; it is
+    then counted as a tie divergence and the library is re-synchronised to the
+    oracle (draft_override for lists, a forced path through vadusa_kv_compact, or
+    a fresh prefill of the oracle's sequence for a differing root);
+  * any decision mismatch with a larger margin, and any logits error above the
+    tolerance, fails.
+"""
+from dataclasses import dataclass, field
+
+import numpy as np
+
+from oracle import vadusa_oracle as O
+from paper_2410_21951_amd import Vadusa, TreeArrays, DBG
+
+MARGIN = 1e-2
+TOL = {"fp32": 1e-4, "bf16": 1e-2}
+
+
+def rel_l2(a, b):
+    return float(np.linalg.norm(np.asarray(a, np.float64) - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def top_gap(z, k=1):
+    """Smallest gap between consecutive entries among the k+1 largest logits."""
+    s = np.sort(np.asarray(z))[::-1][:k + 1]
+    return float(np.min(s[:-1] - s[1:])) if len(s) > 1 else np.inf
+
+
+def edge_margin(z, t, tau):
+    """Distance of the accept/reject decision for token t under tolerance tau from flipping."""
+    s = np.sort(z)[::-1]
+    rank = int((z > z[t]).sum() + (z[:t] == z[t]).sum())
+    if rank < tau:
+        return float(z[t] - s[tau]) if tau < len(s) else np.inf
+    return float(s[tau - 1] - z[t])
+
+
+@dataclass
+class Stats:
+    steps: int = 0
+    compared: int = 0
+    tie_root: int = 0
+    tie_list: int = 0
+    tie_edge: int = 0
+    max_logit_err: float = 0.0
+    max_h_err: float = 0.0
+    max_kv_err: float = 0.0
+    accepted_hist: list = field(default_factory=list)
+
+
+class Lockstep:
+    def __init__(self, cfg, weights, text, prompt, max_tree_nodes, ignore_eos=True):
+        self.cfg = cfg
+        self.model = O.Model(cfg, weights)
+        self.text, self.prompt = text, prompt
+        self.B = len(text)
+        self.ignore_eos = ignore_eos
+        self.tol = TOL[cfg.dtype]
+        self.dev = Vadusa(cfg, max_batch=self.B, max_tree_nodes=max_tree_nodes, ignore_eos=ignore_eos)
+        self.dev.load_weights(weights)
+        self.stats = Stats()
+        self.sts = [O.prefill(self.model, t, p) for t, p in zip(text, prompt)]
+        self.out_base = [0] * self.B
+        self.dev.prefill(text, prompt)
+        self.check_prefill()
+
+    # -- comparisons --------------------------------------------------------
+    def check_prefill(self):
+        L = self.dev.debug(DBG.KV_LEN)
+        for b, st in enumerate(self.sts):
+            assert L[b] == st.L
+        zd = self.dev.debug(DBG.DRAFT_LOGITS)
+        for b, st in enumerate(self.sts):
+            for i, z in enumerate(st.draft_logits):
+                e = rel_l2(zd[b, i], z)
+                assert e < self.tol, f"prefill draft logits seq {b} head {i}: rel-L2 {e}"
+        self.check_kv(layers=[0, self.cfg.n_layers - 1])
+
+    def check_kv(self, layers, seqs=None):
+        for b in (range(self.B) if seqs is None else seqs):
+            st = self.sts[b]
+            for l in layers:
+                for which, ref in ((0, st.K), (1, st.V)):
+                    got = self.dev.read_kv(l, b, which, 0, st.L)
+                    e = rel_l2(got, ref[l, :st.L])
+                    self.stats.max_kv_err = max(self.stats.max_kv_err, e)
+                    assert e < self.tol, f"KV layer {l} seq {b} which {which}: rel-L2 {e}"
+
+    def resync(self):
+        """Fresh prefill of the library with what the oracle has emitted so far."""
+        prompts = [np.concatenate([p, np.asarray(st.emitted, np.int64)]).astype(np.int32)
+                   for p, st in zip(self.prompt, self.sts)]
+        assert not any(st.finished for st in self.sts), "resync of a finished sequence is not supported"
+        self.dev.prefill(self.text, prompts)
+        self.out_base = [len(st.emitted) for st in self.sts]
+
+    def step(self, tree, tau, override=None):
+        """One lockstep step.  override: per-sequence per-head candidate lists (or None)."""
+        cfg, dev, S = self.cfg, self.dev, self.stats
+        tarr = TreeArrays(tree.parent, tree.rank)
+        need = tree.topk_needed(cfg.n_draft_heads)
+        S.steps += 1
+        # (a) roots and lists
+        roots = dev.debug(DBG.ROOT)
+        lists = dev.debug(DBG.DRAFT_TOPK)
+        fin = dev.debug(DBG.FINISHED)
+        o_lists = []
+        root_diverged = False
+        use_override = override is not None
+        for b, st in enumerate(self.sts):
+            assert bool(fin[b]) == st.finished
+            ol = O.draft_lists(self.model, st, tree) if override is None else \
+                [np.asarray(a, np.int64) for a in override[b]]
+            o_lists.append(ol)
+            if st.finished:
+                continue
+            if roots[b] != st.root:
+                # the root came from the previous last-accepted row: margin on that row
+                gap = top_gap(st.root_logits)
+                assert gap <= MARGIN, f"root mismatch seq {b}: {roots[b]} vs {st.root}, gap {gap}"
+                S.tie_root += 1
+                root_diverged = True
+            if override is None:
+                for i, k in enumerate(need):
+                    if k and lists[b, i, :k].tolist() != ol[i].tolist():
+                        gap = top_gap(st.draft_logits[i], k)
+                        assert gap <= MARGIN, f"draft list mismatch seq {b} head {i}, gap {gap}"
+                        S.tie_list += 1
+                        use_override = True
+        if root_diverged:
+            self.resync()
+            roots = dev.debug(DBG.ROOT)
+            if any(roots[b] != st.root for b, st in enumerate(self.sts)):
+                # same tie again: this step cannot be compared; advance the oracle and resync after
+                self._oracle_only(tree, tau, o_lists if override is not None else None)
+                self.resync()
+                return None
+            use_override = True
+        # (b) verification
+        dev.verify(tarr, tau, override=o_lists if use_override else None)
+        tok = dev.debug(DBG.TREE_TOK)
+        logits = dev.debug(DBG.LOGITS)
+        h = dev.debug(DBG.H_NODES)
+        edge = dev.debug(DBG.EDGE_OK)
+        path = dev.debug(DBG.PATH)
+        results = []
+        forced = {}
+        for b, st in enumerate(self.sts):
+            if st.finished:
+                assert path[b, 0] == 0
+                results.append(O.step(self.model, st, tree, tau))
+                continue
+            r = O.step(self.model, st, tree, tau, draft_override=o_lists[b], ignore_eos=self.ignore_eos)
+            results.append(r)
+            assert tok[b].tolist() == r["tok"].tolist(), f"tree tokens differ seq {b}"
+            for n in range(tree.n_nodes):
+                e = rel_l2(logits[b, n], r["logits"][n])
+                S.max_logit_err = max(S.max_logit_err, e)
+                assert e < self.tol, f"logits seq {b} node {n}: rel-L2 {e}"
+            S.max_h_err = max(S.max_h_err, rel_l2(h[b], r["h"]))
+            # edges
+            flipped = False
+            for n in range(1, tree.n_nodes):
+                z = r["logits"][tree.parent[n]]
+                t = int(r["tok"][n])
+                want = int((z > z[t]).sum() + (z[:t] == z[t]).sum()) < tau
+                if bool(edge[b, n]) != want:
+                    mg = edge_margin(z, t, tau)
+                    assert mg <= MARGIN, f"edge decision differs seq {b} node {n}, margin {mg}"
+                    S.tie_edge += 1
+                    flipped = True
+            got_path = path[b, 1:1 + path[b, 0]].tolist()
+            if not flipped:
+                assert got_path == r["path"], f"path differs seq {b}: {got_path} vs {r['path']}"
+            elif got_path != r["path"]:
+                forced[b] = r["path"]
+            S.accepted_hist.append(len(r["path"]))
+        # (c) compaction (forced to the oracle's path where a tie flipped an edge)
+        if forced:
+            for b in range(self.B):
+                if b in forced:
+                    dev.kv_compact(b, forced[b])
+                else:
+                    dev.kv_compact(b)
+        else:
+            dev.kv_compact(-1)
+        L = dev.debug(DBG.KV_LEN)
+        for b, st in enumerate(self.sts):
+            assert L[b] == st.L, f"L differs seq {b}: {L[b]} vs {st.L}"
+            out = dev.read_output(b)
+            assert out.tolist() == st.emitted[self.out_base[b]:], f"output differs seq {b}"
+        S.compared += 1
+        return results
+
+    def _oracle_only(self, tree, tau, o_lists):
+        for b, st in enumerate(self.sts):
+            O.step(self.model, st, tree, tau, draft_override=None if o_lists is None else o_lists[b],
+                   ignore_eos=self.ignore_eos)

@@ -1,0 +1,88 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and its host-only helpers validate configurations and trees."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2410_21951_amd import vadusa as V
+from synth import PRESETS, make_tree, chain_tree, full_tree
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return V.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "vadusa.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(vadusa_[a-z_]+)\s*\(", hdr))
+    assert declared == set(V.EXPORTS), declared ^ set(V.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def _cfg(model, **kw):
+    c = V.make_config(model, kw.pop("max_batch", 1), kw.pop("max_tree_nodes", 64))
+    for k, v in kw.items():
+        setattr(c, k, v)
+    return c
+
+
+def test_config_check_and_sizes(lib):
+    for wl in PRESETS.values():
+        c = _cfg(wl.model, max_batch=wl.batch, max_tree_nodes=wl.tree_nodes)
+        msg = C.create_string_buffer(256)
+        assert lib.vadusa_config_check(C.byref(c), msg, 256) == 0, msg.value
+        m = wl.model
+        d, F, V1 = m.d_model, m.d_ffn, m.n_logits
+        per_layer = 4 * d + 3 * d * d + 3 * d + d * d + d + F * d + F + d * F + d
+        want = (m.text_vocab + V1 + m.max_positions) * d + m.n_layers * per_layer + 2 * d + V1 * d \
+            + m.n_draft_heads * (d * d + d + V1 * d)
+        assert lib.vadusa_blob_floats(C.byref(c)) == want
+        kv = 2 * m.n_layers * wl.batch * m.max_positions * d * (2 if m.dtype == "bf16" else 4)
+        assert lib.vadusa_arena_bytes(C.byref(c)) > kv
+    m = PRESETS["tiny"].model
+    msg = C.create_string_buffer(256)
+    assert lib.vadusa_config_check(C.byref(_cfg(m, head_dim=32)), msg, 256) == -2 and b"head_dim" in msg.value
+    assert lib.vadusa_config_check(C.byref(_cfg(m, dtype=2)), msg, 256) == -1
+    assert lib.vadusa_config_check(C.byref(_cfg(m, n_draft_heads=9)), msg, 256) == -2
+    assert lib.vadusa_config_check(C.byref(_cfg(m, max_tree_nodes=129)), msg, 256) == -2
+    assert lib.vadusa_config_check(C.byref(_cfg(m, reserved=1)), msg, 256) == -1
+    assert lib.vadusa_config_check(None, msg, 256) == -1
+    assert lib.vadusa_arena_bytes(C.byref(_cfg(m, head_dim=32))) == 0
+
+
+def _check(lib, cfg, parent, rank):
+    t = V.TreeArrays(parent, rank)
+    msg = C.create_string_buffer(256)
+    return lib.vadusa_tree_check(C.byref(cfg), C.byref(t.c), msg, 256), msg.value.decode()
+
+
+def test_tree_check(lib):
+    cfg = _cfg(PRESETS["valle_b1"].model, max_tree_nodes=128)
+    for tree in (make_tree(64, (10,) * 4), make_tree(128, (10,) * 4), chain_tree(5), chain_tree(1),
+                 full_tree((3, 2, 2))):
+        rc, msg = _check(lib, cfg, tree.parent, tree.rank)
+        assert rc == 0, msg
+    assert _check(lib, cfg, [0, 0], [0, 0])[0] == -1                 # parent[0] must be -1
+    assert _check(lib, cfg, [-1, 1], [0, 0])[0] == -1                # parent must precede
+    assert _check(lib, cfg, [-1, 0, 0], [0, 1, 0])[0] == -1          # siblings out of order
+    assert _check(lib, cfg, [-1, 0, 0], [0, 1, 1])[0] == -1          # equal siblings
+    assert _check(lib, cfg, [-1, 0, 1, 0], [0, 0, 0, 1])[0] == -1    # depth order broken
+    assert _check(lib, cfg, [-1, 0], [0, 16])[0] == -1               # rank too large
+    rc, msg = _check(lib, cfg, chain_tree(6).parent, chain_tree(6).rank)
+    assert rc == -1 and "deeper" in msg                              # 5 levels, 4 heads
+    small = _cfg(PRESETS["valle_b1"].model, max_tree_nodes=32)
+    assert _check(lib, small, make_tree(64, (10,) * 4).parent, make_tree(64, (10,) * 4).rank)[0] == -1
+
+
+def test_blob_order_matches_generator():
+    from synth import weight_names
+    for wl in (PRESETS["tiny"], PRESETS["longform_b1"]):
+        assert [n for n, _, _ in weight_names(wl.model)] == V.blob_order(wl.model)

@@ -1,0 +1,125 @@
+"""GPU tests of the C ABI's behaviour: call order, error codes, the one-call step
+against verify + compact, asynchronous stepping, run-to-run reproducibility."""
+import numpy as np
+import pytest
+
+from synth import ModelConfig, make_weights, make_tree, chain_tree
+
+pytestmark = pytest.mark.gpu
+
+CFG = ModelConfig(n_layers=2, d_model=128, n_heads=2, head_dim=64, d_ffn=512, speech_vocab=300,
+                  text_vocab=50, n_draft_heads=3, max_positions=160, dtype="bf16")
+
+
+def _dev(cfg=CFG, **kw):
+    from paper_2410_21951_amd import Vadusa
+    return Vadusa(cfg, **kw)
+
+
+def _tree(t):
+    from paper_2410_21951_amd import TreeArrays
+    return TreeArrays(t.parent, t.rank)
+
+
+def _inputs(rng, B=2):
+    text = [rng.integers(0, CFG.text_vocab, 5 + b).astype(np.int32) for b in range(B)]
+    prompt = [rng.integers(0, CFG.speech_vocab, 20 + 3 * b).astype(np.int32) for b in range(B)]
+    return text, prompt
+
+
+def test_call_order_and_argument_errors():
+    from paper_2410_21951_amd import VadusaError
+    print("api errors", flush=True)
+    W = make_weights(CFG, 3)
+    rng = np.random.default_rng(0)
+    text, prompt = _inputs(rng)
+    dev = _dev(max_batch=2, max_tree_nodes=16)
+    tree = _tree(make_tree(16, (4, 2, 2)))
+    with pytest.raises(VadusaError) as e:
+        dev.prefill(text, prompt)                       # weights not loaded
+    assert e.value.code == -4
+    dev.load_weights(W)
+    dev.batch = 2
+    with pytest.raises(VadusaError) as e:
+        dev.step(tree, 1)                               # step before prefill
+    assert e.value.code == -4
+    dev.prefill(text, prompt)
+    with pytest.raises(VadusaError) as e:
+        dev.step(tree, 0)                               # tau < 1
+    assert e.value.code == -1
+    with pytest.raises(VadusaError) as e:
+        dev.step(_tree(make_tree(17, (4, 2, 2))), 1)    # more nodes than max_tree_nodes
+    assert e.value.code == -1
+    with pytest.raises(VadusaError) as e:
+        dev.kv_compact(-1)                              # nothing pending
+    assert e.value.code == -4
+    with pytest.raises(VadusaError) as e:
+        dev.prefill([np.array([999], np.int32)] * 2, prompt)   # token outside the vocabulary
+    assert e.value.code == -1
+    with pytest.raises(VadusaError) as e:
+        dev.prefill(text, [np.zeros(150, np.int32)] * 2)       # no room for the tree rows
+    assert e.value.code == -3
+    # state survived the failed calls
+    out = dev.step(tree, 1)
+    assert all(len(o) >= 1 for o in out)
+    dev.verify(tree, 1)
+    with pytest.raises(VadusaError) as e:
+        dev.verify(tree, 1)                             # compaction still pending
+    assert e.value.code == -4
+    with pytest.raises(VadusaError) as e:
+        dev.kv_compact(0, [0, 5])                       # node 5 is not a child of the root
+    assert e.value.code == -1
+    dev.kv_compact(0, [0, 1])
+    with pytest.raises(VadusaError) as e:
+        dev.kv_compact(0)                               # sequence 0 already compacted
+    assert e.value.code == -4
+    dev.kv_compact(1)
+    dev.step(tree, 2)
+
+
+def test_kv_full_is_reported_not_overrun():
+    from paper_2410_21951_amd import VadusaError
+    print("kv full", flush=True)
+    W = make_weights(CFG, 3)
+    rng = np.random.default_rng(1)
+    dev = _dev(max_batch=1, max_tree_nodes=16, ignore_eos=True)
+    dev.load_weights(W)
+    dev.prefill([np.zeros(4, np.int32)], [rng.integers(0, 300, 130).astype(np.int32)])
+    tree = _tree(chain_tree(4))
+    n = 0
+    with pytest.raises(VadusaError) as e:
+        for _ in range(40):
+            n += len(dev.step(tree, 301)[0])            # accepts 4 tokens per step
+    assert e.value.code == -3
+    assert 134 + n + 4 > 160 and 134 + n <= 160
+    assert len(dev.read_output(0)) == n
+
+
+def test_step_equals_verify_plus_compact_and_async_and_reproducible():
+    from paper_2410_21951_amd import DBG
+    print("step paths", flush=True)
+    W = make_weights(CFG, 4, std=0.08)
+    rng = np.random.default_rng(2)
+    text, prompt = _inputs(rng)
+    tree = _tree(make_tree(16, (4, 2, 2)))
+    outs, logits = [], []
+    for mode in ("sync", "split", "async", "sync"):
+        dev = _dev(max_batch=2, max_tree_nodes=16, ignore_eos=True)
+        dev.load_weights(W)
+        dev.prefill(text, prompt)
+        for i in range(12):
+            tau = 1 + i % 3
+            if mode == "sync":
+                dev.step(tree, tau)
+            elif mode == "async":
+                dev.step(tree, tau, sync=False)
+            else:
+                dev.verify(tree, tau)
+                dev.kv_compact(-1)
+        outs.append([dev.read_output(b).tolist() for b in range(2)])
+        logits.append(dev.debug(DBG.LOGITS).copy())
+        dev.close()
+    assert outs[0] == outs[1] == outs[2] == outs[3]
+    for l in logits[1:]:
+        assert np.array_equal(logits[0], l)             # bit-reproducible
+    assert all(len(o) >= 12 for o in outs[0])

@@ -1,0 +1,186 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI.
+
+Tolerances: logits relative L2 <= 1e-4 (fp32 model) / 1e-2 (bf16 model); token
+decisions exact wherever the oracle's deciding margin exceeds 1e-2 (see
+tests/parity.py for the protocol).
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from oracle import vadusa_oracle as O
+from synth import (ModelConfig, PRESETS, make_weights, make_tokens, make_tree, chain_tree,
+                   full_tree)
+from helpers import planted_lists
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _lock(*a, **k):
+    from parity import Lockstep
+    return Lockstep(*a, **k)
+
+
+def small_cfg(dtype, layers=2, d=128, heads=3, V=300, maxpos=256):
+    return ModelConfig(n_layers=layers, d_model=d, n_heads=d // 64, head_dim=64, d_ffn=4 * d,
+                       speech_vocab=V, text_vocab=50, n_draft_heads=heads, max_positions=maxpos,
+                       dtype=dtype)
+
+
+def rand_tokens(cfg, rng, B, tl, pl):
+    text = [rng.integers(0, cfg.text_vocab, int(rng.integers(tl[0], tl[1] + 1))).astype(np.int32) for _ in range(B)]
+    prompt = [rng.integers(0, cfg.speech_vocab, int(rng.integers(pl[0], pl[1] + 1))).astype(np.int32) for _ in range(B)]
+    return text, prompt
+
+
+@pytest.mark.parametrize("tau", [1, 3])
+def test_tiny_fp32_full_generation(tau):
+    """Configuration 1 end to end: 32 text + 75 prompt tokens, 150 generated, 16-node tree."""
+    wl = PRESETS["tiny"]
+    _say(f"tiny fp32 tau={tau}")
+    W = make_weights(wl.model, wl.seed)
+    text, prompt = make_tokens(wl)
+    tree = make_tree(wl.tree_nodes, wl.topk_caps)
+    ls = _lock(wl.model, W, text, prompt, wl.tree_nodes)
+    while len(ls.sts[0].emitted) < wl.n_generate:
+        ls.step(tree, tau)
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    _say(f"  steps {s.steps} compared {s.compared} ties root/list/edge {s.tie_root}/{s.tie_list}/{s.tie_edge} "
+         f"logit err {s.max_logit_err:.2e} kv err {s.max_kv_err:.2e}")
+    assert s.compared >= 0.8 * s.steps
+    assert s.max_logit_err < 1e-4
+
+
+@pytest.mark.parametrize("dtype,tau", [("fp32", 1), ("fp32", 2), ("bf16", 1), ("bf16", 3)])
+def test_planted_drafts_long_paths(dtype, tau):
+    """Acceptance dial: the true continuation planted among the candidates gives
+    accepted paths of every length, exercising acceptance, compaction and the
+    continuation from the last accepted node."""
+    cfg = small_cfg(dtype)
+    _say(f"planted drafts {dtype} tau={tau}")
+    W = make_weights(cfg, 5, std=0.08, ln_jitter=0.1)
+    rng = np.random.default_rng(21)
+    text, prompt = rand_tokens(cfg, rng, 1, (9, 9), (21, 21))
+    tree = make_tree(24, (5, 4, 3))
+    model = O.Model(cfg, W)
+    greedy = O.generate(model, text[0], prompt[0], chain_tree(1), 1, 70, ignore_eos=True)[0]
+    ls = _lock(cfg, W, text, prompt, 24)
+    while len(ls.sts[0].emitted) < 48:
+        st = ls.sts[0]
+        n = len(st.emitted)
+        on = st.emitted == greedy[:n] and st.root == greedy[n]
+        fut = greedy[n + 1:n + 1 + cfg.n_draft_heads] if on else []
+        lists = planted_lists(fut, tree, cfg.n_draft_heads, cfg.n_logits, rng, p_hit=0.8)
+        ls.step(tree, tau, override=[lists])
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    _say(f"  accepted lengths {np.bincount(s.accepted_hist).tolist()} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} "
+         f"logit err {s.max_logit_err:.2e}")
+    assert max(s.accepted_hist) == cfg.n_draft_heads + 1
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_ragged_batch_multi_chunk_prefill(dtype):
+    """Three sequences of different lengths; prompts longer than one prefill chunk
+    (ragged first chunk), different trees from step to step."""
+    cfg = small_cfg(dtype, maxpos=320)
+    _say(f"ragged batch {dtype}")
+    W = make_weights(cfg, 6, std=0.08, ln_jitter=0.1)
+    rng = np.random.default_rng(22)
+    text, prompt = rand_tokens(cfg, rng, 3, (3, 30), (17, 120))
+    ls = _lock(cfg, W, text, prompt, 32)
+    trees = [make_tree(32, (6, 4, 3)), chain_tree(4), full_tree((3, 2)), make_tree(17, (4, 2, 2)), chain_tree(1)]
+    for i in range(15):
+        ls.step(trees[i % len(trees)], 1 + i % 3)
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    _say(f"  compared {s.compared}/{s.steps} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} logit err {s.max_logit_err:.2e}")
+    assert s.compared >= 10
+
+
+def test_eos_cuts_path_and_finishes():
+    cfg = small_cfg("fp32")
+    W = make_weights(cfg, 8, std=0.08)
+    rng = np.random.default_rng(23)
+    text, prompt = rand_tokens(cfg, rng, 2, (5, 5), (12, 12))
+    tree = chain_tree(4)
+    ls = _lock(cfg, W, text, prompt, 8, ignore_eos=False)
+    eos = cfg.speech_vocab
+    # tau = V+1 accepts every edge; sequence 0 gets EOS as its second draft
+    lists = [[[7], [eos], [9]], [[1], [2], [3]]]
+    r = ls.step(tree, cfg.n_logits, override=lists)
+    assert r[0]["accepted"][-1] == eos and len(r[0]["accepted"]) == 3 and len(r[1]["accepted"]) == 4
+    assert ls.sts[0].finished and not ls.sts[1].finished
+    r = ls.step(tree, cfg.n_logits, override=lists)
+    assert r[0]["accepted"] == []
+    out = ls.dev.step(__import__("paper_2410_21951_amd").TreeArrays(tree.parent, tree.rank), 1)
+    assert out[0] == [] and len(out[1]) >= 1
+
+
+@pytest.fixture(scope="module")
+def valle():
+    wl = PRESETS["valle_b1"]
+    _say("generating 12-layer d=1024 weights")
+    return wl, make_weights(wl.model, wl.seed)
+
+
+@pytest.mark.parametrize("extra", [0, 500])
+def test_valle_b1_sampled_steps(valle, extra):
+    """Configuration 2 at full size (12 layers, d=1024, bf16, 64-node tree): steps at
+    the start of generation (L = 289) and deep into it (L = 789)."""
+    wl, W = valle
+    text, prompt = make_tokens(wl)
+    rng = np.random.default_rng(24)
+    prompt = [np.concatenate([prompt[0], rng.integers(0, wl.model.speech_vocab, extra).astype(np.int32)])]
+    tree = make_tree(wl.tree_nodes, wl.topk_caps)
+    _say(f"valle_b1 L0={len(text[0]) + len(prompt[0])}")
+    ls = _lock(wl.model, W, text, prompt, wl.tree_nodes)
+    for i, tau in enumerate((1, 2, 4, 8)):
+        ls.step(tree, tau)
+        _say(f"  step {i} tau {tau} logit err {ls.stats.max_logit_err:.3e}")
+    ls.check_kv(layers=[0, 5, 11])
+    s = ls.stats
+    _say(f"  compared {s.compared}/{s.steps} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} "
+         f"logit err {s.max_logit_err:.2e} h err {s.max_h_err:.2e} kv err {s.max_kv_err:.2e}")
+    assert s.compared >= 3
+
+
+def test_longform_shape_128_nodes_5_heads():
+    """Configuration 4's shape (5 draft heads, 128-node tree) on a 3-layer d=1024 model
+    with a prompt spanning several prefill chunks."""
+    m = PRESETS["longform_b1"].model
+    cfg = dataclasses.replace(m, n_layers=3, max_positions=1024)
+    W = make_weights(cfg, 9)
+    rng = np.random.default_rng(25)
+    text, prompt = rand_tokens(cfg, rng, 1, (64, 64), (400, 400))
+    tree = make_tree(128, (10,) * 5)
+    ls = _lock(cfg, W, text, prompt, 128)
+    for tau in (1, 4, 4):
+        ls.step(tree, tau)
+    ls.check_kv(layers=[0, 2])
+    s = ls.stats
+    _say(f"longform shape: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e}")
+    assert s.compared >= 2
+
+
+def test_throughput_shape_batch():
+    """Configuration 5's shape (many sequences, 32-node trees) reduced to 8 sequences
+    and 2 layers of the d=1024 model."""
+    m = PRESETS["throughput_b64"].model
+    cfg = dataclasses.replace(m, n_layers=2, max_positions=400)
+    W = make_weights(cfg, 10)
+    rng = np.random.default_rng(26)
+    text, prompt = rand_tokens(cfg, rng, 8, (64, 64), (225, 225))
+    tree = make_tree(32, (10,) * 4)
+    ls = _lock(cfg, W, text, prompt, 32)
+    for tau in (1, 8):
+        ls.step(tree, tau)
+    s = ls.stats
+    _say(f"throughput shape: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e}")
+    assert s.compared >= 1
