@@ -67,7 +67,8 @@ def test_planted_drafts_long_paths(dtype, tau):
     W = make_weights(cfg, 5, std=0.08, ln_jitter=0.1)
     rng = np.random.default_rng(21)
     text, prompt = rand_tokens(cfg, rng, 1, (9, 9), (21, 21))
-    tree = make_tree(24, (5, 4, 3))
+    tree = make_tree(24, (3, 3, 2), alpha0=0.9, decay=1.0)
+    assert tree.max_depth == 3
     model = O.Model(cfg, W)
     greedy = O.generate(model, text[0], prompt[0], chain_tree(1), 1, 70, ignore_eos=True)[0]
     ls = _lock(cfg, W, text, prompt, 24)
@@ -82,7 +83,7 @@ def test_planted_drafts_long_paths(dtype, tau):
     s = ls.stats
     _say(f"  accepted lengths {np.bincount(s.accepted_hist).tolist()} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} "
          f"logit err {s.max_logit_err:.2e}")
-    assert max(s.accepted_hist) == cfg.n_draft_heads + 1
+    assert max(s.accepted_hist) == cfg.n_draft_heads + 1 and min(s.accepted_hist) == 1
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
