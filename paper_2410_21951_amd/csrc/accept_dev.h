@@ -1,0 +1,200 @@
+// Device functions for verification with tolerance (Algorithm 1), choice of the
+// accepted path (Sec. 2.3), continuation from the last accepted node (Sec. 2.1),
+// KV compaction and the draft heads' top-k lists.  Each function is the body of
+// one workgroup of 256 threads (64 for the compaction); the generic kernels and
+// the persistent step kernel both call them.
+#pragma once
+#include "common.h"
+
+// Total order used everywhere a "largest logit" is needed: value descending,
+// then token id ascending.  before(a, b) = a ranks strictly ahead of b.
+__device__ __forceinline__ bool before(float va, int ia, float vb, int ib) {
+    return va > vb || (va == vb && ia < ib);
+}
+
+// Block-wide arg-best under the order above, restricted to entries that come
+// strictly after (pv, pi).  Every thread returns the winner.  256 threads.
+__device__ inline int block_argbest(const float* __restrict__ z, int n, float pv, int pi, float* best_val) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int v = threadIdx.x; v < n; v += 256) {
+        const float zv = z[v];
+        if (before(pv, pi, zv, v) && before(zv, v, bv, bi)) { bv = zv; bi = v; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    __syncthreads();   // protects sv/si against the previous call's readers
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    bv = sv[0]; bi = si[0];
+    for (int w = 1; w < 4; ++w) if (before(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+    if (best_val) *best_val = bv;
+    return bi;
+}
+
+// Algorithm 1 on every edge of sequence b at once, then Sec. 2.3's choice.
+// Edge n is accepted iff fewer than tau entries of the parent's logit row rank
+// before the node's token (one wave counts one edge).  path_ok[n] = every edge
+// from the root to n accepted; the chosen node is the deepest such node,
+// smallest index among equals (canonical order = leftmost).
+// Output: path[b] = {count, node indices...}; the count is cut after the first EOS.
+__device__ inline void dev_accept(const Dims& D, const DevState& s, int b, int tau, int ignore_eos) {
+    __shared__ int s_edge[VADUSA_MAX_TREE_NODES];
+    __shared__ int s_ok[VADUSA_MAX_TREE_NODES];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int32_t* path = s.path + (size_t)b * (VADUSA_MAX_DRAFT_HEADS + 2);
+    if (s.finished[b]) {
+        if (threadIdx.x == 0) path[0] = 0;
+        for (int n = threadIdx.x; n < D.M; n += 256) s.edge_ok[b * D.M + n] = 0;
+        return;
+    }
+    const int32_t* parent = s.t_parent[0];
+    const int32_t* depth = s.t_depth[0];
+    const int32_t* tok = s.tok + (size_t)b * D.M;
+    for (int n = wave; n < D.M; n += 4) {
+        int edge = 1;
+        if (n > 0) {
+            const float* z = s.logits + ((size_t)b * D.M + parent[n]) * D.V1;
+            const int t = tok[n];
+            const float zt = z[t];
+            int cnt = 0;
+            for (int v = lane; v < D.V1; v += 64) cnt += before(z[v], v, zt, t) ? 1 : 0;
+            edge = wave_sum_i(cnt) < tau;
+        }
+        if (lane == 0) { s_edge[n] = edge; s.edge_ok[b * D.M + n] = edge; }
+    }
+    __syncthreads();
+    for (int n = threadIdx.x; n < D.M; n += 256) {
+        int ok = 1, m = n;
+        while (m > 0) { ok &= s_edge[m]; m = parent[m]; }
+        s_ok[n] = ok;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int best = 0;
+        for (int n = 1; n < D.M; ++n)
+            if (s_ok[n] && depth[n] > depth[best]) best = n;
+        int cnt = depth[best] + 1;
+        int m = best;
+        for (int j = cnt - 1; j >= 0; --j) { path[1 + j] = m; m = parent[m]; }
+        if (!ignore_eos)
+            for (int j = 0; j < cnt; ++j)
+                if (tok[path[1 + j]] == D.V1 - 1) { cnt = j + 1; break; }
+        path[0] = cnt;
+    }
+    __syncthreads();
+}
+
+// Continue from the last accepted node (Sec. 2.1): advance L, append the
+// accepted tokens to the output, next root = best logit of that node's row, and
+// its final-LayerNorm'd hidden state for the draft heads (copied from hn, or, if
+// from_x, computed here from the residual stream).  acc_len[b] keeps the number
+// of committed rows for the compaction that follows.  In prefill mode the
+// "path" is the chunk's last row and nothing is emitted.
+template <class T>
+__device__ inline void dev_finalize(const Dims& D, const DevState& s, int b, int prefill_mode, int ignore_eos,
+                                    int from_x) {
+    __shared__ float s_red[8];
+    int32_t* path = s.path + (size_t)b * (VADUSA_MAX_DRAFT_HEADS + 2);
+    int cnt, last;
+    if (prefill_mode) {
+        cnt = s.n_rows[b];
+        last = cnt - 1;
+    } else {
+        cnt = path[0];
+        last = cnt > 0 ? path[cnt] : 0;
+    }
+    if (threadIdx.x == 0) s.acc_len[b] = prefill_mode ? 0 : cnt;
+    if (cnt <= 0) return;
+    const int32_t* tok = s.tok + (size_t)b * D.M;
+    const int r = b * D.M + last;
+    const int root = block_argbest(s.logits + (size_t)r * D.V1, D.V1, INFINITY, -1, nullptr);
+    T* hb = (T*)s.hbest + (size_t)b * D.d;
+    if (from_x) {
+        const float* xr = s.x + (size_t)r * D.d;
+        float sum = 0.f;
+        for (int i = threadIdx.x; i < D.d; i += 256) sum += xr[i];
+        sum = wave_sum(sum);
+        if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = sum;
+        __syncthreads();
+        const float mu = (s_red[0] + s_red[1] + s_red[2] + s_red[3]) / D.d;
+        float sq = 0.f;
+        for (int i = threadIdx.x; i < D.d; i += 256) { const float t = xr[i] - mu; sq += t * t; }
+        sq = wave_sum(sq);
+        if ((threadIdx.x & 63) == 0) s_red[4 + (threadIdx.x >> 6)] = sq;
+        __syncthreads();
+        const float rstd = rsqrtf((s_red[4] + s_red[5] + s_red[6] + s_red[7]) / D.d + LN_EPS);
+        for (int i = threadIdx.x; i < D.d; i += 256) stf(hb + i, (xr[i] - mu) * rstd * s.lnf_g[i] + s.lnf_b[i]);
+    } else {
+        const T* h = (const T*)s.hn + (size_t)r * D.d;
+        for (int i = threadIdx.x; i < D.d; i += 256) hb[i] = h[i];
+    }
+    if (threadIdx.x == 0) {
+        s.root[b] = root;
+        s.L[b] += cnt;
+        if (!prefill_mode) {
+            int no = s.n_out[b];
+            bool fin = false;
+            for (int j = 0; j < cnt; ++j) {
+                const int t = tok[path[1 + j]];
+                s.acc_tok[b * (VADUSA_MAX_DRAFT_HEADS + 1) + j] = t;
+                if (no < D.maxpos) s.out_tok[(size_t)b * D.maxpos + no++] = t;
+                if (t == D.V1 - 1) fin = true;
+            }
+            s.n_out[b] = no;
+            path[0] = 0;   // consumed
+            if (fin && !ignore_eos) s.finished[b] = 1;
+        }
+    }
+}
+
+// KV compaction after dev_finalize: cache row L0 + j <- row L0 + path[j], where
+// L0 = L - acc_len is the length before this step and acc_len the number of
+// committed rows.  path[j] >= j, so a destination row can be the source of an
+// earlier j: every thread owns one column of one head and reads all its sources
+// before writing.  64 threads (one per head dimension).
+template <class T>
+__device__ inline void dev_commit_kv(const Dims& D, const DevState& s, int layer, int b, int head, int dim) {
+    const int32_t* path = s.path + (size_t)b * (VADUSA_MAX_DRAFT_HEADS + 2);
+    const int cnt = s.acc_len[b];
+    if (cnt <= 0) return;
+    const int L0 = s.L[b] - cnt;
+    const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
+    T* Kh = (T*)s.Kc + hb;
+    T* Vh = (T*)s.Vc + hb;
+    T kr[VADUSA_MAX_DRAFT_HEADS + 1], vr[VADUSA_MAX_DRAFT_HEADS + 1];
+#pragma unroll
+    for (int j = 0; j < VADUSA_MAX_DRAFT_HEADS + 1; ++j)
+        if (j < cnt) {
+            kr[j] = Kh[(size_t)(L0 + path[1 + j]) * 64 + dim];
+            vr[j] = Vh[(size_t)dim * D.maxpos + L0 + path[1 + j]];
+        }
+#pragma unroll
+    for (int j = 0; j < VADUSA_MAX_DRAFT_HEADS + 1; ++j)
+        if (j < cnt) {
+            Kh[(size_t)(L0 + j) * 64 + dim] = kr[j];
+            Vh[(size_t)dim * D.maxpos + L0 + j] = vr[j];
+        }
+}
+
+// Draft list of head i, sequence b: the VADUSA_MAX_TOPK best ids of its logits,
+// descending, equal logits: lower id first (Sec. 2.1).
+__device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) {
+    const float* z = s.zdraft + ((size_t)i * D.Bmax + b) * D.V1;
+    int32_t* out = s.draft_topk + ((size_t)b * D.Hh + i) * VADUSA_MAX_TOPK;
+    float pv = INFINITY;
+    int pi = -1;
+    const int kmax = D.V1 < VADUSA_MAX_TOPK ? D.V1 : VADUSA_MAX_TOPK;
+    for (int k = 0; k < kmax; ++k) {
+        float bv;
+        const int bi = block_argbest(z, D.V1, pv, pi, &bv);
+        if (threadIdx.x == 0) out[k] = bi;
+        pv = bv; pi = bi;
+    }
+}

@@ -110,7 +110,7 @@ struct Carver {
     }
 };
 
-struct WeightSlot { void* dev; size_t rows, cols; bool is_matrix; };   // blob order
+struct WeightSlot { void* dev; size_t rows, cols; int kind; };   // blob order; kind 0 vector, 1 table, 2 linear map
 
 static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vector<LayerW>* layers,
                      std::vector<DraftW>* draft, std::vector<WeightSlot>* slots, size_t* staging_floats) {
@@ -123,18 +123,18 @@ static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vecto
     std::vector<DraftW> dw(Hh);
     std::vector<WeightSlot> sl;
     size_t biggest = std::max(R * std::max(d, V1), P * d);
-    auto mat = [&](const void** dst, size_t rows, size_t cols) {
+    auto mat = [&](const void** dst, size_t rows, size_t cols, int kind = 2) {
         *dst = cv.take((size_t)pad16((int)rows) * cols * e);
-        sl.push_back({(void*)*dst, rows, cols, true});
+        sl.push_back({(void*)*dst, rows, cols, kind});
         biggest = std::max(biggest, rows * cols);
     };
     auto vec = [&](const float** dst, size_t n) {
         *dst = (const float*)cv.take(n * 4);
-        sl.push_back({(void*)*dst, 1, n, false});
+        sl.push_back({(void*)*dst, 1, n, 0});
     };
-    mat(&st.E_text, c.text_vocab, d);
-    mat(&st.E_speech, V1, d);
-    mat(&st.P, P, d);
+    mat(&st.E_text, c.text_vocab, d, 1);
+    mat(&st.E_speech, V1, d, 1);
+    mat(&st.P, P, d, 1);
     for (int l = 0; l < c.n_layers; ++l) {
         LayerW& w = lw[l];
         vec(&w.ln1_g, d); vec(&w.ln1_b, d);
@@ -270,21 +270,27 @@ extern "C" int vadusa_load_weights(vadusa_ctx* c, const float* blob, size_t n_fl
         const size_t n = w.rows * w.cols;
         void* dst = w.dev;
         const float* src = blob + off;
+        const bool is_matrix = w.kind != 0;
         if (!on_device) {
-            if (w.is_matrix) {
+            if (is_matrix) {
                 HIP_TRY(c, hipMemcpyAsync(c->s.staging, src, n * 4, hipMemcpyHostToDevice, c->stream));
                 src = c->s.staging;
             } else {
                 HIP_TRY(c, hipMemcpyAsync(dst, src, n * 4, hipMemcpyHostToDevice, c->stream));
             }
-        } else if (!w.is_matrix) {
+        } else if (!is_matrix) {
             HIP_TRY(c, hipMemcpyAsync(dst, src, n * 4, hipMemcpyDeviceToDevice, c->stream));
         }
-        if (w.is_matrix) {
-            const size_t padded = (size_t)pad16((int)w.rows) * w.cols;
-            if (padded > n)
-                HIP_TRY(c, hipMemsetAsync((char*)dst + n * c->elem, 0, (padded - n) * c->elem, c->stream));
-            launch_convert(src, dst, n, c->cfg.dtype, c->stream);
+        if (is_matrix) {
+            if (w.kind == 2 && c->cfg.dtype) {
+                // linear maps of the bf16 model are stored in the MFMA-tiled layout
+                launch_pack_w(src, dst, (int)w.rows, (int)w.cols, c->stream);
+            } else {
+                const size_t padded = (size_t)pad16((int)w.rows) * w.cols;
+                if (padded > n)
+                    HIP_TRY(c, hipMemsetAsync((char*)dst + n * c->elem, 0, (padded - n) * c->elem, c->stream));
+                launch_convert(src, dst, n, c->cfg.dtype, c->stream);
+            }
         }
         off += n;
     }
@@ -298,6 +304,11 @@ extern "C" int vadusa_load_weights(vadusa_ctx* c, const float* blob, size_t n_fl
 // forward of B x M rows through the decoder (Sec. 2.1 tree attention; the
 // prefill uses the same path with a causal chunk as the "tree")
 // ---------------------------------------------------------------------------
+static void gemm(vadusa_ctx* c, const GemmArgs& a) {
+    if (c->cfg.dtype) launch_gemm_mfma(a, c->stream);
+    else launch_gemm_simple(a, 0, c->stream);
+}
+
 static void forward(vadusa_ctx* c, const Dims& D, int table, int prefill_mode, bool want_logits) {
     const int dt = c->cfg.dtype;
     const DevState& s = c->s;
@@ -312,24 +323,24 @@ static void forward(vadusa_ctx* c, const Dims& D, int table, int prefill_mode, b
         a.X = s.xn; a.W = w.Wqkv; a.bias = w.bqkv; a.R = R; a.K = D.d; a.N = 3 * D.d; a.epi = EPI_QKV;
         a.out = s.q; a.Kc = (char*)s.Kc + l * kv_layer; a.Vc = (char*)s.Vc + l * kv_layer;
         a.L = s.L; a.M = D.M; a.nH = D.nH; a.maxpos = D.maxpos; a.d = D.d;
-        launch_gemm_simple(a, dt, st);
+        gemm(c, a);
         launch_attn_simple(D, s, l, table, dt, st);
         GemmArgs o{};
         o.X = s.att; o.W = w.Wo; o.bias = w.bo; o.R = R; o.K = D.d; o.N = D.d; o.epi = EPI_RESID; o.outf = s.x;
-        launch_gemm_simple(o, dt, st);
+        gemm(c, o);
         launch_layernorm(s.x, w.ln2_g, w.ln2_b, s.xn, R, D.d, dt, st);
         GemmArgs f1{};
         f1.X = s.xn; f1.W = w.W1; f1.bias = w.b1; f1.R = R; f1.K = D.d; f1.N = D.F; f1.epi = EPI_GELU; f1.out = s.hid;
-        launch_gemm_simple(f1, dt, st);
+        gemm(c, f1);
         GemmArgs f2{};
         f2.X = s.hid; f2.W = w.W2; f2.bias = w.b2; f2.R = R; f2.K = D.F; f2.N = D.d; f2.epi = EPI_RESID; f2.outf = s.x;
-        launch_gemm_simple(f2, dt, st);
+        gemm(c, f2);
     }
     if (want_logits) {
         launch_layernorm(s.x, s.lnf_g, s.lnf_b, s.hn, R, D.d, dt, st);
         GemmArgs h{};
         h.X = s.hn; h.W = s.W_out; h.bias = nullptr; h.R = R; h.K = D.d; h.N = D.V1; h.epi = EPI_F32; h.outf = s.logits;
-        launch_gemm_simple(h, dt, st);
+        gemm(c, h);
     }
 }
 
@@ -343,11 +354,11 @@ static void draft_heads(vadusa_ctx* c, const Dims& D, int seq0, int nseq) {
         GemmArgs a{};
         a.X = (char*)s.hbest + (size_t)seq0 * D.d * c->elem; a.W = c->draft[i].W1; a.bias = c->draft[i].b1;
         a.R = nseq; a.K = D.d; a.N = D.d; a.epi = EPI_SILU_RESID; a.out = r;
-        launch_gemm_simple(a, dt, c->stream);
+        gemm(c, a);
         GemmArgs z{};
         z.X = r; z.W = c->draft[i].W2; z.bias = nullptr; z.R = nseq; z.K = D.d; z.N = D.V1; z.epi = EPI_F32;
         z.outf = s.zdraft + ((size_t)i * D.Bmax + seq0) * D.V1;
-        launch_gemm_simple(z, dt, c->stream);
+        gemm(c, z);
     }
     launch_topk(D, s, seq0, nseq, c->stream);
 }
@@ -523,8 +534,8 @@ extern "C" int vadusa_kv_compact(vadusa_ctx* c, int32_t seq, const int32_t* path
             HIP_TRY(c, hipStreamSynchronize(c->stream));
         }
     }
-    launch_commit_kv(D, s, seq0, nseq, c->cfg.dtype, c->stream);
     launch_finalize(D, s, seq0, nseq, 0, c->cfg.ignore_eos, c->cfg.dtype, c->stream);
+    launch_commit_kv(D, s, seq0, nseq, c->cfg.dtype, c->stream);
     draft_heads(c, D, seq0, nseq);
     HIP_TRY(c, hipGetLastError());
     bool any = false;
@@ -644,7 +655,7 @@ extern "C" int vadusa_debug_read_kv(vadusa_ctx* c, int32_t layer, int32_t seq, i
     const size_t kv_layer = (size_t)D.Bmax * D.nH * D.maxpos * 64 * c->elem;
     const char* base = (const char*)(which ? c->s.Vc : c->s.Kc) + layer * kv_layer;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    launch_read_kv(D, base, seq, pos0, npos, c->s.staging, c->cfg.dtype, c->stream);
+    launch_read_kv(D, base, seq, which, pos0, npos, c->s.staging, c->cfg.dtype, c->stream);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     HIP_TRY(c, hipMemcpy(host, c->s.staging, (size_t)npos * D.d * 4, hipMemcpyDeviceToHost));
     return VADUSA_OK;

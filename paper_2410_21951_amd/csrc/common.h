@@ -50,6 +50,8 @@ struct Dims {
 struct LayerW {
     const float *ln1_g, *ln1_b, *bqkv, *bo, *ln2_g, *ln2_b, *b1, *b2;
     const void *Wqkv, *Wo, *W1, *W2;   // element type follows the context dtype
+    // bf16 model only: LayerNorm folded into the following linear map (see k_step.hip)
+    float *cs_qkv, *t_qkv, *cs_w1, *t_w1;
 };
 struct DraftW {
     const void* W1; const float* b1; const void* W2;
@@ -61,10 +63,17 @@ struct DevState {
     const void *E_text, *E_speech, *P;
     const float *lnf_g, *lnf_b;
     const void* W_out;
-    // KV cache, element type = dtype: [Ly][Bmax][nH][maxpos][64]
+    float *cs_out, *t_out;          // bf16 model: folded final LayerNorm for the vocabulary map
+    const LayerW* layers_dev;       // bf16 model: the layer table in device memory
+    const DraftW* draft_dev;
+    // KV cache, element type = dtype: K [Ly][Bmax][nH][maxpos][64], V [Ly][Bmax][nH][64][maxpos]
     void *Kc, *Vc;
     // activations
     float* x;        // [R][d]  residual stream
+    bf16_t* xb;      // [R][d]  bf16 copy of the residual stream (bf16 model)
+    float* stats[2]; // [d/16][R][2] per 16-column tile: mean and sum of squared deviations
+    uint32_t* flags; // [1024] grid-barrier flags of the persistent step kernel
+    int32_t* kerr;   // [4] error flag raised by a kernel (barrier time-out)
     void* xn;        // [R][d]  LayerNorm output
     void* q;         // [R][d]
     void* att;       // [R][d]
@@ -129,10 +138,30 @@ struct GemmArgs {
     int M, nH, maxpos, d;
 };
 
+// Parameters of the persistent step kernel (bf16 model).
+struct StepParams {
+    Dims D;
+    DevState s;
+    int table;          // which tree table the rows use (0 tree, 1 causal chunk)
+    int prefill_mode;
+    int tau, ignore_eos;
+    int ph_lo, ph_hi;   // phases to run: [ph_lo, ph_hi)
+    int persistent;     // 1: one cooperative launch with grid barriers between phases
+    uint32_t epoch;     // barrier epoch before the first barrier of this launch
+    int seq0, nseq;     // sequences the compaction phases act on
+};
+int step_num_phases(int n_layers);
+// phase index helpers: 0 embed; 1+5l.. layer l (qkv, attn, wo, ffn1, ffn2); then head, accept, finalize, commit+draft1, draft2, topk
+void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err);
+void launch_pack_w_ln(const float* src, const float* gamma, const float* beta, const float* bias, void* dst,
+                      float* colsum, float* tvec, int N, int K, hipStream_t st);
+
 // ---- launch wrappers (each enqueues on `st`, no synchronisation) ----
 void launch_embed(const Dims& D, const DevState& s, int dtype, int prefill_mode, int table, hipStream_t st);
 void launch_layernorm(const float* x, const float* g, const float* b, void* out, int R, int d, int dtype, hipStream_t st);
 void launch_gemm_simple(const GemmArgs& a, int dtype, hipStream_t st);
+void launch_gemm_mfma(const GemmArgs& a, hipStream_t st);
+void launch_pack_w(const float* src, void* dst, int N, int K, hipStream_t st);
 void launch_attn_simple(const Dims& D, const DevState& s, int layer, int table, int dtype, hipStream_t st);
 void launch_accept(const Dims& D, const DevState& s, int tau, int ignore_eos, hipStream_t st);
 void launch_commit_kv(const Dims& D, const DevState& s, int seq0, int nseq, int dtype, hipStream_t st);
@@ -140,5 +169,5 @@ void launch_finalize(const Dims& D, const DevState& s, int seq0, int nseq, int p
 void launch_topk(const Dims& D, const DevState& s, int seq0, int nseq, hipStream_t st);
 void launch_convert(const float* src, void* dst, size_t n, int dtype, hipStream_t st);
 void launch_advance(const DevState& s, int B, hipStream_t st);
-void launch_read_kv(const Dims& D, const void* cache_layer, int seq, int pos0, int npos, float* out, int dtype, hipStream_t st);
+void launch_read_kv(const Dims& D, const void* cache_layer, int seq, int which, int pos0, int npos, float* out, int dtype, hipStream_t st);
 void launch_to_float(const void* src, float* dst, size_t n, int dtype, hipStream_t st);

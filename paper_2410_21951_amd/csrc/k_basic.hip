@@ -102,8 +102,9 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, int r, int n, float 
         const int b = r / a.M, node = r % a.M;
         const int pos = a.L[b] + node;
         if (pos < a.maxpos) {
-            T* base = (T*)(which ? a.Vc : a.Kc);
-            stf(base + (((size_t)b * a.nH + head) * a.maxpos + pos) * 64 + dim, acc);
+            const size_t hb = ((size_t)b * a.nH + head) * a.maxpos * 64;
+            if (which) stf((T*)a.Vc + hb + (size_t)dim * a.maxpos + pos, acc);   // V is kept [dim][pos]
+            else stf((T*)a.Kc + hb + (size_t)pos * 64 + dim, acc);               // K is kept [pos][dim]
         }
         break;
     }
@@ -184,9 +185,9 @@ __global__ void k_attn_simple(Dims D, DevState s, int layer, int table) {
         const float mn = fmaxf(m, sc);
         const float corr = __expf(m - mn), p = __expf(sc - mn);
         l = l * corr + p;
-        const T* vr = Vh + (size_t)j * 64;
+        const T* vr = Vh + j;
 #pragma unroll
-        for (int i = 0; i < 64; ++i) o[i] = o[i] * corr + p * ldf(vr + i);
+        for (int i = 0; i < 64; ++i) o[i] = o[i] * corr + p * ldf(vr + (size_t)i * D.maxpos);
         m = mn;
     }
     const float mx = wave_max(m);
@@ -246,17 +247,18 @@ void launch_advance(const DevState& s, int B, hipStream_t st) {
     hipLaunchKernelGGL(k_advance, dim3((B + 63) / 64), dim3(64), 0, st, s, B);
 }
 
-// out[p][head*64 + dim] = cache[seq][head][pos0 + p][dim]
+// out[p][head*64 + dim] = K[seq][head][pos0 + p][dim]  or  V[seq][head][dim][pos0 + p]
 template <class T>
-__global__ void k_read_kv(Dims D, const T* __restrict__ cache, int seq, int pos0, int npos, float* out) {
+__global__ void k_read_kv(Dims D, const T* __restrict__ cache, int seq, int which, int pos0, int npos, float* out) {
     const int p = blockIdx.x;
     for (int c = threadIdx.x; c < D.d; c += blockDim.x) {
         const int head = c >> 6, dim = c & 63;
-        out[(size_t)p * D.d + c] =
-            ldf(cache + (((size_t)seq * D.nH + head) * D.maxpos + pos0 + p) * 64 + dim);
+        const size_t hb = ((size_t)seq * D.nH + head) * D.maxpos * 64;
+        out[(size_t)p * D.d + c] = which ? ldf(cache + hb + (size_t)dim * D.maxpos + pos0 + p)
+                                         : ldf(cache + hb + (size_t)(pos0 + p) * 64 + dim);
     }
 }
-void launch_read_kv(const Dims& D, const void* cache_layer, int seq, int pos0, int npos, float* out, int dtype, hipStream_t st) {
-    if (dtype) hipLaunchKernelGGL(k_read_kv<bf16_t>, dim3(npos), dim3(256), 0, st, D, (const bf16_t*)cache_layer, seq, pos0, npos, out);
-    else hipLaunchKernelGGL(k_read_kv<float>, dim3(npos), dim3(256), 0, st, D, (const float*)cache_layer, seq, pos0, npos, out);
+void launch_read_kv(const Dims& D, const void* cache_layer, int seq, int which, int pos0, int npos, float* out, int dtype, hipStream_t st) {
+    if (dtype) hipLaunchKernelGGL(k_read_kv<bf16_t>, dim3(npos), dim3(256), 0, st, D, (const bf16_t*)cache_layer, seq, which, pos0, npos, out);
+    else hipLaunchKernelGGL(k_read_kv<float>, dim3(npos), dim3(256), 0, st, D, (const float*)cache_layer, seq, which, pos0, npos, out);
 }

@@ -26,6 +26,13 @@ def _lock(*a, **k):
     return Lockstep(*a, **k)
 
 
+# Weight scale of the small models.  The 1e-2 decision margin is an absolute logit
+# gap stated for the workload's logit scale (std ~0.64 = 0.02 * sqrt(1024)); the small
+# bf16 models are scaled to the same logit std (0.05 * sqrt(128) ~ 0.57) so that the
+# same absolute margin means the same thing.
+STD = {"fp32": 0.08, "bf16": 0.05}
+
+
 def small_cfg(dtype, layers=2, d=128, heads=3, V=300, maxpos=256):
     return ModelConfig(n_layers=layers, d_model=d, n_heads=d // 64, head_dim=64, d_ffn=4 * d,
                        speech_vocab=V, text_vocab=50, n_draft_heads=heads, max_positions=maxpos,
@@ -64,7 +71,7 @@ def test_planted_drafts_long_paths(dtype, tau):
     continuation from the last accepted node."""
     cfg = small_cfg(dtype)
     _say(f"planted drafts {dtype} tau={tau}")
-    W = make_weights(cfg, 5, std=0.08, ln_jitter=0.1)
+    W = make_weights(cfg, 5, std=STD[dtype], ln_jitter=0.1)
     rng = np.random.default_rng(21)
     text, prompt = rand_tokens(cfg, rng, 1, (9, 9), (21, 21))
     tree = make_tree(24, (3, 3, 2), alpha0=0.9, decay=1.0)
@@ -92,7 +99,7 @@ def test_ragged_batch_multi_chunk_prefill(dtype):
     (ragged first chunk), different trees from step to step."""
     cfg = small_cfg(dtype, maxpos=320)
     _say(f"ragged batch {dtype}")
-    W = make_weights(cfg, 6, std=0.08, ln_jitter=0.1)
+    W = make_weights(cfg, 6, std=STD[dtype], ln_jitter=0.1)
     rng = np.random.default_rng(22)
     text, prompt = rand_tokens(cfg, rng, 3, (3, 30), (17, 120))
     ls = _lock(cfg, W, text, prompt, 32)
