@@ -19,9 +19,15 @@ __device__ inline int block_argbest(const float* __restrict__ z, int n, float pv
     __shared__ int si[4];
     float bv = -INFINITY;
     int bi = 0x7fffffff;
-    for (int v = threadIdx.x; v < n; v += 256) {
-        const float zv = z[v];
-        if (before(pv, pi, zv, v) && before(zv, v, bv, bi)) { bv = zv; bi = v; }
+    for (int v0 = threadIdx.x; v0 < n; v0 += 256 * 4) {
+        float zv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) zv[j] = v0 + 256 * j < n ? z[v0 + 256 * j] : 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int v = v0 + 256 * j;
+            if (v < n && before(pv, pi, zv[j], v) && before(zv[j], v, bv, bi)) { bv = zv[j]; bi = v; }
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -50,8 +56,8 @@ __device__ inline void dev_accept(const Dims& D, const DevState& s, int b, int t
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     int32_t* path = s.path + (size_t)b * (VADUSA_MAX_DRAFT_HEADS + 2);
     if (s.finished[b]) {
-        if (threadIdx.x == 0) path[0] = 0;
-        for (int n = threadIdx.x; n < D.M; n += 256) s.edge_ok[b * D.M + n] = 0;
+        if (threadIdx.x == 0) stwi(path, 0);
+        for (int n = threadIdx.x; n < D.M; n += 256) stwi(s.edge_ok + b * D.M + n, 0);
         return;
     }
     const int32_t* parent = s.t_parent[0];
@@ -64,10 +70,16 @@ __device__ inline void dev_accept(const Dims& D, const DevState& s, int b, int t
             const int t = tok[n];
             const float zt = z[t];
             int cnt = 0;
-            for (int v = lane; v < D.V1; v += 64) cnt += before(z[v], v, zt, t) ? 1 : 0;
+            for (int v0 = lane; v0 < D.V1; v0 += 64 * 8) {
+                float zv[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) zv[j] = v0 + 64 * j < D.V1 ? z[v0 + 64 * j] : -INFINITY;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) cnt += (v0 + 64 * j < D.V1 && before(zv[j], v0 + 64 * j, zt, t)) ? 1 : 0;
+            }
             edge = wave_sum_i(cnt) < tau;
         }
-        if (lane == 0) { s_edge[n] = edge; s.edge_ok[b * D.M + n] = edge; }
+        if (lane == 0) { s_edge[n] = edge; stwi(s.edge_ok + b * D.M + n, edge); }
     }
     __syncthreads();
     for (int n = threadIdx.x; n < D.M; n += 256) {
@@ -82,11 +94,13 @@ __device__ inline void dev_accept(const Dims& D, const DevState& s, int b, int t
             if (s_ok[n] && depth[n] > depth[best]) best = n;
         int cnt = depth[best] + 1;
         int m = best;
-        for (int j = cnt - 1; j >= 0; --j) { path[1 + j] = m; m = parent[m]; }
+        int nodes[VADUSA_MAX_DRAFT_HEADS + 1];
+        for (int j = cnt - 1; j >= 0; --j) { nodes[j] = m; m = parent[m]; }
         if (!ignore_eos)
             for (int j = 0; j < cnt; ++j)
-                if (tok[path[1 + j]] == D.V1 - 1) { cnt = j + 1; break; }
-        path[0] = cnt;
+                if (tok[nodes[j]] == D.V1 - 1) { cnt = j + 1; break; }
+        for (int j = 0; j < cnt; ++j) stwi(path + 1 + j, nodes[j]);
+        stwi(path, cnt);
     }
     __syncthreads();
 }
@@ -107,10 +121,10 @@ __device__ inline void dev_finalize(const Dims& D, const DevState& s, int b, int
         cnt = s.n_rows[b];
         last = cnt - 1;
     } else {
-        cnt = path[0];
-        last = cnt > 0 ? path[cnt] : 0;
+        cnt = ldci(path);
+        last = cnt > 0 ? ldci(path + cnt) : 0;
     }
-    if (threadIdx.x == 0) s.acc_len[b] = prefill_mode ? 0 : cnt;
+    if (threadIdx.x == 0) stwi(s.acc_len + b, prefill_mode ? 0 : cnt);
     if (cnt <= 0) return;
     const int32_t* tok = s.tok + (size_t)b * D.M;
     const int r = b * D.M + last;
@@ -119,37 +133,41 @@ __device__ inline void dev_finalize(const Dims& D, const DevState& s, int b, int
     if (from_x) {
         const float* xr = s.x + (size_t)r * D.d;
         float sum = 0.f;
-        for (int i = threadIdx.x; i < D.d; i += 256) sum += xr[i];
+        for (int i = threadIdx.x; i < D.d; i += 256) sum += ldcf(xr + i);
         sum = wave_sum(sum);
         if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = sum;
         __syncthreads();
         const float mu = (s_red[0] + s_red[1] + s_red[2] + s_red[3]) / D.d;
         float sq = 0.f;
-        for (int i = threadIdx.x; i < D.d; i += 256) { const float t = xr[i] - mu; sq += t * t; }
+        for (int i = threadIdx.x; i < D.d; i += 256) { const float t = ldcf(xr + i) - mu; sq += t * t; }
         sq = wave_sum(sq);
         if ((threadIdx.x & 63) == 0) s_red[4 + (threadIdx.x >> 6)] = sq;
         __syncthreads();
         const float rstd = rsqrtf((s_red[4] + s_red[5] + s_red[6] + s_red[7]) / D.d + LN_EPS);
-        for (int i = threadIdx.x; i < D.d; i += 256) stf(hb + i, (xr[i] - mu) * rstd * s.lnf_g[i] + s.lnf_b[i]);
+        for (int i = threadIdx.x * 2; i < D.d; i += 512) {
+            const float a = (ldcf(xr + i) - mu) * rstd * s.lnf_g[i] + s.lnf_b[i];
+            const float c2 = (ldcf(xr + i + 1) - mu) * rstd * s.lnf_g[i + 1] + s.lnf_b[i + 1];
+            stw32((bf16_t*)hb + i, pack_bf16(a, c2));
+        }
     } else {
         const T* h = (const T*)s.hn + (size_t)r * D.d;
         for (int i = threadIdx.x; i < D.d; i += 256) hb[i] = h[i];
     }
     if (threadIdx.x == 0) {
-        s.root[b] = root;
-        s.L[b] += cnt;
+        stwi(s.root + b, root);
+        stwi(s.L + b, s.L[b] + cnt);
         if (!prefill_mode) {
             int no = s.n_out[b];
             bool fin = false;
             for (int j = 0; j < cnt; ++j) {
-                const int t = tok[path[1 + j]];
-                s.acc_tok[b * (VADUSA_MAX_DRAFT_HEADS + 1) + j] = t;
-                if (no < D.maxpos) s.out_tok[(size_t)b * D.maxpos + no++] = t;
+                const int t = tok[ldci(path + 1 + j)];
+                stwi(s.acc_tok + b * (VADUSA_MAX_DRAFT_HEADS + 1) + j, t);
+                if (no < D.maxpos) stwi(s.out_tok + (size_t)b * D.maxpos + no++, t);
                 if (t == D.V1 - 1) fin = true;
             }
-            s.n_out[b] = no;
-            path[0] = 0;   // consumed
-            if (fin && !ignore_eos) s.finished[b] = 1;
+            stwi(s.n_out + b, no);
+            stwi(path, 0);   // consumed
+            if (fin && !ignore_eos) stwi(s.finished + b, 1);
         }
     }
 }
@@ -162,9 +180,9 @@ __device__ inline void dev_finalize(const Dims& D, const DevState& s, int b, int
 template <class T>
 __device__ inline void dev_commit_kv(const Dims& D, const DevState& s, int layer, int b, int head, int dim) {
     const int32_t* path = s.path + (size_t)b * (VADUSA_MAX_DRAFT_HEADS + 2);
-    const int cnt = s.acc_len[b];
+    const int cnt = ldci(s.acc_len + b);
     if (cnt <= 0) return;
-    const int L0 = s.L[b] - cnt;
+    const int L0 = ldci(s.L + b) - cnt;
     const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
     T* Kh = (T*)s.Kc + hb;
     T* Vh = (T*)s.Vc + hb;
@@ -172,8 +190,9 @@ __device__ inline void dev_commit_kv(const Dims& D, const DevState& s, int layer
 #pragma unroll
     for (int j = 0; j < VADUSA_MAX_DRAFT_HEADS + 1; ++j)
         if (j < cnt) {
-            kr[j] = Kh[(size_t)(L0 + path[1 + j]) * 64 + dim];
-            vr[j] = Vh[(size_t)dim * D.maxpos + L0 + path[1 + j]];
+            const int src = ldci(path + 1 + j);
+            kr[j] = Kh[(size_t)(L0 + src) * 64 + dim];
+            vr[j] = Vh[(size_t)dim * D.maxpos + L0 + src];
         }
 #pragma unroll
     for (int j = 0; j < VADUSA_MAX_DRAFT_HEADS + 1; ++j)
@@ -194,7 +213,7 @@ __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) 
     for (int k = 0; k < kmax; ++k) {
         float bv;
         const int bi = block_argbest(z, D.V1, pv, pi, &bv);
-        if (threadIdx.x == 0) out[k] = bi;
+        if (threadIdx.x == 0) stwi(out + k, bi);
         pv = bv; pi = bi;
     }
 }

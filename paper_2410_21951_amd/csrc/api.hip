@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -57,6 +58,8 @@ extern "C" int vadusa_config_check(const vadusa_config* c, char* msg, size_t n) 
         BAD(VADUSA_ESHAPE, "max_tree_nodes must be <= %d", VADUSA_MAX_TREE_NODES);
     if (c->max_positions <= c->max_tree_nodes)
         BAD(VADUSA_ESHAPE, "max_positions must exceed max_tree_nodes");
+    if (c->max_positions % 8) BAD(VADUSA_ESHAPE, "max_positions must be a multiple of 8");
+    if (c->d_model % 64) BAD(VADUSA_ESHAPE, "d_model must be a multiple of 64");
     if ((int64_t)c->max_batch * c->max_tree_nodes > (1 << 20)) BAD(VADUSA_ESHAPE, "max_batch * max_tree_nodes too large");
 #undef BAD
     return VADUSA_OK;
@@ -110,7 +113,12 @@ struct Carver {
     }
 };
 
-struct WeightSlot { void* dev; size_t rows, cols; int kind; };   // blob order; kind 0 vector, 1 table, 2 linear map
+// blob order; kind 0 vector, 1 table, 2 linear map.  For LayerNorm-folded maps of the bf16 model:
+// gamma/beta of the LayerNorm in front, the map's own bias (or null) and where colsum / t go.
+struct WeightSlot {
+    void* dev; size_t rows, cols; int kind;
+    const float *gamma, *beta, *bias; float *colsum, *tvec;
+};
 
 static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vector<LayerW>* layers,
                      std::vector<DraftW>* draft, std::vector<WeightSlot>* slots, size_t* staging_floats) {
@@ -125,27 +133,43 @@ static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vecto
     size_t biggest = std::max(R * std::max(d, V1), P * d);
     auto mat = [&](const void** dst, size_t rows, size_t cols, int kind = 2) {
         *dst = cv.take((size_t)pad16((int)rows) * cols * e);
-        sl.push_back({(void*)*dst, rows, cols, kind});
+        sl.push_back({(void*)*dst, rows, cols, kind, nullptr, nullptr, nullptr, nullptr, nullptr});
         biggest = std::max(biggest, rows * cols);
     };
     auto vec = [&](const float** dst, size_t n) {
         *dst = (const float*)cv.take(n * 4);
-        sl.push_back({(void*)*dst, 1, n, 0});
+        sl.push_back({(void*)*dst, 1, n, 0, nullptr, nullptr, nullptr, nullptr, nullptr});
     };
     mat(&st.E_text, c.text_vocab, d, 1);
     mat(&st.E_speech, V1, d, 1);
     mat(&st.P, P, d, 1);
+    auto fold = [&](const float* g, const float* b, float** cs, float** t, size_t n) {
+        // call right after mat(): remembers the LayerNorm to fold into that map
+        *cs = (float*)cv.take(n * 4);
+        *t = (float*)cv.take(n * 4);
+        WeightSlot& w = sl.back();
+        w.gamma = g; w.beta = b; w.colsum = *cs; w.tvec = *t;
+    };
     for (int l = 0; l < c.n_layers; ++l) {
         LayerW& w = lw[l];
         vec(&w.ln1_g, d); vec(&w.ln1_b, d);
-        mat(&w.Wqkv, 3 * d, d); vec(&w.bqkv, 3 * d);
+        mat(&w.Wqkv, 3 * d, d);
+        if (c.dtype) fold(w.ln1_g, w.ln1_b, &w.cs_qkv, &w.t_qkv, 3 * d);
+        const size_t iq = sl.size() - 1;
+        vec(&w.bqkv, 3 * d);
+        sl[iq].bias = w.bqkv;
         mat(&w.Wo, d, d); vec(&w.bo, d);
         vec(&w.ln2_g, d); vec(&w.ln2_b, d);
-        mat(&w.W1, F, d); vec(&w.b1, F);
+        mat(&w.W1, F, d);
+        if (c.dtype) fold(w.ln2_g, w.ln2_b, &w.cs_w1, &w.t_w1, F);
+        const size_t i1 = sl.size() - 1;
+        vec(&w.b1, F);
+        sl[i1].bias = w.b1;
         mat(&w.W2, d, F); vec(&w.b2, d);
     }
     vec(&st.lnf_g, d); vec(&st.lnf_b, d);
     mat(&st.W_out, V1, d);
+    if (c.dtype) fold(st.lnf_g, st.lnf_b, &st.cs_out, &st.t_out, V1);
     for (size_t i = 0; i < Hh; ++i) {
         mat(&dw[i].W1, d, d); vec(&dw[i].b1, d); mat(&dw[i].W2, V1, d);
     }
@@ -153,10 +177,19 @@ static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vecto
     st.Kc = cv.take(kv);
     st.Vc = cv.take(kv);
     st.x = (float*)cv.take(R * d * 4);
+    const size_t nslots = c.dtype ? 2 * (size_t)c.n_layers + 1 : 0, per_layer = c.dtype ? c.n_layers : 1;
+    st.act_stride = R * d; st.stats_stride = (d / 16) * R * 2; st.hid_stride = R * F;
+    st.xb = (bf16_t*)cv.take(nslots * R * d * 2);
+    st.stats = (float*)cv.take(nslots * st.stats_stride * 4);
+    st.bar = (uint32_t*)cv.take(4096 * 4);
+    st.kerr = (int32_t*)cv.take(4 * 4);
+    st.tprof = (long long*)cv.take(256 * 8);
+    st.layers_dev = (const LayerW*)cv.take(sizeof(LayerW) * c.n_layers);
+    st.draft_dev = (const DraftW*)cv.take(sizeof(DraftW) * Hh);
     st.xn = cv.take(R * d * e);
-    st.q = cv.take(R * d * e);
-    st.att = cv.take(R * d * e);
-    st.hid = cv.take(R * F * e);
+    st.q = cv.take(per_layer * R * d * e);
+    st.att = cv.take(per_layer * R * d * e);
+    st.hid = cv.take(per_layer * R * F * e);
     st.hn = cv.take(R * d * e);
     st.logits = (float*)cv.take(R * V1 * 4);
     st.hbest = cv.take(B * d * e);
@@ -233,6 +266,22 @@ extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena
     layout(*cfg, c->arena, &c->s, &c->layers, &c->draft, nullptr, &c->staging_floats);
     c->L_ub.assign(cfg->max_batch, 0);
     c->pending.assign(cfg->max_batch, 0);
+    c->epoch = 0;
+    c->persistent = getenv("VADUSA_PHASE_LAUNCHES") ? 0 : 1;
+    {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) { delete c; return VADUSA_EHIP; }
+        c->n_cus = std::min(prop.multiProcessorCount, 1024);
+        // barrier flags and the error flag start at zero; an unwritten KV row must never hold NaN bits
+        const size_t kv = (size_t)cfg->n_layers * cfg->max_batch * cfg->n_heads * cfg->max_positions * 64 * c->elem;
+        hipError_t e0 = hipMemset(c->s.bar, 0, 4096 * 4);
+        if (e0 == hipSuccess) e0 = hipMemset(c->s.tprof, 0, 256 * 8);
+        if (e0 == hipSuccess) e0 = hipMemset(c->s.kerr, 0, 16);
+        if (e0 == hipSuccess) e0 = hipMemset(c->s.Kc, 0, kv);
+        if (e0 == hipSuccess) e0 = hipMemset(c->s.Vc, 0, kv);
+        if (e0 != hipSuccess) { delete c; return VADUSA_EHIP; }
+    }
     // causal table for prefill chunks: row n sees rows 0..n; positions are consecutive
     const int Mm = VADUSA_MAX_TREE_NODES;
     std::vector<int32_t> par(Mm), dep(Mm), rk(Mm, 0);
@@ -283,8 +332,10 @@ extern "C" int vadusa_load_weights(vadusa_ctx* c, const float* blob, size_t n_fl
         }
         if (is_matrix) {
             if (w.kind == 2 && c->cfg.dtype) {
-                // linear maps of the bf16 model are stored in the MFMA-tiled layout
-                launch_pack_w(src, dst, (int)w.rows, (int)w.cols, c->stream);
+                // linear maps of the bf16 model are stored in the MFMA-tiled layout, with the
+                // LayerNorm in front of them (if any) folded in
+                if (w.gamma) launch_pack_w_ln(src, w.gamma, w.beta, dst, w.colsum, w.tvec, (int)w.rows, (int)w.cols, c->stream);
+                else launch_pack_w(src, dst, (int)w.rows, (int)w.cols, c->stream);
             } else {
                 const size_t padded = (size_t)pad16((int)w.rows) * w.cols;
                 if (padded > n)
@@ -293,6 +344,14 @@ extern "C" int vadusa_load_weights(vadusa_ctx* c, const float* blob, size_t n_fl
             }
         }
         off += n;
+    }
+    if (c->cfg.dtype) {
+        for (auto& w : sl)   // t = beta W^T + bias, once every bias has arrived
+            if (w.gamma && w.bias) launch_add_vec(w.tvec, w.bias, (int)w.rows, c->stream);
+        HIP_TRY(c, hipMemcpyAsync((void*)c->s.layers_dev, c->layers.data(), sizeof(LayerW) * c->layers.size(),
+                                  hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync((void*)c->s.draft_dev, c->draft.data(), sizeof(DraftW) * c->draft.size(),
+                                  hipMemcpyHostToDevice, c->stream));
     }
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     HIP_TRY(c, hipGetLastError());
@@ -304,9 +363,29 @@ extern "C" int vadusa_load_weights(vadusa_ctx* c, const float* blob, size_t n_fl
 // forward of B x M rows through the decoder (Sec. 2.1 tree attention; the
 // prefill uses the same path with a causal chunk as the "tree")
 // ---------------------------------------------------------------------------
-static void gemm(vadusa_ctx* c, const GemmArgs& a) {
-    if (c->cfg.dtype) launch_gemm_mfma(a, c->stream);
-    else launch_gemm_simple(a, 0, c->stream);
+static void gemm(vadusa_ctx* c, const GemmArgs& a) { launch_gemm_simple(a, 0, c->stream); }
+
+// bf16 model: run phases [lo, hi) of the step kernel (see k_step.hip)
+static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode, int tau, int lo, int hi,
+                      int seq0, int nseq) {
+    StepParams P;
+    P.D = D; P.s = c->s; P.table = table; P.prefill_mode = prefill_mode; P.tau = tau;
+    P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent;
+    P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq;
+    hipError_t e;
+    launch_step(P, c->n_cus, c->stream, &e);
+    if (e != hipSuccess) return fail(c, VADUSA_EHIP, "step kernel launch failed: %s", hipGetErrorString(e));
+    if (c->persistent) c->epoch += (uint32_t)(hi - lo - 1);
+    return VADUSA_OK;
+}
+
+// After a synchronisation: did a kernel give up at a grid barrier?
+static int check_kerr(vadusa_ctx* c) {
+    if (!c->cfg.dtype) return VADUSA_OK;
+    int32_t k = 0;
+    HIP_TRY(c, hipMemcpy(&k, c->s.kerr, 4, hipMemcpyDeviceToHost));
+    if (k) return fail(c, VADUSA_EHIP, "the step kernel timed out at a grid barrier");
+    return VADUSA_OK;
 }
 
 static void forward(vadusa_ctx* c, const Dims& D, int table, int prefill_mode, bool want_logits) {
@@ -424,13 +503,24 @@ extern "C" int vadusa_prefill(vadusa_ctx* c, int32_t batch, const int32_t* text_
         HIP_TRY(c, hipMemcpyAsync(s.chunk_tok, ctok.data(), ctok.size() * 4, hipMemcpyHostToDevice, c->stream));
         HIP_TRY(c, hipMemcpyAsync(s.n_rows, rows.data(), rows.size() * 4, hipMemcpyHostToDevice, c->stream));
         const bool last = ch == max_chunks - 1;
-        forward(c, D, 1, 1, last);
+        if (c->cfg.dtype) {
+            // bf16 model: the chunk is a causal "tree" for the step kernel; the last chunk also runs
+            // the base head, the continuation and the draft heads (acceptance has no units here)
+            const int H = 1 + 5 * D.Ly;
+            int rc = run_phases(c, D, 1, 1, 1, 0, last ? H + 6 : H, 0, batch);
+            if (rc) return rc;
+        } else {
+            forward(c, D, 1, 1, last);
+        }
         if (!last) launch_advance(s, batch, c->stream);
     }
-    launch_finalize(D, s, 0, batch, 1, c->cfg.ignore_eos, c->cfg.dtype, c->stream);
-    draft_heads(c, D, 0, batch);
+    if (!c->cfg.dtype) {
+        launch_finalize(D, s, 0, batch, 1, c->cfg.ignore_eos, c->cfg.dtype, c->stream);
+        draft_heads(c, D, 0, batch);
+    }
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     HIP_TRY(c, hipGetLastError());
+    { int rc = check_kerr(c); if (rc) return rc; }
     if (first_root) HIP_TRY(c, hipMemcpy(first_root, s.root, B * 4, hipMemcpyDeviceToHost));
     c->batch = batch;
     c->state = 2;
@@ -463,7 +553,22 @@ static int upload_tree(vadusa_ctx* c, const vadusa_tree_spec* t, const std::vect
     return VADUSA_OK;
 }
 
-extern "C" int vadusa_verify(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau, const int32_t* draft_override) {
+static void mark_compacted(vadusa_ctx* c, int seq0, int nseq, int n_forced) {
+    bool any = false;
+    for (int b = 0; b < c->batch; ++b) {
+        if (b >= seq0 && b < seq0 + nseq && c->pending[b]) {
+            c->pending[b] = 0;
+            c->L_ub[b] += (n_forced ? n_forced : std::min(c->cfg.n_draft_heads + 1, c->M));
+        }
+        any |= c->pending[b] != 0;
+    }
+    if (!any) c->state = 2;
+}
+
+// Verification; with fuse_compact the compaction of every sequence's chosen path and the
+// draft heads follow in the same launch (bf16 model) or right behind (fp32 model).
+static int verify_impl(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau, const int32_t* draft_override,
+                       bool fuse_compact) {
     if (!c) return VADUSA_EINVAL;
     if (c->state != 2) return fail(c, VADUSA_ESTATE, c->state == 3 ? "a verification is still waiting for vadusa_kv_compact" : "prefill first");
     if (tau < 1) return fail(c, VADUSA_EINVAL, "tau must be >= 1 (got %d)", tau);
@@ -498,13 +603,29 @@ extern "C" int vadusa_verify(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_
         HIP_TRY(c, hipStreamSynchronize(c->stream));   // the caller's buffer is not kept
     }
     const Dims D = make_dims(c, B, M);
-    forward(c, D, 0, 0, true);
-    launch_accept(D, s, tau, c->cfg.ignore_eos, c->stream);
-    HIP_TRY(c, hipGetLastError());
     c->M = M;
+    if (c->cfg.dtype) {
+        const int H = 1 + 5 * D.Ly;
+        rc = run_phases(c, D, 0, 0, tau, 0, fuse_compact ? H + 6 : H + 2, 0, B);
+        if (rc) return rc;
+    } else {
+        forward(c, D, 0, 0, true);
+        launch_accept(D, s, tau, c->cfg.ignore_eos, c->stream);
+        if (fuse_compact) {
+            launch_finalize(D, s, 0, B, 0, c->cfg.ignore_eos, 0, c->stream);
+            launch_commit_kv(D, s, 0, B, 0, c->stream);
+            draft_heads(c, D, 0, B);
+        }
+        HIP_TRY(c, hipGetLastError());
+    }
     c->state = 3;
     for (int b = 0; b < B; ++b) c->pending[b] = 1;
+    if (fuse_compact) mark_compacted(c, 0, B, 0);
     return VADUSA_OK;
+}
+
+extern "C" int vadusa_verify(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau, const int32_t* draft_override) {
+    return verify_impl(c, tree, tau, draft_override, false);
 }
 
 extern "C" int vadusa_kv_compact(vadusa_ctx* c, int32_t seq, const int32_t* path_nodes, int32_t n) {
@@ -534,19 +655,17 @@ extern "C" int vadusa_kv_compact(vadusa_ctx* c, int32_t seq, const int32_t* path
             HIP_TRY(c, hipStreamSynchronize(c->stream));
         }
     }
-    launch_finalize(D, s, seq0, nseq, 0, c->cfg.ignore_eos, c->cfg.dtype, c->stream);
-    launch_commit_kv(D, s, seq0, nseq, c->cfg.dtype, c->stream);
-    draft_heads(c, D, seq0, nseq);
-    HIP_TRY(c, hipGetLastError());
-    bool any = false;
-    for (int b = 0; b < B; ++b) {
-        if (b >= seq0 && b < seq0 + nseq && c->pending[b]) {
-            c->pending[b] = 0;
-            c->L_ub[b] += (path_nodes ? n : std::min(c->cfg.n_draft_heads + 1, c->M));
-        }
-        any |= c->pending[b] != 0;
+    if (c->cfg.dtype) {
+        const int H = 1 + 5 * D.Ly;
+        int rc = run_phases(c, D, 0, 0, 1, H + 2, H + 6, seq0, nseq);
+        if (rc) return rc;
+    } else {
+        launch_finalize(D, s, seq0, nseq, 0, c->cfg.ignore_eos, 0, c->stream);
+        launch_commit_kv(D, s, seq0, nseq, 0, c->stream);
+        draft_heads(c, D, seq0, nseq);
+        HIP_TRY(c, hipGetLastError());
     }
-    if (!any) c->state = 2;
+    mark_compacted(c, seq0, nseq, path_nodes ? n : 0);
     return VADUSA_OK;
 }
 
@@ -555,14 +674,14 @@ extern "C" int vadusa_step(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t 
     if (!c) return VADUSA_EINVAL;
     if ((accepted_tok == nullptr) != (accepted_len == nullptr))
         return fail(c, VADUSA_EINVAL, "accepted_tok and accepted_len must both be given or both be null");
-    int rc = vadusa_verify(c, tree, tau, draft_override);
-    if (rc) return rc;
-    rc = vadusa_kv_compact(c, -1, nullptr, 0);
+    int rc = verify_impl(c, tree, tau, draft_override, true);
     if (rc) return rc;
     if (accepted_tok) {
         const int B = c->batch, W = VADUSA_MAX_DRAFT_HEADS + 1, Hh1 = c->cfg.n_draft_heads + 1;
         std::vector<int32_t> tok((size_t)B * W), len(B), L(B);
         HIP_TRY(c, hipStreamSynchronize(c->stream));
+        rc = check_kerr(c);
+        if (rc) return rc;
         HIP_TRY(c, hipMemcpy(tok.data(), c->s.acc_tok, tok.size() * 4, hipMemcpyDeviceToHost));
         HIP_TRY(c, hipMemcpy(len.data(), c->s.acc_len, B * 4, hipMemcpyDeviceToHost));
         HIP_TRY(c, hipMemcpy(L.data(), c->s.L, B * 4, hipMemcpyDeviceToHost));
@@ -580,6 +699,7 @@ extern "C" int vadusa_read_output(vadusa_ctx* c, int32_t seq, int32_t* tok, int3
     if (c->state < 2) return fail(c, VADUSA_ESTATE, "prefill first");
     if (seq < 0 || seq >= c->batch || !n_out) return fail(c, VADUSA_EINVAL, "bad seq or null n_out");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    { int rc = check_kerr(c); if (rc) return rc; }
     int32_t n = 0;
     HIP_TRY(c, hipMemcpy(&n, c->s.n_out + seq, 4, hipMemcpyDeviceToHost));
     *n_out = n;
@@ -610,9 +730,12 @@ extern "C" int vadusa_debug_read(vadusa_ctx* c, int32_t what, void* host, size_t
     case VADUSA_DBG_ROOT: src = s.root; need = B * 4; break;
     case VADUSA_DBG_EDGE_OK: src = s.edge_ok; need = B * M * 4; break;
     case VADUSA_DBG_FINISHED: src = s.finished; need = B * 4; break;
+    case VADUSA_DBG_PHASE_CLOCK: src = s.tprof; need = 256 * 8; break;
     case VADUSA_DBG_H_NODES: {
         need = B * M * d * 4;
         if (bytes != need) return fail(c, VADUSA_EINVAL, "expected %zu bytes", need);
+        if (c->cfg.dtype)   // the step kernel keeps no node states: recompute them from the residual stream
+            launch_layernorm(s.x, s.lnf_g, s.lnf_b, s.hn, (int)(B * M), (int)d, 1, c->stream);
         launch_to_float(s.hn, s.staging, B * M * d, c->cfg.dtype, c->stream);
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         HIP_TRY(c, hipMemcpy(host, s.staging, need, hipMemcpyDeviceToHost));

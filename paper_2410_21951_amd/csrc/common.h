@@ -24,6 +24,31 @@ __device__ __forceinline__ float ldf(const bf16_t* p) { return bf2f(*p); }
 __device__ __forceinline__ void stf(float* p, float v) { *p = v; }
 __device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f2bf(v); }
 
+// Stores / loads that are coherent across the whole GPU without cache maintenance
+// (write-through to / read from the memory side).  The persistent step kernel uses them
+// for every value that crosses workgroups inside one launch.
+__device__ __forceinline__ void stw32(void* p, uint32_t v) {
+    __hip_atomic_store((uint32_t*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void stw64(void* p, uint64_t v) {
+    __hip_atomic_store((uint64_t*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void stw16(void* p, uint16_t v) {
+    __hip_atomic_store((uint16_t*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void stwi(int32_t* p, int32_t v) { stw32(p, (uint32_t)v); }
+__device__ __forceinline__ void stwf(float* p, float v) { stw32(p, __float_as_uint(v)); }
+__device__ __forceinline__ void stwf2(float* p, float a, float b) {
+    stw64(p, (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32));
+}
+__device__ __forceinline__ int32_t ldci(const int32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ldcf(const float* p) {
+    return __uint_as_float(__hip_atomic_load((const uint32_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) { return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16); }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -70,14 +95,20 @@ struct DevState {
     void *Kc, *Vc;
     // activations
     float* x;        // [R][d]  residual stream
-    bf16_t* xb;      // [R][d]  bf16 copy of the residual stream (bf16 model)
-    float* stats[2]; // [d/16][R][2] per 16-column tile: mean and sum of squared deviations
-    uint32_t* flags; // [1024] grid-barrier flags of the persistent step kernel
+    // bf16 model, persistent step kernel.  Buffers that cross workgroups are written once
+    // per launch, so there is one instance per producer: xb / stats have 2*Ly+1 slots
+    // (embedding, then after the out-projection and after FFN2 of every layer), q / att /
+    // hid one slot per layer.  Slot strides are in elements.
+    bf16_t* xb;      // [2Ly+1][R][d]  bf16 copy of the residual stream
+    float* stats;    // [2Ly+1][d/16][R][2] per 16-column tile: mean, sum of squared deviations
+    size_t act_stride, stats_stride, hid_stride;
+    uint32_t* bar;   // grid barrier: [0..16*64) group counters, [1024] top counter, [2048 + 16*64) release flags
     int32_t* kerr;   // [4] error flag raised by a kernel (barrier time-out)
+    long long* tprof; // [256] device clock at the start of every phase of the last launch (100 MHz)
     void* xn;        // [R][d]  LayerNorm output
-    void* q;         // [R][d]
-    void* att;       // [R][d]
-    void* hid;       // [R][F]
+    void* q;         // [R][d]   (bf16 model: one slot per layer)
+    void* att;       // [R][d]   (bf16 model: one slot per layer)
+    void* hid;       // [R][F]   (bf16 model: one slot per layer)
     void* hn;        // [R][d]  final-LayerNorm'd node states
     float* logits;   // [R][V1]
     void* hbest;     // [Bmax][d]
@@ -111,6 +142,9 @@ struct vadusa_ctx {
     std::vector<char> pending;   // per sequence: verification waits for compaction
     std::vector<int32_t> tree_parent, tree_rank, tree_depth;   // last uploaded tree
     size_t staging_floats;
+    int n_cus;                   // workgroups of the persistent step kernel (one per compute unit)
+    int persistent;              // 0: one launch per phase (debugging aid)
+    uint32_t epoch;              // grid-barrier epoch reached so far
     std::string err;
 };
 
@@ -153,14 +187,14 @@ struct StepParams {
 int step_num_phases(int n_layers);
 // phase index helpers: 0 embed; 1+5l.. layer l (qkv, attn, wo, ffn1, ffn2); then head, accept, finalize, commit+draft1, draft2, topk
 void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err);
-void launch_pack_w_ln(const float* src, const float* gamma, const float* beta, const float* bias, void* dst,
-                      float* colsum, float* tvec, int N, int K, hipStream_t st);
+void launch_pack_w_ln(const float* src, const float* gamma, const float* beta, void* dst, float* colsum,
+                      float* tvec, int N, int K, hipStream_t st);
+void launch_add_vec(float* dst, const float* src, int n, hipStream_t st);
 
 // ---- launch wrappers (each enqueues on `st`, no synchronisation) ----
 void launch_embed(const Dims& D, const DevState& s, int dtype, int prefill_mode, int table, hipStream_t st);
 void launch_layernorm(const float* x, const float* g, const float* b, void* out, int R, int d, int dtype, hipStream_t st);
 void launch_gemm_simple(const GemmArgs& a, int dtype, hipStream_t st);
-void launch_gemm_mfma(const GemmArgs& a, hipStream_t st);
 void launch_pack_w(const float* src, void* dst, int N, int K, hipStream_t st);
 void launch_attn_simple(const Dims& D, const DevState& s, int layer, int table, int dtype, hipStream_t st);
 void launch_accept(const Dims& D, const DevState& s, int tau, int ignore_eos, hipStream_t st);

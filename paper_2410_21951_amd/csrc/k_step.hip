@@ -1,0 +1,730 @@
+// The speculative step of the bf16 model as ONE persistent kernel.
+//
+// A step is a fixed sequence of phases; every phase is a set of independent
+// units that the workgroups of the grid take round-robin, and a grid barrier
+// separates dependent phases.  Phases:
+//   0                 embed: tree expansion + token/position embedding (Sec. 2.1)
+//   1+5l .. 5+5l      layer l: QKV, attention, out-projection, FFN1, FFN2
+//   H = 1+5*Ly        base head (logits of every node; Algorithm 1 line 1)
+//   H+1               acceptance: Algorithm 1 on all edges + Sec. 2.3 path choice
+//   H+2               continuation from the last accepted node (Sec. 2.1)
+//   H+3               KV compaction to the accepted path || draft heads, first map
+//   H+4               draft heads, vocabulary map
+//   H+5               draft top-k lists
+//
+// Linear maps stream pre-tiled bf16 weights straight from HBM into the B
+// operand of v_mfma_f32_16x16x32_bf16; activations are staged in LDS.
+// LayerNorm is folded into the map that follows it:
+//   LN(x) W^T = rstd * (x (g*W)^T - mu * colsum(g*W)) + (beta W^T + bias),
+// so the map reads the bf16 copy of the raw residual stream and applies the
+// row statistics in its epilogue.  The statistics are produced, per 16-column
+// tile, by whoever wrote the residual stream (exact fp32 values), and merged
+// by the consumer (pairwise mean / sum-of-squared-deviations merge).
+// No atomics combine data: results are bit-reproducible.
+//
+// Coherence inside the one launch: the eight XCDs have private L2 caches and a
+// cache write-back / invalidate at every barrier costs several microseconds.
+// Instead every value that crosses workgroups is stored write-through (agent
+// scope) into a buffer that is written exactly once per launch and was never
+// read before in this launch (one activation slot per layer), so a plain cached
+// load after the barrier can only miss and fetch the fresh line.  Values that
+// are re-read after having been cached (L, the residual row of the accepted
+// node) are loaded at agent scope.
+#include <algorithm>
+
+#include "accept_dev.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+#define ST_TILE_BYTES (64 * 1032 * 2)        // 64 rows x (1024 + 8) bf16 == 16 rows x (4096 + 8) bf16
+#define ST_LDS_BYTES (ST_TILE_BYTES + 1024)  // + row statistics
+#define ST_SPIN_LIMIT (1 << 22)
+
+enum { SE_QKV = 0, SE_GELU, SE_LOGITS, SE_RESID, SE_SILU_RESID, SE_F32 };
+
+struct GemmD {
+    const bf16_t* X;      // [R][K]
+    int K, N, R;
+    const uint4* Wp;      // packed weights
+    const float* bias;    // [N] or null (LN-folded maps: beta W^T + bias)
+    const float* colsum;  // [N], LN-folded maps only
+    const float* stats;   // [K/16][R][2] statistics of X's rows, or null: no LayerNorm
+    int epi;
+    bf16_t* out;          // SE_GELU / SE_SILU_RESID / SE_QKV (q)
+    float* outf;          // SE_LOGITS / SE_F32
+    float* stats_out;     // SE_RESID
+    int layer;
+};
+
+__device__ __forceinline__ float gelu_s(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752f)); }
+__device__ __forceinline__ float silu_s(float v) { return v / (1.f + __expf(-v)); }
+
+// ---------------------------------------------------------------------------
+// phase bookkeeping (host and device)
+// ---------------------------------------------------------------------------
+__host__ __device__ inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+int step_num_phases(int n_layers) { return 1 + 5 * n_layers + 6; }
+
+__host__ __device__ inline int phase_units(const StepParams& P, int ph) {
+    const Dims& D = P.D;
+    const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
+    if (ph == 0) return R;
+    if (ph < H) {
+        switch ((ph - 1) % 5) {
+        case 0: return (3 * D.d / 16) * RG;
+        case 1: return D.B * D.nH * cdiv(D.M, 16);
+        case 2: return (D.d / 16) * RB;
+        case 3: return (D.F / 16) * RG;
+        default: return (D.d / 16) * RB;
+        }
+    }
+    const int RGb = cdiv(P.nseq, 64);
+    switch (ph - H) {
+    case 0: return cdiv(D.V1, 16) * RG;
+    case 1: return P.prefill_mode ? 0 : D.B;
+    case 2: return P.nseq;
+    case 3: return D.Ly * D.nH * P.nseq + D.Hh * (D.d / 16) * RGb;
+    case 4: return D.Hh * cdiv(D.V1, 16) * RGb;
+    default: return D.Hh * P.nseq;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// grid barrier, two levels, no cache maintenance (see the coherence note above):
+// workgroups arrive on one of 16 group counters; the last of a group arrives on
+// the top counter, waits for all groups and releases its group through a flag.
+// All counters grow monotonically (epoch = number of barriers so far).
+// Bounded: after ST_SPIN_LIMIT polls, or when another workgroup has raised the
+// error flag, the workgroup gives up and the kernel ends (the host reports it).
+// ---------------------------------------------------------------------------
+#define BAR_GROUPS 16
+__device__ bool grid_sync(const StepParams& P, uint32_t epoch) {
+    __shared__ int s_ok;
+    __syncthreads();   // every wave's stores have completed (write-through: at the memory side)
+    if (threadIdx.x == 0) {
+        uint32_t* bar = P.s.bar;
+        const int g = blockIdx.x % BAR_GROUPS;
+        const uint32_t members = (gridDim.x - g + BAR_GROUPS - 1) / BAR_GROUPS;
+        const uint32_t ngroups = gridDim.x < BAR_GROUPS ? gridDim.x : BAR_GROUPS;
+        int ok = 1, spins = 0;
+        const uint32_t old = __hip_atomic_fetch_add(&bar[g * 64], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old + 1 == epoch * members) {
+            __hip_atomic_fetch_add(&bar[1024], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            while ((int32_t)(__hip_atomic_load(&bar[1024], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch * ngroups) < 0) {
+                if (++spins > ST_SPIN_LIMIT || ((spins & 255) == 0 && ldci(P.s.kerr) != 0)) { ok = 0; break; }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (ok) __hip_atomic_store(&bar[2048 + g * 64], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            while ((int32_t)(__hip_atomic_load(&bar[2048 + g * 64], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) < 0) {
+                if (++spins > ST_SPIN_LIMIT || ((spins & 255) == 0 && ldci(P.s.kerr) != 0)) { ok = 0; break; }
+                __builtin_amdgcn_s_sleep(1);
+            }
+        }
+        if (!ok) stwi(P.s.kerr, 1);
+        s_ok = ok;
+    }
+    __syncthreads();
+    return s_ok != 0;
+}
+
+// ---------------------------------------------------------------------------
+// embed (phase 0): one unit per row.  Writes x (fp32), its bf16 copy and the
+// per-tile row statistics.
+// ---------------------------------------------------------------------------
+__device__ void embed_unit(const StepParams& P, int r) {
+    const Dims& D = P.D;
+    const DevState& s = P.s;
+    const int b = r / D.M, n = r % D.M, tid = threadIdx.x;
+    int rows;
+    if (P.prefill_mode) rows = s.n_rows[b];
+    else rows = s.finished[b] ? 0 : D.M;
+    if (!P.prefill_mode && n == 0 && tid == 0) stwi(s.n_rows + b, rows);
+    const bool valid = n < rows;
+    int tok = 0, pos = 0;
+    const bf16_t* E = (const bf16_t*)s.E_speech;
+    if (valid) {
+        if (P.prefill_mode) {
+            const int t = s.chunk_tok[r];
+            pos = s.L[b] + n;
+            if (t < 0) { tok = -t - 1; E = (const bf16_t*)s.E_text; }
+            else tok = t;
+        } else {
+            const int dep = s.t_depth[P.table][n];
+            pos = s.L[b] + dep;
+            tok = n == 0 ? s.root[b]
+                         : s.draft_topk[((size_t)b * D.Hh + (dep - 1)) * VADUSA_MAX_TOPK + s.t_rank[P.table][n]];
+        }
+        if (pos >= D.maxpos) pos = D.maxpos - 1;   // the host checks capacity before launching
+    }
+    if (tid == 0) stwi(s.tok + r, tok);
+    const bf16_t* e = E + (size_t)tok * D.d;
+    const bf16_t* p = (const bf16_t*)s.P + (size_t)pos * D.d;
+    float* x = s.x + (size_t)r * D.d;
+    bf16_t* xb = s.xb + (size_t)r * D.d;   // slot 0
+    float* st = s.stats;                    // slot 0
+    const int R = D.B * D.M;
+    for (int c0 = tid * 4; c0 < D.d; c0 += 1024) {
+        float v[4];
+        const uint2 ev = *(const uint2*)(e + c0), pv = *(const uint2*)(p + c0);
+        v[0] = bf2f((bf16_t)ev.x) + bf2f((bf16_t)pv.x);
+        v[1] = bf2f((bf16_t)(ev.x >> 16)) + bf2f((bf16_t)(pv.x >> 16));
+        v[2] = bf2f((bf16_t)ev.y) + bf2f((bf16_t)pv.y);
+        v[3] = bf2f((bf16_t)(ev.y >> 16)) + bf2f((bf16_t)(pv.y >> 16));
+        if (!valid) v[0] = v[1] = v[2] = v[3] = 0.f;
+        float sum = v[0] + v[1] + v[2] + v[3];
+        sum += __shfl_xor(sum, 1, 64);
+        sum += __shfl_xor(sum, 2, 64);
+        const float mean = sum * (1.f / 16.f);
+        float m2 = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { const float t = v[j] - mean; m2 += t * t; }
+        m2 += __shfl_xor(m2, 1, 64);
+        m2 += __shfl_xor(m2, 2, 64);
+        stwf2(x + c0, v[0], v[1]);
+        stwf2(x + c0 + 2, v[2], v[3]);
+        stw64(xb + c0, (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32));
+        if ((tid & 3) == 0) stwf2(st + ((size_t)(c0 >> 4) * R + r) * 2, mean, m2);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// linear-map unit.  NRT = 4: 64 rows x one 16-column tile, K <= 1024 per LDS
+// chunk (QKV, FFN1, heads).  NRT = 1: 16 rows x one tile, K <= 4096 per chunk
+// (out-projection, FFN2: residual update + statistics of the new rows).
+// The four waves split the k-steps round-robin; partial sums are combined in
+// wave order through LDS.
+// ---------------------------------------------------------------------------
+template <int NRT>
+__device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0, uint4* smem, float* s_stat) {
+    constexpr int KC = NRT == 4 ? 1024 : 4096;
+    constexpr int LDV = KC / 8 + 1;
+    constexpr int ROWS = NRT * 16;
+    const Dims& D = P.D;
+    const DevState& s = P.s;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, gq = lane >> 4, c = lane & 15;
+    const int nks = g.K >> 5;
+    const uint4* Wp = g.Wp + (size_t)nt * nks * 64 + lane;
+    f32x4_t acc[NRT];
+#pragma unroll
+    for (int i = 0; i < NRT; ++i) acc[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+
+    for (int kc0 = 0; kc0 < g.K; kc0 += KC) {
+        const int kcl = min(KC, g.K - kc0);
+        const int ks0 = kc0 >> 5, ksn = kcl >> 5;
+        uint4 bw[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int ks = wave + 4 * i;
+            bw[i] = ks < ksn ? Wp[(size_t)(ks0 + ks) * 64] : make_uint4(0, 0, 0, 0);
+        }
+        __syncthreads();   // earlier users of the LDS tile are done
+        const int v8 = kcl >> 3, total = ROWS * v8;
+        for (int base = tid; base < total; base += 256 * 8) {
+            uint4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int idx = base + j * 256;
+                v[j] = make_uint4(0, 0, 0, 0);
+                if (idx < total) {
+                    const int row = idx / v8, col = idx - row * v8;
+                    if (row0 + row < g.R) v[j] = *(const uint4*)(g.X + (size_t)(row0 + row) * g.K + kc0 + col * 8);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int idx = base + j * 256;
+                if (idx < total) {
+                    const int row = idx / v8, col = idx - row * v8;
+                    smem[row * LDV + col] = v[j];
+                }
+            }
+        }
+        if (kc0 == 0 && g.stats && tid < ROWS * 4) {
+            // row statistics: four threads per row, each merges a quarter of the tiles
+            const int row = tid >> 2, part = tid & 3, r = row0 + row, tiles = g.K >> 4;
+            float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            if (r < g.R) {
+                const float2* sp = (const float2*)g.stats + r;
+                for (int t0 = part; t0 < tiles; t0 += 32) {
+                    float2 v[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const int t = t0 + 4 * j;
+                        v[j] = t < tiles ? sp[(size_t)t * g.R] : make_float2(0.f, 0.f);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) { s1 += v[j].x; s2 += v[j].y; s3 += v[j].x * v[j].x; }
+                }
+            }
+            s1 += __shfl_xor(s1, 1, 64); s1 += __shfl_xor(s1, 2, 64);
+            s2 += __shfl_xor(s2, 1, 64); s2 += __shfl_xor(s2, 2, 64);
+            s3 += __shfl_xor(s3, 1, 64); s3 += __shfl_xor(s3, 2, 64);
+            if (part == 0) {
+                // mean of tile means; M2 = sum M2_t + 16 sum (mean_t - mean)^2
+                const float mean = s1 / tiles;
+                const float m2 = s2 + 16.f * fmaxf(s3 - tiles * mean * mean, 0.f);
+                s_stat[row] = mean;
+                s_stat[64 + row] = rsqrtf(m2 / g.K + LN_EPS);
+            }
+        }
+        __syncthreads();
+        for (int i0 = 0; wave + 4 * i0 < ksn; i0 += 8) {
+            uint4 bn[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int ks = wave + 4 * (i0 + 8 + i);
+                bn[i] = ks < ksn ? Wp[(size_t)(ks0 + ks) * 64] : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int ks = wave + 4 * (i0 + i);
+                if (ks < ksn) {
+                    const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bw[i]);
+#pragma unroll
+                    for (int rt = 0; rt < NRT; ++rt) {
+                        const uint4 av = smem[(rt * 16 + c) * LDV + ks * 4 + gq];
+                        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av), bfrag,
+                                                                          acc[rt], 0, 0, 0);
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) bw[i] = bn[i];
+        }
+    }
+    __syncthreads();
+    float* red = (float*)smem;   // [wave][rt][lane][4]
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) red[((wave * NRT + rt) * 64 + lane) * 4 + i] = acc[rt][i];
+    __syncthreads();
+
+    if (NRT == 4) {
+        const int row = tid >> 2, rt = row >> 4, rr = row & 15, r = row0 + row;
+        const int n0 = nt * 16 + (tid & 3) * 4;       // four consecutive output columns
+        if (r < g.R && n0 < g.N) {
+            const float mu = g.stats ? s_stat[row] : 0.f, rstd = g.stats ? s_stat[64 + row] : 1.f;
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = (tid & 3) * 4 + j, n = n0 + j;
+                const int src = ((rt * 64) + (rr >> 2) * 16 + col) * 4 + (rr & 3);
+                float a = red[src];
+#pragma unroll
+                for (int w = 1; w < 4; ++w) a += red[w * 1024 + src];
+                if (n < g.N) {
+                    if (g.stats) a = rstd * (a - mu * g.colsum[n]);
+                    if (g.bias) a += g.bias[n];
+                }
+                v[j] = a;
+            }
+            const bool full = n0 + 3 < g.N;   // only the vocabulary maps have a ragged last tile
+            switch (g.epi) {
+            case SE_GELU:
+                stw64(g.out + (size_t)r * g.N + n0,
+                      (uint64_t)pack_bf16(gelu_s(v[0]), gelu_s(v[1])) | ((uint64_t)pack_bf16(gelu_s(v[2]), gelu_s(v[3])) << 32));
+                break;
+            case SE_LOGITS:
+            case SE_F32:
+                // rows of V+1 floats are only 4-byte aligned: single-word write-through stores
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (full || n0 + j < g.N) stwf(g.outf + (size_t)r * g.N + n0 + j, v[j]);
+                break;
+            case SE_SILU_RESID: {
+                const uint2 xin = *(const uint2*)(g.X + (size_t)r * g.K + n0);
+                const float h0 = bf2f((bf16_t)xin.x) + silu_s(v[0]), h1 = bf2f((bf16_t)(xin.x >> 16)) + silu_s(v[1]);
+                const float h2 = bf2f((bf16_t)xin.y) + silu_s(v[2]), h3 = bf2f((bf16_t)(xin.y >> 16)) + silu_s(v[3]);
+                stw64(g.out + (size_t)r * g.N + n0, (uint64_t)pack_bf16(h0, h1) | ((uint64_t)pack_bf16(h2, h3) << 32));
+                break;
+            }
+            case SE_QKV: {
+                const uint64_t pk = (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32);
+                if (n0 < D.d) { stw64(g.out + (size_t)r * D.d + n0, pk); break; }
+                const int b = r / D.M, node = r - b * D.M;
+                const int which = n0 / D.d - 1, cc = n0 % D.d, head = cc >> 6, dim = cc & 63;
+                const int pos = s.L[b] + node;
+                if (pos < D.maxpos && s.n_rows[b] > 0) {
+                    const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
+                    if (which) {
+                        bf16_t* vp = (bf16_t*)s.Vc + hb + (size_t)dim * D.maxpos + pos;   // V is kept [dim][pos]
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) stw16(vp + (size_t)j * D.maxpos, f2bf(v[j]));
+                    } else {
+                        stw64((bf16_t*)s.Kc + hb + (size_t)pos * 64 + dim, pk);             // K is kept [pos][dim]
+                    }
+                }
+                break;
+            }
+            default: break;
+            }
+        }
+    } else {
+        // residual update: one element per thread, statistics over the 16 columns of the tile
+        const int row = tid >> 4, col = tid & 15, r = row0 + row, n = nt * 16 + col;
+        const int src = ((row >> 2) * 16 + col) * 4 + (row & 3);
+        float v = red[src];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) v += red[w * 256 + src];
+        const bool ok = r < g.R;
+        float xn = 0.f;
+        if (ok) {
+            xn = s.x[(size_t)r * g.N + n] + v + g.bias[n];
+            stwf(s.x + (size_t)r * g.N + n, xn);
+        }
+        {
+            const float nb = __shfl_down(xn, 1, 64);   // pair of columns -> one 32-bit store
+            if (ok && !(col & 1)) stw32(g.out + (size_t)r * g.N + n, pack_bf16(xn, nb));
+        }
+        float sum = xn;
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 64);
+        const float mean = sum * (1.f / 16.f);
+        float m2 = (xn - mean) * (xn - mean);
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) m2 += __shfl_xor(m2, o, 64);
+        if (ok && col == 0) stwf2(g.stats_out + ((size_t)nt * g.R + r) * 2, mean, m2);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// tree-masked attention unit (Sec. 2.1): one head, 16 query rows of one
+// sequence.  Keys: cache positions [0, L) and the rows of this forward at
+// L + m where the query's mask bit m is set.  The four waves take 32-key blocks
+// round-robin with a private online softmax (S^T = K Q^T, O^T += V^T P^T on
+// MFMA), then merge through LDS.  K is kept [pos][64], V is kept [64][pos].
+// ---------------------------------------------------------------------------
+__device__ void attn_unit(const StepParams& P, int layer, int u, uint4* smem) {
+    const Dims& D = P.D;
+    const DevState& s = P.s;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, gq = lane >> 4, c = lane & 15;
+    const int QT = cdiv(D.M, 16);
+    const int qt = u % QT, h = (u / QT) % D.nH, b = u / (QT * D.nH);
+    const int n_rows = s.n_rows[b];
+    bf16_t* att = (bf16_t*)s.att + (size_t)layer * s.act_stride;
+    if (n_rows == 0) {
+        const int q = tid >> 4, d0 = (tid & 15) * 4, node = qt * 16 + q;
+        if (node < D.M) stw64(att + ((size_t)(b * D.M + node)) * D.d + h * 64 + d0, 0ull);
+        return;
+    }
+    const int L = s.L[b];
+    const int T = min(L + D.M, D.maxpos);
+    const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + h) * D.maxpos) * 64;
+    const bf16_t* Kh = (const bf16_t*)s.Kc + hb;
+    const bf16_t* Vh = (const bf16_t*)s.Vc + hb;
+    const int node = min(qt * 16 + c, D.M - 1);
+    const bf16_t* qp = (const bf16_t*)s.q + (size_t)layer * s.act_stride + ((size_t)(b * D.M + node)) * D.d + h * 64;
+    const bf16x8_t Q0 = __builtin_bit_cast(bf16x8_t, *(const uint4*)(qp + 8 * gq));
+    const bf16x8_t Q1 = __builtin_bit_cast(bf16x8_t, *(const uint4*)(qp + 32 + 8 * gq));
+    const uint4 mw = *(const uint4*)(s.t_mask[P.table] + (size_t)node * MASK_WORDS);
+    const uint32_t mword[4] = {mw.x, mw.y, mw.z, mw.w};
+
+    float m_run = -1e30f, l_run = 0.f;
+    f32x4_t O[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) O[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    const int nblk = (T + 31) >> 5;
+    // operands of one 32-key block: K rows of the two 16-key tiles (two k-steps each), V^T tiles
+    auto load_block = [&](int blk, uint4* kv /*[8]*/) {
+        const int p0 = blk << 5;
+        const int keyA = p0 + 8 * (c >> 2) + (c & 3), keyB = keyA + 4;
+        const bf16_t* ka = Kh + (size_t)(keyA < T ? keyA : 0) * 64 + 8 * gq;
+        const bf16_t* kb = Kh + (size_t)(keyB < T ? keyB : 0) * 64 + 8 * gq;
+        kv[0] = *(const uint4*)ka; kv[1] = *(const uint4*)(ka + 32);
+        kv[2] = *(const uint4*)kb; kv[3] = *(const uint4*)(kb + 32);
+        const int v0 = p0 + 8 * gq, vv = v0 < T ? v0 : 0;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) kv[4 + dt] = *(const uint4*)(Vh + (size_t)(dt * 16 + c) * D.maxpos + vv);
+    };
+    uint4 cur[8], nxt[8];
+    if (wave < nblk) load_block(wave, cur);
+    for (int blk = wave; blk < nblk; blk += 4) {
+        if (blk + 4 < nblk) load_block(blk + 4, nxt);   // in flight while this block is computed
+        const int p0 = blk << 5;
+        const int v0 = p0 + 8 * gq;
+        const uint4 a0 = cur[0], a1 = cur[1], b0 = cur[2], b1 = cur[3];
+        uint4 vt[4];
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) vt[dt] = cur[4 + dt];
+        f32x4_t sa = (f32x4_t){0.f, 0.f, 0.f, 0.f}, sb = sa;
+        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a0), Q0, sa, 0, 0, 0);
+        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a1), Q1, sa, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, b0), Q0, sb, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, b1), Q1, sb, 0, 0, 0);
+        // this lane: query c, keys v0 + 0..3 (sa) and v0 + 4..7 (sb)
+        float sc[8];
+        bool ok[8];
+        float mx = -1e30f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int key = v0 + j;
+            bool okj = key < L;
+            if (!okj && key < T) {
+                const int mm = key - L;
+                okj = (mword[mm >> 5] >> (mm & 31)) & 1u;
+            }
+            ok[j] = okj;
+            sc[j] = okj ? (j < 4 ? sa[j] : sb[j - 4]) * 0.125f : -1e30f;
+            mx = fmaxf(mx, sc[j]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float corr = __expf(m_run - m_new);
+        float psum = 0.f;
+        uint32_t pk[4];
+#pragma unroll
+        for (int j = 0; j < 8; j += 2) {
+            const float p0f = ok[j] ? __expf(sc[j] - m_new) : 0.f;
+            const float p1f = ok[j + 1] ? __expf(sc[j + 1] - m_new) : 0.f;
+            psum += p0f + p1f;
+            pk[j >> 1] = (uint32_t)f2bf(p0f) | ((uint32_t)f2bf(p1f) << 16);
+        }
+        l_run = l_run * corr + psum;
+        m_run = m_new;
+        const bf16x8_t pfrag = __builtin_bit_cast(bf16x8_t, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            O[dt] *= corr;
+            O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vt[dt]), pfrag, O[dt], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
+    }
+    // merge the four waves: sm_m / sm_l [wave][query], sm_o [wave][dim][query]
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+    float* sm_o = (float*)smem;
+    float* sm_m = sm_o + 4 * 64 * 16;
+    float* sm_l = sm_m + 64;
+    __syncthreads();
+    if (gq == 0) { sm_m[wave * 16 + c] = m_run; sm_l[wave * 16 + c] = l_run; }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sm_o[(wave * 64 + dt * 16 + 4 * gq + i) * 16 + c] = O[dt][i];
+    __syncthreads();
+    {
+        const int q = tid >> 4, d0 = (tid & 15) * 4, nd = qt * 16 + q;
+        float mstar = sm_m[q];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) mstar = fmaxf(mstar, sm_m[w * 16 + q]);
+        float f[4], lsum = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { f[w] = __expf(sm_m[w * 16 + q] - mstar); lsum += f[w] * sm_l[w * 16 + q]; }
+        const float inv = 1.f / lsum;
+        float o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float a = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) a += f[w] * sm_o[(w * 64 + d0 + j) * 16 + q];
+            o[j] = a * inv;
+        }
+        if (nd < D.M)
+            stw64(att + ((size_t)(b * D.M + nd)) * D.d + h * 64 + d0,
+                  (uint64_t)pack_bf16(o[0], o[1]) | ((uint64_t)pack_bf16(o[2], o[3]) << 32));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// one unit of one phase
+// ---------------------------------------------------------------------------
+__device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float* s_stat) {
+    const Dims& D = P.D;
+    const DevState& s = P.s;
+    const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
+    if (ph == 0) { embed_unit(P, u); return; }
+    GemmD g;
+    g.R = R; g.stats = nullptr; g.colsum = nullptr; g.bias = nullptr; g.out = nullptr; g.outf = nullptr;
+    g.stats_out = nullptr; g.layer = 0;
+    if (ph < H) {
+        const int l = (ph - 1) / 5, k = (ph - 1) % 5;
+        const LayerW& w = s.layers_dev[l];
+        g.layer = l;
+        // slots: xb / stats 2l = input of the layer, 2l+1 = after the out-projection, 2l+2 = after FFN2
+        bf16_t* xb0 = s.xb + (size_t)(2 * l) * s.act_stride;
+        float* st0 = s.stats + (size_t)(2 * l) * s.stats_stride;
+        bf16_t* q_l = (bf16_t*)s.q + (size_t)l * s.act_stride;
+        bf16_t* att_l = (bf16_t*)s.att + (size_t)l * s.act_stride;
+        bf16_t* hid_l = (bf16_t*)s.hid + (size_t)l * s.hid_stride;
+        switch (k) {
+        case 0:
+            g.X = xb0; g.K = D.d; g.N = 3 * D.d; g.Wp = (const uint4*)w.Wqkv; g.bias = w.t_qkv; g.colsum = w.cs_qkv;
+            g.stats = st0; g.epi = SE_QKV; g.out = q_l;
+            gemm_unit<4>(P, g, u / RG, (u % RG) * 64, smem, s_stat);
+            return;
+        case 1: attn_unit(P, l, u, smem); return;
+        case 2:
+            g.X = att_l; g.K = D.d; g.N = D.d; g.Wp = (const uint4*)w.Wo; g.bias = w.bo;
+            g.epi = SE_RESID; g.out = xb0 + s.act_stride; g.stats_out = st0 + s.stats_stride;
+            gemm_unit<1>(P, g, u / RB, (u % RB) * 16, smem, s_stat);
+            return;
+        case 3:
+            g.X = xb0 + s.act_stride; g.K = D.d; g.N = D.F; g.Wp = (const uint4*)w.W1; g.bias = w.t_w1; g.colsum = w.cs_w1;
+            g.stats = st0 + s.stats_stride; g.epi = SE_GELU; g.out = hid_l;
+            gemm_unit<4>(P, g, u / RG, (u % RG) * 64, smem, s_stat);
+            return;
+        default:
+            g.X = hid_l; g.K = D.F; g.N = D.d; g.Wp = (const uint4*)w.W2; g.bias = w.b2;
+            g.epi = SE_RESID; g.out = xb0 + 2 * s.act_stride; g.stats_out = st0 + 2 * s.stats_stride;
+            gemm_unit<1>(P, g, u / RB, (u % RB) * 16, smem, s_stat);
+            return;
+        }
+    }
+    const int RGb = cdiv(P.nseq, 64);
+    switch (ph - H) {
+    case 0:
+        g.X = s.xb + (size_t)(2 * D.Ly) * s.act_stride; g.K = D.d; g.N = D.V1; g.Wp = (const uint4*)s.W_out;
+        g.bias = s.t_out; g.colsum = s.cs_out;
+        g.stats = s.stats + (size_t)(2 * D.Ly) * s.stats_stride; g.epi = SE_LOGITS; g.outf = s.logits;
+        gemm_unit<4>(P, g, u / RG, (u % RG) * 64, smem, s_stat);
+        return;
+    case 1: dev_accept(D, s, u, P.tau, P.ignore_eos); return;
+    case 2: dev_finalize<bf16_t>(D, s, P.seq0 + u, P.prefill_mode, P.ignore_eos, 1); return;
+    case 3: {
+        const int ncommit = D.Ly * D.nH * P.nseq;
+        if (u < ncommit) {
+            if (threadIdx.x < 64) {
+                const int head = u % D.nH, b = (u / D.nH) % P.nseq, layer = u / (D.nH * P.nseq);
+                dev_commit_kv<bf16_t>(D, s, layer, P.seq0 + b, head, threadIdx.x);
+            }
+            return;
+        }
+        u -= ncommit;
+        const int per = (D.d / 16) * RGb, i = u / per, v = u % per;
+        const DraftW& dw = s.draft_dev[i];
+        g.R = P.nseq; g.X = (const bf16_t*)s.hbest + (size_t)P.seq0 * D.d; g.K = D.d; g.N = D.d;
+        g.Wp = (const uint4*)dw.W1; g.bias = dw.b1; g.epi = SE_SILU_RESID;
+        g.out = (bf16_t*)s.rdraft + ((size_t)i * D.Bmax + P.seq0) * D.d;
+        gemm_unit<4>(P, g, v / RGb, (v % RGb) * 64, smem, s_stat);
+        return;
+    }
+    case 4: {
+        const int per = cdiv(D.V1, 16) * RGb, i = u / per, v = u % per;
+        const DraftW& dw = s.draft_dev[i];
+        g.R = P.nseq; g.X = (const bf16_t*)s.rdraft + ((size_t)i * D.Bmax + P.seq0) * D.d; g.K = D.d; g.N = D.V1;
+        g.Wp = (const uint4*)dw.W2; g.epi = SE_F32;
+        g.outf = s.zdraft + ((size_t)i * D.Bmax + P.seq0) * D.V1;
+        gemm_unit<4>(P, g, v / RGb, (v % RGb) * 64, smem, s_stat);
+        return;
+    }
+    default: dev_topk(D, s, u / P.nseq, P.seq0 + u % P.nseq); return;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_step(StepParams P) {
+    extern __shared__ uint4 smem[];
+    float* s_stat = (float*)((char*)smem + ST_TILE_BYTES);
+    uint32_t epoch = P.epoch;
+    for (int ph = P.ph_lo; ph < P.ph_hi; ++ph) {
+        if (blockIdx.x == 0 && threadIdx.x == 0 && ph < 255) P.s.tprof[ph] = wall_clock64();
+        const int nu = phase_units(P, ph);
+        for (int u = blockIdx.x; u < nu; u += gridDim.x) {
+            run_unit(P, ph, u, smem, s_stat);
+            __syncthreads();
+        }
+        if (P.persistent && ph + 1 < P.ph_hi) {
+            ++epoch;
+            if (!grid_sync(P, epoch)) return;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) P.s.tprof[255] = wall_clock64();
+}
+
+void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err) {
+    static bool once = false;
+    if (!once) {
+        (void)hipFuncSetAttribute((const void*)k_step, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS_BYTES);
+        once = true;
+    }
+    *err = hipSuccess;
+    if (p.persistent) {
+        StepParams q = p;
+        void* args[] = {&q};
+        *err = hipLaunchCooperativeKernel((const void*)k_step, dim3(n_cus), dim3(256), args, ST_LDS_BYTES, st);
+        return;
+    }
+    for (int ph = p.ph_lo; ph < p.ph_hi; ++ph) {
+        StepParams q = p;
+        q.ph_lo = ph; q.ph_hi = ph + 1;
+        const int nu = phase_units(q, ph);
+        if (nu <= 0) continue;
+        hipLaunchKernelGGL(k_step, dim3(std::min(nu, 4096)), dim3(256), ST_LDS_BYTES, st, q);
+    }
+    *err = hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// weight preparation: fp32 [N][K] row-major -> packed bf16 tiles
+// [n-tile][k-step][lane][8]; lane (c, g) of tile (nt, ks) holds
+// W[nt*16 + c][ks*32 + 8g .. 8g+7] (times gamma[k] for LN-folded maps).
+// Rows >= N are zero.
+// ---------------------------------------------------------------------------
+__global__ void k_pack_w(const float* __restrict__ src, const float* __restrict__ gamma, uint4* __restrict__ dst,
+                         int N, int K) {
+    const int nks = K >> 5;
+    const size_t total = (size_t)((N + 15) / 16) * nks * 64;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(i & 63);
+        const size_t tile = i >> 6;
+        const int ks = (int)(tile % nks), nt = (int)(tile / nks);
+        const int n = nt * 16 + (lane & 15), k0 = ks * 32 + 8 * (lane >> 4);
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float lo = 0.f, hi = 0.f;
+            if (n < N) {
+                lo = src[(size_t)n * K + k0 + 2 * j];
+                hi = src[(size_t)n * K + k0 + 2 * j + 1];
+                if (gamma) { lo *= gamma[k0 + 2 * j]; hi *= gamma[k0 + 2 * j + 1]; }
+            }
+            w[j] = (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+        }
+        dst[i] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// colsum[n] = sum_k bf16(gamma[k] W[n][k]),  tvec[n] = sum_k beta[k] W[n][k]; one wave per n
+__global__ void k_fold_vectors(const float* __restrict__ src, const float* __restrict__ gamma,
+                               const float* __restrict__ beta, float* __restrict__ colsum, float* __restrict__ tvec,
+                               int N, int K) {
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (n >= N) return;
+    float cs = 0.f, tv = 0.f;
+    for (int k = lane; k < K; k += 64) {
+        const float w = src[(size_t)n * K + k];
+        cs += bf2f(f2bf(w * gamma[k]));
+        tv += beta[k] * w;
+    }
+    cs = wave_sum(cs);
+    tv = wave_sum(tv);
+    if (lane == 0) { colsum[n] = cs; tvec[n] = tv; }
+}
+
+__global__ void k_add_vec(float* __restrict__ dst, const float* __restrict__ src, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] += src[i];
+}
+
+void launch_pack_w(const float* src, void* dst, int N, int K, hipStream_t st) {
+    const size_t total = (size_t)((N + 15) / 16) * (K >> 5) * 64;
+    const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+    hipLaunchKernelGGL(k_pack_w, dim3(blocks), dim3(256), 0, st, src, (const float*)nullptr, (uint4*)dst, N, K);
+}
+
+void launch_pack_w_ln(const float* src, const float* gamma, const float* beta, void* dst, float* colsum,
+                      float* tvec, int N, int K, hipStream_t st) {
+    const size_t total = (size_t)((N + 15) / 16) * (K >> 5) * 64;
+    const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+    hipLaunchKernelGGL(k_pack_w, dim3(blocks), dim3(256), 0, st, src, gamma, (uint4*)dst, N, K);
+    hipLaunchKernelGGL(k_fold_vectors, dim3((N + 3) / 4), dim3(256), 0, st, src, gamma, beta, colsum, tvec, N, K);
+}
+
+void launch_add_vec(float* dst, const float* src, int n, hipStream_t st) {
+    hipLaunchKernelGGL(k_add_vec, dim3((n + 255) / 256), dim3(256), 0, st, dst, src, n);
+}
