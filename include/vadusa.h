@@ -208,8 +208,9 @@ enum {
     VADUSA_DBG_PATH       = 7,  /* int32 [batch][n_draft_heads+2]: count, then node indices */
     VADUSA_DBG_FINISHED   = 8,  /* int32 [batch] */
     VADUSA_DBG_DRAFT_LOGITS = 9, /* float [batch][n_draft_heads][V+1], logits behind the lists */
-    VADUSA_DBG_PHASE_CLOCK = 10  /* int64 [256]: device clock (100 MHz) at the start of every phase of the
-                                    last launch of the bf16 step kernel, [255] = its end; zeros for fp32 */
+    VADUSA_DBG_PHASE_CLOCK = 10  /* int64 [128][8]: device clock (100 MHz) of workgroup 0 in the last launch of
+                                    the bf16 step kernel: [p][0] start of phase p, [p][1] its own units done,
+                                    [p][2..] points inside a unit, [127][0] end of the kernel */
 };
 
 /* Copies one of the items above to host memory after synchronising the stream.

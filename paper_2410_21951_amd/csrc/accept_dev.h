@@ -147,7 +147,7 @@ __device__ inline void dev_finalize(const Dims& D, const DevState& s, int b, int
         for (int i = threadIdx.x * 2; i < D.d; i += 512) {
             const float a = (ldcf(xr + i) - mu) * rstd * s.lnf_g[i] + s.lnf_b[i];
             const float c2 = (ldcf(xr + i + 1) - mu) * rstd * s.lnf_g[i + 1] + s.lnf_b[i + 1];
-            stw32((bf16_t*)hb + i, pack_bf16(a, c2));
+            stw32((bf16_t*)s.hbest + toff(b, i, D.d >> 5), pack_bf16(a, c2));   // tiled for the draft maps
         }
     } else {
         const T* h = (const T*)s.hn + (size_t)r * D.d;

@@ -178,22 +178,23 @@ static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vecto
     st.Vc = cv.take(kv);
     st.x = (float*)cv.take(R * d * 4);
     const size_t nslots = c.dtype ? 2 * (size_t)c.n_layers + 1 : 0, per_layer = c.dtype ? c.n_layers : 1;
-    st.act_stride = R * d; st.stats_stride = (d / 16) * R * 2; st.hid_stride = R * F;
-    st.xb = (bf16_t*)cv.take(nslots * R * d * 2);
+    const size_t Rp = (R + 15) / 16 * 16, Bp = (B + 15) / 16 * 16;   // tiled activation buffers hold whole row tiles
+    st.act_stride = Rp * d; st.stats_stride = (d / 16) * R * 2; st.hid_stride = Rp * F; st.draft_stride = Bp * d;
+    st.xb = (bf16_t*)cv.take(nslots * Rp * d * 2);
     st.stats = (float*)cv.take(nslots * st.stats_stride * 4);
     st.bar = (uint32_t*)cv.take(4096 * 4);
     st.kerr = (int32_t*)cv.take(4 * 4);
-    st.tprof = (long long*)cv.take(256 * 8);
+    st.tprof = (long long*)cv.take(1024 * 8);
     st.layers_dev = (const LayerW*)cv.take(sizeof(LayerW) * c.n_layers);
     st.draft_dev = (const DraftW*)cv.take(sizeof(DraftW) * Hh);
     st.xn = cv.take(R * d * e);
-    st.q = cv.take(per_layer * R * d * e);
-    st.att = cv.take(per_layer * R * d * e);
-    st.hid = cv.take(per_layer * R * F * e);
+    st.q = cv.take(per_layer * Rp * d * e);
+    st.att = cv.take(per_layer * Rp * d * e);
+    st.hid = cv.take(per_layer * Rp * F * e);
     st.hn = cv.take(R * d * e);
     st.logits = (float*)cv.take(R * V1 * 4);
-    st.hbest = cv.take(B * d * e);
-    st.rdraft = cv.take(Hh * B * d * e);
+    st.hbest = cv.take(Bp * d * e);
+    st.rdraft = cv.take(Hh * Bp * d * e);
     st.zdraft = (float*)cv.take(Hh * B * V1 * 4);
     auto ints = [&](size_t n) { return (int32_t*)cv.take(n * 4); };
     st.L = ints(B); st.root = ints(B); st.finished = ints(B);
@@ -276,7 +277,7 @@ extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena
         // barrier flags and the error flag start at zero; an unwritten KV row must never hold NaN bits
         const size_t kv = (size_t)cfg->n_layers * cfg->max_batch * cfg->n_heads * cfg->max_positions * 64 * c->elem;
         hipError_t e0 = hipMemset(c->s.bar, 0, 4096 * 4);
-        if (e0 == hipSuccess) e0 = hipMemset(c->s.tprof, 0, 256 * 8);
+        if (e0 == hipSuccess) e0 = hipMemset(c->s.tprof, 0, 1024 * 8);
         if (e0 == hipSuccess) e0 = hipMemset(c->s.kerr, 0, 16);
         if (e0 == hipSuccess) e0 = hipMemset(c->s.Kc, 0, kv);
         if (e0 == hipSuccess) e0 = hipMemset(c->s.Vc, 0, kv);
@@ -730,7 +731,7 @@ extern "C" int vadusa_debug_read(vadusa_ctx* c, int32_t what, void* host, size_t
     case VADUSA_DBG_ROOT: src = s.root; need = B * 4; break;
     case VADUSA_DBG_EDGE_OK: src = s.edge_ok; need = B * M * 4; break;
     case VADUSA_DBG_FINISHED: src = s.finished; need = B * 4; break;
-    case VADUSA_DBG_PHASE_CLOCK: src = s.tprof; need = 256 * 8; break;
+    case VADUSA_DBG_PHASE_CLOCK: src = s.tprof; need = 1024 * 8; break;
     case VADUSA_DBG_H_NODES: {
         need = B * M * d * 4;
         if (bytes != need) return fail(c, VADUSA_EINVAL, "expected %zu bytes", need);

@@ -47,6 +47,12 @@ __device__ __forceinline__ int32_t ldci(const int32_t* p) {
 __device__ __forceinline__ float ldcf(const float* p) {
     return __uint_as_float(__hip_atomic_load((const uint32_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 }
+// Offset of element (r, k) of a bf16 activation matrix kept in MFMA-operand tiles:
+// [row tile of 16][k-step of 32][lane = (r & 15) + 16 * ((k & 31) >> 3)][k & 7], nks = K / 32.
+// A wave reads one (row tile, k-step) as the A operand with one contiguous KiB load.
+__device__ __forceinline__ size_t toff(int r, int k, int nks) {
+    return ((size_t)((r >> 4) * nks + (k >> 5)) * 64 + (r & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
+}
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) { return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16); }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -101,10 +107,10 @@ struct DevState {
     // hid one slot per layer.  Slot strides are in elements.
     bf16_t* xb;      // [2Ly+1][R][d]  bf16 copy of the residual stream
     float* stats;    // [2Ly+1][d/16][R][2] per 16-column tile: mean, sum of squared deviations
-    size_t act_stride, stats_stride, hid_stride;
+    size_t act_stride, stats_stride, hid_stride, draft_stride;   // rows padded to a multiple of 16
     uint32_t* bar;   // grid barrier: [0..16*64) group counters, [1024] top counter, [2048 + 16*64) release flags
     int32_t* kerr;   // [4] error flag raised by a kernel (barrier time-out)
-    long long* tprof; // [256] device clock at the start of every phase of the last launch (100 MHz)
+    long long* tprof; // [128][8] timing points of workgroup 0 in the last launch (device clock, 100 MHz)
     void* xn;        // [R][d]  LayerNorm output
     void* q;         // [R][d]   (bf16 model: one slot per layer)
     void* att;       // [R][d]   (bf16 model: one slot per layer)

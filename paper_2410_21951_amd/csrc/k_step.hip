@@ -37,7 +37,7 @@
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
-#define ST_TILE_BYTES (64 * 1032 * 2)        // 64 rows x (1024 + 8) bf16 == 16 rows x (4096 + 8) bf16
+#define ST_TILE_BYTES (20 * 1024)           // reduction buffer of the linear maps (16 KiB), attention merge buffers
 #define ST_LDS_BYTES (ST_TILE_BYTES + 1024)  // + row statistics
 #define ST_SPIN_LIMIT (1 << 22)
 
@@ -55,6 +55,7 @@ struct GemmD {
     float* outf;          // SE_LOGITS / SE_F32
     float* stats_out;     // SE_RESID
     int layer;
+    int ph;               // phase index (timing points only)
 };
 
 __device__ __forceinline__ float gelu_s(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752f)); }
@@ -80,15 +81,21 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
         default: return (D.d / 16) * RB;
         }
     }
-    const int RGb = cdiv(P.nseq, 64);
+    const int RGb = cdiv(D.B, 64);
     switch (ph - H) {
     case 0: return cdiv(D.V1, 16) * RG;
     case 1: return P.prefill_mode ? 0 : D.B;
     case 2: return P.nseq;
     case 3: return D.Ly * D.nH * P.nseq + D.Hh * (D.d / 16) * RGb;
     case 4: return D.Hh * cdiv(D.V1, 16) * RGb;
-    default: return D.Hh * P.nseq;
+    default: return D.Hh * D.B;
     }
+}
+
+// Timing points of workgroup 0 (device clock, 100 MHz): tprof[phase][k]; k = 0 phase start,
+// 1 own units done, 2.. points inside a unit.  Read back through vadusa_debug_read.
+__device__ __forceinline__ void tp(const StepParams& P, int ph, int k) {
+    if (blockIdx.x == 0 && threadIdx.x == 0 && ph < 128) P.s.tprof[ph * 8 + k] = wall_clock64();
 }
 
 // ---------------------------------------------------------------------------
@@ -100,9 +107,10 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
 // error flag, the workgroup gives up and the kernel ends (the host reports it).
 // ---------------------------------------------------------------------------
 #define BAR_GROUPS 16
-__device__ bool grid_sync(const StepParams& P, uint32_t epoch) {
+__device__ bool grid_sync(const StepParams& P, uint32_t epoch, int ph) {
     __shared__ int s_ok;
     __syncthreads();   // every wave's stores have completed (write-through: at the memory side)
+    tp(P, ph, 4);
     if (threadIdx.x == 0) {
         uint32_t* bar = P.s.bar;
         const int g = blockIdx.x % BAR_GROUPS;
@@ -163,7 +171,7 @@ __device__ void embed_unit(const StepParams& P, int r) {
     const bf16_t* e = E + (size_t)tok * D.d;
     const bf16_t* p = (const bf16_t*)s.P + (size_t)pos * D.d;
     float* x = s.x + (size_t)r * D.d;
-    bf16_t* xb = s.xb + (size_t)r * D.d;   // slot 0
+    bf16_t* xb = s.xb;                      // slot 0, tiled
     float* st = s.stats;                    // slot 0
     const int R = D.B * D.M;
     for (int c0 = tid * 4; c0 < D.d; c0 += 1024) {
@@ -185,67 +193,67 @@ __device__ void embed_unit(const StepParams& P, int r) {
         m2 += __shfl_xor(m2, 2, 64);
         stwf2(x + c0, v[0], v[1]);
         stwf2(x + c0 + 2, v[2], v[3]);
-        stw64(xb + c0, (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32));
+        stw64(xb + toff(r, c0, D.d >> 5), (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32));
         if ((tid & 3) == 0) stwf2(st + ((size_t)(c0 >> 4) * R + r) * 2, mean, m2);
     }
 }
 
 // ---------------------------------------------------------------------------
-// linear-map unit.  NRT = 4: 64 rows x one 16-column tile, K <= 1024 per LDS
-// chunk (QKV, FFN1, heads).  NRT = 1: 16 rows x one tile, K <= 4096 per chunk
-// (out-projection, FFN2: residual update + statistics of the new rows).
-// The four waves split the k-steps round-robin; partial sums are combined in
-// wave order through LDS.
+// linear-map unit.  NRT = 4: 64 rows x one 16-column tile (QKV, FFN1, heads).
+// NRT = 1: 16 rows x one tile (out-projection, FFN2: residual update +
+// statistics of the new rows).  Wave w owns a contiguous quarter of the
+// k-steps and loads BOTH operands straight from global memory into the MFMA
+// register layout: B (weights, one contiguous KiB per wave load, from HBM) and
+// A (activations, 16 bytes per lane, from L2).  Every load of a chunk is issued
+// before the first MFMA, so a unit pays one memory latency per chunk.  Partial
+// sums are combined in wave order through LDS.
 // ---------------------------------------------------------------------------
 template <int NRT>
 __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0, uint4* smem, float* s_stat) {
-    constexpr int KC = NRT == 4 ? 1024 : 4096;
-    constexpr int LDV = KC / 8 + 1;
+    constexpr int CH = NRT == 4 ? 8 : 16;     // k-steps per chunk
     constexpr int ROWS = NRT * 16;
     const Dims& D = P.D;
     const DevState& s = P.s;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, gq = lane >> 4, c = lane & 15;
     const int nks = g.K >> 5;
+    const int ks_lo = (nks * wave) >> 2, ks_hi = (nks * (wave + 1)) >> 2;
     const uint4* Wp = g.Wp + (size_t)nt * nks * 64 + lane;
+    // A operand: tile (row tile, k-step) of the tiled activation layout = 64 lanes x 16 bytes
+    const uint4* Ap[NRT];
+    bool rowok[NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+        rowok[rt] = row0 + rt * 16 < g.R;   // whole tile beyond the last row: skipped
+        Ap[rt] = (const uint4*)g.X + (size_t)(rowok[rt] ? (row0 >> 4) + rt : 0) * nks * 64 + lane;
+    }
     f32x4_t acc[NRT];
 #pragma unroll
     for (int i = 0; i < NRT; ++i) acc[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    tp(P, g.ph, 5);
 
-    for (int kc0 = 0; kc0 < g.K; kc0 += KC) {
-        const int kcl = min(KC, g.K - kc0);
-        const int ks0 = kc0 >> 5, ksn = kcl >> 5;
-        uint4 bw[8];
+    // row statistics of the LayerNorm folded into this map: four threads per row, each
+    // merges a quarter of the 16-column tiles (loads issued with the first operand chunk)
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    const int tiles = g.K >> 4;
+    const bool do_stats = g.stats != nullptr && tid < ROWS * 4;
+
+    for (int kb = ks_lo; kb < ks_hi; kb += CH) {
+        uint4 bw[CH], aw[NRT][CH];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int ks = wave + 4 * i;
-            bw[i] = ks < ksn ? Wp[(size_t)(ks0 + ks) * 64] : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < CH; ++i) {
+            const int ks = kb + i;
+            bw[i] = ks < ks_hi ? Wp[(size_t)ks * 64] : make_uint4(0, 0, 0, 0);
         }
-        __syncthreads();   // earlier users of the LDS tile are done
-        const int v8 = kcl >> 3, total = ROWS * v8;
-        for (int base = tid; base < total; base += 256 * 8) {
-            uint4 v[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int idx = base + j * 256;
-                v[j] = make_uint4(0, 0, 0, 0);
-                if (idx < total) {
-                    const int row = idx / v8, col = idx - row * v8;
-                    if (row0 + row < g.R) v[j] = *(const uint4*)(g.X + (size_t)(row0 + row) * g.K + kc0 + col * 8);
-                }
-            }
+        for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int idx = base + j * 256;
-                if (idx < total) {
-                    const int row = idx / v8, col = idx - row * v8;
-                    smem[row * LDV + col] = v[j];
-                }
+            for (int i = 0; i < CH; ++i) {
+                const int ks = kb + i;
+                aw[rt][i] = (ks < ks_hi && rowok[rt]) ? Ap[rt][(size_t)ks * 64] : make_uint4(0, 0, 0, 0);
             }
-        }
-        if (kc0 == 0 && g.stats && tid < ROWS * 4) {
-            // row statistics: four threads per row, each merges a quarter of the tiles
-            const int row = tid >> 2, part = tid & 3, r = row0 + row, tiles = g.K >> 4;
-            float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        if (kb == ks_lo) tp(P, g.ph, 6);
+        if (kb == ks_lo && do_stats) {
+            const int row = tid >> 2, part = tid & 3, r = row0 + row;
             if (r < g.R) {
                 const float2* sp = (const float2*)g.stats + r;
                 for (int t0 = part; t0 < tiles; t0 += 32) {
@@ -259,40 +267,28 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
                     for (int j = 0; j < 8; ++j) { s1 += v[j].x; s2 += v[j].y; s3 += v[j].x * v[j].x; }
                 }
             }
-            s1 += __shfl_xor(s1, 1, 64); s1 += __shfl_xor(s1, 2, 64);
-            s2 += __shfl_xor(s2, 1, 64); s2 += __shfl_xor(s2, 2, 64);
-            s3 += __shfl_xor(s3, 1, 64); s3 += __shfl_xor(s3, 2, 64);
-            if (part == 0) {
-                // mean of tile means; M2 = sum M2_t + 16 sum (mean_t - mean)^2
-                const float mean = s1 / tiles;
-                const float m2 = s2 + 16.f * fmaxf(s3 - tiles * mean * mean, 0.f);
-                s_stat[row] = mean;
-                s_stat[64 + row] = rsqrtf(m2 / g.K + LN_EPS);
-            }
         }
-        __syncthreads();
-        for (int i0 = 0; wave + 4 * i0 < ksn; i0 += 8) {
-            uint4 bn[8];
+        if (kb == ks_lo) tp(P, g.ph, 7);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int ks = wave + 4 * (i0 + 8 + i);
-                bn[i] = ks < ksn ? Wp[(size_t)(ks0 + ks) * 64] : make_uint4(0, 0, 0, 0);
-            }
+        for (int i = 0; i < CH; ++i) {
+            const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bw[i]);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int ks = wave + 4 * (i0 + i);
-                if (ks < ksn) {
-                    const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bw[i]);
-#pragma unroll
-                    for (int rt = 0; rt < NRT; ++rt) {
-                        const uint4 av = smem[(rt * 16 + c) * LDV + ks * 4 + gq];
-                        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av), bfrag,
-                                                                          acc[rt], 0, 0, 0);
-                    }
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) bw[i] = bn[i];
+            for (int rt = 0; rt < NRT; ++rt)
+                acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aw[rt][i]), bfrag,
+                                                                  acc[rt], 0, 0, 0);
+        }
+    }
+    tp(P, g.ph, 2);   // operands arrived, MFMAs issued
+    if (g.stats) {
+        s1 += __shfl_xor(s1, 1, 64); s1 += __shfl_xor(s1, 2, 64);
+        s2 += __shfl_xor(s2, 1, 64); s2 += __shfl_xor(s2, 2, 64);
+        s3 += __shfl_xor(s3, 1, 64); s3 += __shfl_xor(s3, 2, 64);
+        if (do_stats && (tid & 3) == 0) {
+            // mean of tile means; M2 = sum M2_t + 16 sum (mean_t - mean)^2
+            const float mean = s1 / tiles;
+            const float m2 = s2 + 16.f * fmaxf(s3 - tiles * mean * mean, 0.f);
+            s_stat[tid >> 2] = mean;
+            s_stat[64 + (tid >> 2)] = rsqrtf(m2 / g.K + LN_EPS);
         }
     }
     __syncthreads();
@@ -302,6 +298,7 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
 #pragma unroll
         for (int i = 0; i < 4; ++i) red[((wave * NRT + rt) * 64 + lane) * 4 + i] = acc[rt][i];
     __syncthreads();
+    tp(P, g.ph, 3);   // partial sums exchanged
 
     if (NRT == 4) {
         const int row = tid >> 2, rt = row >> 4, rr = row & 15, r = row0 + row;
@@ -325,7 +322,7 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
             const bool full = n0 + 3 < g.N;   // only the vocabulary maps have a ragged last tile
             switch (g.epi) {
             case SE_GELU:
-                stw64(g.out + (size_t)r * g.N + n0,
+                stw64(g.out + toff(r, n0, g.N >> 5),
                       (uint64_t)pack_bf16(gelu_s(v[0]), gelu_s(v[1])) | ((uint64_t)pack_bf16(gelu_s(v[2]), gelu_s(v[3])) << 32));
                 break;
             case SE_LOGITS:
@@ -336,15 +333,15 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
                     if (full || n0 + j < g.N) stwf(g.outf + (size_t)r * g.N + n0 + j, v[j]);
                 break;
             case SE_SILU_RESID: {
-                const uint2 xin = *(const uint2*)(g.X + (size_t)r * g.K + n0);
+                const uint2 xin = *(const uint2*)(g.X + toff(r, n0, g.K >> 5));
                 const float h0 = bf2f((bf16_t)xin.x) + silu_s(v[0]), h1 = bf2f((bf16_t)(xin.x >> 16)) + silu_s(v[1]);
                 const float h2 = bf2f((bf16_t)xin.y) + silu_s(v[2]), h3 = bf2f((bf16_t)(xin.y >> 16)) + silu_s(v[3]);
-                stw64(g.out + (size_t)r * g.N + n0, (uint64_t)pack_bf16(h0, h1) | ((uint64_t)pack_bf16(h2, h3) << 32));
+                stw64(g.out + toff(r, n0, g.N >> 5), (uint64_t)pack_bf16(h0, h1) | ((uint64_t)pack_bf16(h2, h3) << 32));
                 break;
             }
             case SE_QKV: {
                 const uint64_t pk = (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32);
-                if (n0 < D.d) { stw64(g.out + (size_t)r * D.d + n0, pk); break; }
+                if (n0 < D.d) { stw64(g.out + toff(r, n0, D.d >> 5), pk); break; }
                 const int b = r / D.M, node = r - b * D.M;
                 const int which = n0 / D.d - 1, cc = n0 % D.d, head = cc >> 6, dim = cc & 63;
                 const int pos = s.L[b] + node;
@@ -378,7 +375,7 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
         }
         {
             const float nb = __shfl_down(xn, 1, 64);   // pair of columns -> one 32-bit store
-            if (ok && !(col & 1)) stw32(g.out + (size_t)r * g.N + n, pack_bf16(xn, nb));
+            if (ok && !(col & 1)) stw32(g.out + toff(r, n, g.N >> 5), pack_bf16(xn, nb));
         }
         float sum = xn;
 #pragma unroll
@@ -408,7 +405,7 @@ __device__ void attn_unit(const StepParams& P, int layer, int u, uint4* smem) {
     bf16_t* att = (bf16_t*)s.att + (size_t)layer * s.act_stride;
     if (n_rows == 0) {
         const int q = tid >> 4, d0 = (tid & 15) * 4, node = qt * 16 + q;
-        if (node < D.M) stw64(att + ((size_t)(b * D.M + node)) * D.d + h * 64 + d0, 0ull);
+        if (node < D.M) stw64(att + toff(b * D.M + node, h * 64 + d0, D.d >> 5), 0ull);
         return;
     }
     const int L = s.L[b];
@@ -417,9 +414,10 @@ __device__ void attn_unit(const StepParams& P, int layer, int u, uint4* smem) {
     const bf16_t* Kh = (const bf16_t*)s.Kc + hb;
     const bf16_t* Vh = (const bf16_t*)s.Vc + hb;
     const int node = min(qt * 16 + c, D.M - 1);
-    const bf16_t* qp = (const bf16_t*)s.q + (size_t)layer * s.act_stride + ((size_t)(b * D.M + node)) * D.d + h * 64;
-    const bf16x8_t Q0 = __builtin_bit_cast(bf16x8_t, *(const uint4*)(qp + 8 * gq));
-    const bf16x8_t Q1 = __builtin_bit_cast(bf16x8_t, *(const uint4*)(qp + 32 + 8 * gq));
+    const bf16_t* ql = (const bf16_t*)s.q + (size_t)layer * s.act_stride;
+    const int qrow = b * D.M + node;
+    const bf16x8_t Q0 = __builtin_bit_cast(bf16x8_t, *(const uint4*)(ql + toff(qrow, h * 64 + 8 * gq, D.d >> 5)));
+    const bf16x8_t Q1 = __builtin_bit_cast(bf16x8_t, *(const uint4*)(ql + toff(qrow, h * 64 + 32 + 8 * gq, D.d >> 5)));
     const uint4 mw = *(const uint4*)(s.t_mask[P.table] + (size_t)node * MASK_WORDS);
     const uint32_t mword[4] = {mw.x, mw.y, mw.z, mw.w};
 
@@ -526,7 +524,7 @@ __device__ void attn_unit(const StepParams& P, int layer, int u, uint4* smem) {
             o[j] = a * inv;
         }
         if (nd < D.M)
-            stw64(att + ((size_t)(b * D.M + nd)) * D.d + h * 64 + d0,
+            stw64(att + toff(b * D.M + nd, h * 64 + d0, D.d >> 5),
                   (uint64_t)pack_bf16(o[0], o[1]) | ((uint64_t)pack_bf16(o[2], o[3]) << 32));
     }
 }
@@ -541,7 +539,7 @@ __device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float*
     if (ph == 0) { embed_unit(P, u); return; }
     GemmD g;
     g.R = R; g.stats = nullptr; g.colsum = nullptr; g.bias = nullptr; g.out = nullptr; g.outf = nullptr;
-    g.stats_out = nullptr; g.layer = 0;
+    g.stats_out = nullptr; g.layer = 0; g.ph = ph;
     if (ph < H) {
         const int l = (ph - 1) / 5, k = (ph - 1) % 5;
         const LayerW& w = s.layers_dev[l];
@@ -576,7 +574,7 @@ __device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float*
             return;
         }
     }
-    const int RGb = cdiv(P.nseq, 64);
+    const int RGb = cdiv(D.B, 64);
     switch (ph - H) {
     case 0:
         g.X = s.xb + (size_t)(2 * D.Ly) * s.act_stride; g.K = D.d; g.N = D.V1; g.Wp = (const uint4*)s.W_out;
@@ -598,42 +596,53 @@ __device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float*
         u -= ncommit;
         const int per = (D.d / 16) * RGb, i = u / per, v = u % per;
         const DraftW& dw = s.draft_dev[i];
-        g.R = P.nseq; g.X = (const bf16_t*)s.hbest + (size_t)P.seq0 * D.d; g.K = D.d; g.N = D.d;
+        g.R = D.B; g.X = (const bf16_t*)s.hbest; g.K = D.d; g.N = D.d;
         g.Wp = (const uint4*)dw.W1; g.bias = dw.b1; g.epi = SE_SILU_RESID;
-        g.out = (bf16_t*)s.rdraft + ((size_t)i * D.Bmax + P.seq0) * D.d;
+        g.out = (bf16_t*)s.rdraft + (size_t)i * s.draft_stride;
         gemm_unit<4>(P, g, v / RGb, (v % RGb) * 64, smem, s_stat);
         return;
     }
     case 4: {
         const int per = cdiv(D.V1, 16) * RGb, i = u / per, v = u % per;
         const DraftW& dw = s.draft_dev[i];
-        g.R = P.nseq; g.X = (const bf16_t*)s.rdraft + ((size_t)i * D.Bmax + P.seq0) * D.d; g.K = D.d; g.N = D.V1;
+        g.R = D.B; g.X = (const bf16_t*)s.rdraft + (size_t)i * s.draft_stride; g.K = D.d; g.N = D.V1;
         g.Wp = (const uint4*)dw.W2; g.epi = SE_F32;
-        g.outf = s.zdraft + ((size_t)i * D.Bmax + P.seq0) * D.V1;
+        g.outf = s.zdraft + (size_t)i * D.Bmax * D.V1;
         gemm_unit<4>(P, g, v / RGb, (v % RGb) * 64, smem, s_stat);
         return;
     }
-    default: dev_topk(D, s, u / P.nseq, P.seq0 + u % P.nseq); return;
+    default: dev_topk(D, s, u / D.B, u % D.B); return;
     }
 }
 
-__global__ __launch_bounds__(256) void k_step(StepParams P) {
+__global__ __launch_bounds__(256) void k_step(StepParams Parg) {
     extern __shared__ uint4 smem[];
+    // The kernel-argument segment may live in host memory: a re-load of an argument in the
+    // middle of the kernel then costs microseconds.  Copy the parameters into LDS once.
+    __shared__ StepParams sP;
+    {
+        const uint32_t* src = (const uint32_t*)&Parg;
+        uint32_t* dst = (uint32_t*)&sP;
+        for (int i = threadIdx.x; i < (int)(sizeof(StepParams) / 4); i += 256) dst[i] = src[i];
+    }
+    __syncthreads();
+    const StepParams& P = sP;
     float* s_stat = (float*)((char*)smem + ST_TILE_BYTES);
     uint32_t epoch = P.epoch;
     for (int ph = P.ph_lo; ph < P.ph_hi; ++ph) {
-        if (blockIdx.x == 0 && threadIdx.x == 0 && ph < 255) P.s.tprof[ph] = wall_clock64();
+        tp(P, ph, 0);
         const int nu = phase_units(P, ph);
         for (int u = blockIdx.x; u < nu; u += gridDim.x) {
             run_unit(P, ph, u, smem, s_stat);
             __syncthreads();
         }
+        tp(P, ph, 1);
         if (P.persistent && ph + 1 < P.ph_hi) {
             ++epoch;
-            if (!grid_sync(P, epoch)) return;
+            if (!grid_sync(P, epoch, ph)) return;
         }
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) P.s.tprof[255] = wall_clock64();
+    tp(P, 127, 0);
 }
 
 void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err) {

@@ -234,7 +234,7 @@ class Vadusa:
             DBG.TREE_TOK: ((B, M), np.int32), DBG.DRAFT_TOPK: ((B, Hh, MAX_TOPK), np.int32),
             DBG.KV_LEN: ((B,), np.int32), DBG.ROOT: ((B,), np.int32), DBG.EDGE_OK: ((B, M), np.int32),
             DBG.PATH: ((B, Hh + 2), np.int32), DBG.FINISHED: ((B,), np.int32),
-            DBG.DRAFT_LOGITS: ((B, Hh, V1), np.float32), DBG.PHASE_CLOCK: ((256,), np.int64),
+            DBG.DRAFT_LOGITS: ((B, Hh, V1), np.float32), DBG.PHASE_CLOCK: ((128, 8), np.int64),
         }
         shape, dt = shapes[what]
         out = np.zeros(shape, dt)
