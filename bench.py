@@ -33,6 +33,20 @@ def algorithmic_bytes(m, B, M, L_mean):
     return w_layers + w_out + w_draft + B * L_mean * kv_pos + B * M * kv_pos
 
 
+def measured_traffic(workload):
+    """HBM bytes per k_step launch from the rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by a
+    copy kernel of known size); the summary under profiles/ carries the figure on a `traffic_bytes_per_launch:`
+    line.  None when no such measurement exists for the workload."""
+    path = os.path.join(ROOT, "profiles", f"k_step_{workload}_pmc.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(wl, W, text, prompt, tree, budget_s=15.0):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
     from oracle import vadusa_oracle as O
@@ -64,12 +78,24 @@ def main():
     ap.add_argument("--workload", default="valle_b1")
     ap.add_argument("--tau", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain copy kernel of known size (256 MiB read + 256 MiB written, 8 launches): "
+                         "under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` its counters give the scale of the HBM byte counters")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the step shards over sequences, "
-              "see DESIGN.md, but no multi-GPU path is built)", file=sys.stderr)
+              "but no multi-GPU path is built)", file=sys.stderr)
         sys.exit(2)
     import torch
+    if a.copy_calibration:
+        torch.cuda.set_device(0)
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(8):
+            torch.mul(src, 1.0, out=dst)      # one elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"launches": 8, "bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4}}))
+        return
     from synth import PRESETS, make_weights, make_tokens, make_tree
     from paper_2410_21951_amd import Vadusa, TreeArrays
     wl = PRESETS[a.workload]
@@ -118,11 +144,14 @@ def main():
         "config": {"workload": f"{wl.name}: {m.n_layers}L d={m.d_model} {m.dtype}, batch {B}, {M}-node tree, "
                                f"tau={a.tau}, L {int(np.mean(L0))}->{int(np.mean(L0) + np.mean(n_out))}",
                    "mean_committed_per_step": float(np.mean(n_out)) / min(seg, a.steps)},
+        # dominant kernel: k_step, the persistent kernel that runs a whole step; one launch per step,
+        # so its average launch duration is the event-timed region divided by the number of steps
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "whole step (all launches of one vadusa_step)",
-                     "algorithmic_bytes_per_step": nbytes},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name),
+                     "kernel": "k_step (one launch = one speculative step)",
+                     "avg_launch_us": ms_step * 1e3, "algorithmic_bytes_per_launch": nbytes},
     }
+    dev.close()
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, W, text, prompt, tree)
     print(json.dumps(out))
