@@ -65,6 +65,10 @@ __device__ __forceinline__ float silu_s(float v) { return v / (1.f + __expf(-v))
 // phase bookkeeping (host and device)
 // ---------------------------------------------------------------------------
 __host__ __device__ inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+// Units of a linear map are numbered (row block) * pad8(column tiles) + column tile: workgroup i
+// runs on XCD i mod 8, so the row blocks that share a weight tile share an XCD and its L2, and
+// the tile leaves HBM once.  Numbers whose column tile is padding are empty units.
+__host__ __device__ inline int pad8(int a) { return (a + 7) & ~7; }
 
 int step_num_phases(int n_layers) { return 1 + 5 * n_layers + 6; }
 
@@ -74,16 +78,16 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     if (ph == 0) return R;
     if (ph < H) {
         switch ((ph - 1) % 5) {
-        case 0: return (3 * D.d / 16) * RG;
+        case 0: return pad8(3 * D.d / 16) * RG;
         case 1: return D.B * D.nH * cdiv(D.M, 16);
-        case 2: return (D.d / 16) * RB;
-        case 3: return (D.F / 16) * RG;
-        default: return (D.d / 16) * RB;
+        case 2: return pad8(D.d / 16) * RB;
+        case 3: return pad8(D.F / 16) * RG;
+        default: return pad8(D.d / 16) * RB;
         }
     }
     const int RGb = cdiv(D.B, 64);
     switch (ph - H) {
-    case 0: return cdiv(D.V1, 16) * RG;
+    case 0: return pad8(cdiv(D.V1, 16)) * RG;
     case 1: return P.prefill_mode ? 0 : D.B;
     case 2: return P.nseq;
     case 3: return D.Ly * D.nH * P.nseq + D.Hh * (D.d / 16) * RGb;
@@ -540,6 +544,9 @@ __device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float*
     GemmD g;
     g.R = R; g.stats = nullptr; g.colsum = nullptr; g.bias = nullptr; g.out = nullptr; g.outf = nullptr;
     g.stats_out = nullptr; g.layer = 0; g.ph = ph;
+    // (column tile, row block) of unit u of a map with NT column tiles; false: empty unit
+    int nt = 0, rb = 0;
+    auto split = [&](int NT) { const int NTp = pad8(NT); nt = u % NTp; rb = u / NTp; return nt < NT; };
     if (ph < H) {
         const int l = (ph - 1) / 5, k = (ph - 1) % 5;
         const LayerW& w = s.layers_dev[l];
@@ -554,23 +561,23 @@ __device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float*
         case 0:
             g.X = xb0; g.K = D.d; g.N = 3 * D.d; g.Wp = (const uint4*)w.Wqkv; g.bias = w.t_qkv; g.colsum = w.cs_qkv;
             g.stats = st0; g.epi = SE_QKV; g.out = q_l;
-            gemm_unit<4>(P, g, u / RG, (u % RG) * 64, smem, s_stat);
+            if (split(3 * D.d / 16)) gemm_unit<4>(P, g, nt, rb * 64, smem, s_stat);
             return;
         case 1: attn_unit(P, l, u, smem); return;
         case 2:
             g.X = att_l; g.K = D.d; g.N = D.d; g.Wp = (const uint4*)w.Wo; g.bias = w.bo;
             g.epi = SE_RESID; g.out = xb0 + s.act_stride; g.stats_out = st0 + s.stats_stride;
-            gemm_unit<1>(P, g, u / RB, (u % RB) * 16, smem, s_stat);
+            if (split(D.d / 16)) gemm_unit<1>(P, g, nt, rb * 16, smem, s_stat);
             return;
         case 3:
             g.X = xb0 + s.act_stride; g.K = D.d; g.N = D.F; g.Wp = (const uint4*)w.W1; g.bias = w.t_w1; g.colsum = w.cs_w1;
             g.stats = st0 + s.stats_stride; g.epi = SE_GELU; g.out = hid_l;
-            gemm_unit<4>(P, g, u / RG, (u % RG) * 64, smem, s_stat);
+            if (split(D.F / 16)) gemm_unit<4>(P, g, nt, rb * 64, smem, s_stat);
             return;
         default:
             g.X = hid_l; g.K = D.F; g.N = D.d; g.Wp = (const uint4*)w.W2; g.bias = w.b2;
             g.epi = SE_RESID; g.out = xb0 + 2 * s.act_stride; g.stats_out = st0 + 2 * s.stats_stride;
-            gemm_unit<1>(P, g, u / RB, (u % RB) * 16, smem, s_stat);
+            if (split(D.d / 16)) gemm_unit<1>(P, g, nt, rb * 16, smem, s_stat);
             return;
         }
     }
@@ -580,7 +587,7 @@ __device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float*
         g.X = s.xb + (size_t)(2 * D.Ly) * s.act_stride; g.K = D.d; g.N = D.V1; g.Wp = (const uint4*)s.W_out;
         g.bias = s.t_out; g.colsum = s.cs_out;
         g.stats = s.stats + (size_t)(2 * D.Ly) * s.stats_stride; g.epi = SE_LOGITS; g.outf = s.logits;
-        gemm_unit<4>(P, g, u / RG, (u % RG) * 64, smem, s_stat);
+        if (split(cdiv(D.V1, 16))) gemm_unit<4>(P, g, nt, rb * 64, smem, s_stat);
         return;
     case 1: dev_accept(D, s, u, P.tau, P.ignore_eos); return;
     case 2: dev_finalize<bf16_t>(D, s, P.seq0 + u, P.prefill_mode, P.ignore_eos, 1); return;
