@@ -265,6 +265,24 @@ extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena
     c->batch = 0;
     c->M = 0;
     layout(*cfg, c->arena, &c->s, &c->layers, &c->draft, nullptr, &c->staging_floats);
+    if (cfg->dtype) {
+        // the step kernel addresses layer l as layer 0 + l * stride: the layout must be that regular
+        auto off = [](const void* a, const void* b) { return (const char*)a - (const char*)b; };
+        bool ok = true;
+        for (size_t l = 1; l < c->layers.size() && ok; ++l) {
+            const LayerW &a = c->layers[0], &b = c->layers[l];
+            const ptrdiff_t st = off(c->layers[1].Wqkv, a.Wqkv) * (ptrdiff_t)l;
+            ok = off(b.Wqkv, a.Wqkv) == st && off(b.Wo, a.Wo) == st && off(b.W1, a.W1) == st && off(b.W2, a.W2) == st &&
+                 off(b.bo, a.bo) == st && off(b.b2, a.b2) == st && off(b.t_qkv, a.t_qkv) == st &&
+                 off(b.cs_qkv, a.cs_qkv) == st && off(b.t_w1, a.t_w1) == st && off(b.cs_w1, a.cs_w1) == st;
+        }
+        for (size_t i = 1; i < c->draft.size() && ok; ++i) {
+            const DraftW &a = c->draft[0], &b = c->draft[i];
+            const ptrdiff_t st = off(c->draft[1].W1, a.W1) * (ptrdiff_t)i;
+            ok = off(b.W1, a.W1) == st && off(b.b1, a.b1) == st && off(b.W2, a.W2) == st;
+        }
+        if (!ok) { delete c; return VADUSA_ESHAPE; }
+    }
     c->L_ub.assign(cfg->max_batch, 0);
     c->pending.assign(cfg->max_batch, 0);
     c->epoch = 0;
@@ -373,6 +391,9 @@ static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode,
     P.D = D; P.s = c->s; P.table = table; P.prefill_mode = prefill_mode; P.tau = tau;
     P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent;
     P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq;
+    P.lw0 = c->layers[0]; P.dw0 = c->draft[0];
+    P.lw_stride = c->layers.size() > 1 ? (size_t)((const char*)c->layers[1].Wqkv - (const char*)c->layers[0].Wqkv) : 0;
+    P.dw_stride = c->draft.size() > 1 ? (size_t)((const char*)c->draft[1].W1 - (const char*)c->draft[0].W1) : 0;
     hipError_t e;
     launch_step(P, c->n_cus, c->stream, &e);
     if (e != hipSuccess) return fail(c, VADUSA_EHIP, "step kernel launch failed: %s", hipGetErrorString(e));

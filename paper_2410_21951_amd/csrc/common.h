@@ -189,6 +189,12 @@ struct StepParams {
     int persistent;     // 1: one cooperative launch with grid barriers between phases
     uint32_t epoch;     // barrier epoch before the first barrier of this launch
     int seq0, nseq;     // sequences the compaction phases act on
+    // Every layer's parameters sit at the same offsets from the previous layer's:
+    // layer l = layer 0 advanced by l * lw_stride bytes (likewise the draft heads), so no
+    // kernel has to fetch a parameter table from memory before it can address its weights.
+    LayerW lw0;
+    DraftW dw0;
+    size_t lw_stride, dw_stride;
 };
 int step_num_phases(int n_layers);
 // phase index helpers: 0 embed; 1+5l.. layer l (qkv, attn, wo, ffn1, ffn2); then head, accept, finalize, commit+draft1, draft2, topk

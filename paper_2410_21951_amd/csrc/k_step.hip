@@ -79,7 +79,7 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     if (ph < H) {
         switch ((ph - 1) % 5) {
         case 0: return pad8(3 * D.d / 16) * RG;
-        case 1: return D.B * D.nH * cdiv(D.M, 16);
+        case 1: return pad8(D.B * D.nH) * cdiv(D.M, 16);
         case 2: return pad8(D.d / 16) * RB;
         case 3: return pad8(D.F / 16) * RG;
         default: return pad8(D.d / 16) * RB;
@@ -403,8 +403,11 @@ __device__ void attn_unit(const StepParams& P, int layer, int u, uint4* smem) {
     const Dims& D = P.D;
     const DevState& s = P.s;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, gq = lane >> 4, c = lane & 15;
-    const int QT = cdiv(D.M, 16);
-    const int qt = u % QT, h = (u / QT) % D.nH, b = u / (QT * D.nH);
+    // unit = (query tile) * pad8(B * nH) + (sequence, head): the query tiles of one head run on
+    // one XCD (workgroup i is on XCD i mod 8) and share its L2 for that head's K / V rows
+    const int BH = pad8(D.B * D.nH), bh = u % BH, qt = u / BH;
+    if (bh >= D.B * D.nH) return;
+    const int h = bh % D.nH, b = bh / D.nH;
     const int n_rows = s.n_rows[b];
     bf16_t* att = (bf16_t*)s.att + (size_t)layer * s.act_stride;
     if (n_rows == 0) {
@@ -549,7 +552,15 @@ __device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float*
     auto split = [&](int NT) { const int NTp = pad8(NT); nt = u % NTp; rb = u / NTp; return nt < NT; };
     if (ph < H) {
         const int l = (ph - 1) / 5, k = (ph - 1) % 5;
-        const LayerW& w = s.layers_dev[l];
+        LayerW w;   // layer l = layer 0 advanced by l * lw_stride bytes
+        {
+            const size_t off = (size_t)l * P.lw_stride;
+            w.Wqkv = (const char*)P.lw0.Wqkv + off; w.Wo = (const char*)P.lw0.Wo + off;
+            w.W1 = (const char*)P.lw0.W1 + off; w.W2 = (const char*)P.lw0.W2 + off;
+            w.bo = (const float*)((const char*)P.lw0.bo + off); w.b2 = (const float*)((const char*)P.lw0.b2 + off);
+            w.t_qkv = (float*)((char*)P.lw0.t_qkv + off); w.cs_qkv = (float*)((char*)P.lw0.cs_qkv + off);
+            w.t_w1 = (float*)((char*)P.lw0.t_w1 + off); w.cs_w1 = (float*)((char*)P.lw0.cs_w1 + off);
+        }
         g.layer = l;
         // slots: xb / stats 2l = input of the layer, 2l+1 = after the out-projection, 2l+2 = after FFN2
         bf16_t* xb0 = s.xb + (size_t)(2 * l) * s.act_stride;
@@ -602,7 +613,9 @@ __device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float*
         }
         u -= ncommit;
         const int per = (D.d / 16) * RGb, i = u / per, v = u % per;
-        const DraftW& dw = s.draft_dev[i];
+        DraftW dw;
+        dw.W1 = (const char*)P.dw0.W1 + (size_t)i * P.dw_stride;
+        dw.b1 = (const float*)((const char*)P.dw0.b1 + (size_t)i * P.dw_stride);
         g.R = D.B; g.X = (const bf16_t*)s.hbest; g.K = D.d; g.N = D.d;
         g.Wp = (const uint4*)dw.W1; g.bias = dw.b1; g.epi = SE_SILU_RESID;
         g.out = (bf16_t*)s.rdraft + (size_t)i * s.draft_stride;
@@ -611,7 +624,8 @@ __device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float*
     }
     case 4: {
         const int per = cdiv(D.V1, 16) * RGb, i = u / per, v = u % per;
-        const DraftW& dw = s.draft_dev[i];
+        DraftW dw;
+        dw.W2 = (const char*)P.dw0.W2 + (size_t)i * P.dw_stride;
         g.R = D.B; g.X = (const bf16_t*)s.rdraft + (size_t)i * s.draft_stride; g.K = D.d; g.N = D.V1;
         g.Wp = (const uint4*)dw.W2; g.epi = SE_F32;
         g.outf = s.zdraft + (size_t)i * D.Bmax * D.V1;
