@@ -44,44 +44,34 @@ __device__ inline int block_argbest(const float* __restrict__ z, int n, float pv
     return bi;
 }
 
-// Algorithm 1 on every edge of sequence b at once, then Sec. 2.3's choice.
-// Edge n is accepted iff fewer than tau entries of the parent's logit row rank
-// before the node's token (one wave counts one edge).  path_ok[n] = every edge
-// from the root to n accepted; the chosen node is the deepest such node,
-// smallest index among equals (canonical order = leftmost).
-// Output: path[b] = {count, node indices...}; the count is cut after the first EOS.
-__device__ inline void dev_accept(const Dims& D, const DevState& s, int b, int tau, int ignore_eos) {
-    __shared__ int s_edge[VADUSA_MAX_TREE_NODES];
-    __shared__ int s_ok[VADUSA_MAX_TREE_NODES];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    int32_t* path = s.path + (size_t)b * (VADUSA_MAX_DRAFT_HEADS + 2);
-    if (s.finished[b]) {
-        if (threadIdx.x == 0) stwi(path, 0);
-        for (int n = threadIdx.x; n < D.M; n += 256) stwi(s.edge_ok + b * D.M + n, 0);
-        return;
+// Algorithm 1, one edge: node n of sequence b is accepted iff fewer than tau entries of its
+// parent's logit row rank before its token.  One wave; every lane returns the decision.
+__device__ inline int dev_edge(const Dims& D, const DevState& s, int b, int n, int tau) {
+    if (n == 0) return 1;
+    const int lane = threadIdx.x & 63;
+    const float* z = s.logits + ((size_t)b * D.M + s.t_parent[0][n]) * D.V1;
+    const int t = s.tok[(size_t)b * D.M + n];
+    const float zt = z[t];
+    int cnt = 0;
+    for (int v0 = lane; v0 < D.V1; v0 += 64 * 17) {
+        float zv[17];
+#pragma unroll
+        for (int q = 0; q < 17; ++q) zv[q] = v0 + 64 * q < D.V1 ? z[v0 + 64 * q] : -INFINITY;
+#pragma unroll
+        for (int q = 0; q < 17; ++q) cnt += (v0 + 64 * q < D.V1 && before(zv[q], v0 + 64 * q, zt, t)) ? 1 : 0;
     }
+    return wave_sum_i(cnt) < tau;
+}
+
+// Sec. 2.3's choice from the edge decisions in s_edge (LDS, complete and visible on entry):
+// path_ok[n] = every edge from the root to n accepted; the chosen node is the deepest such
+// node, smallest index among equals (canonical order = leftmost).
+// Output: path[b] = {count, node indices...}; the count is cut after the first EOS.
+__device__ inline void dev_choose(const Dims& D, const DevState& s, int b, int ignore_eos, const int* s_edge, int* s_ok) {
+    int32_t* path = s.path + (size_t)b * (VADUSA_MAX_DRAFT_HEADS + 2);
     const int32_t* parent = s.t_parent[0];
     const int32_t* depth = s.t_depth[0];
     const int32_t* tok = s.tok + (size_t)b * D.M;
-    for (int n = wave; n < D.M; n += 4) {
-        int edge = 1;
-        if (n > 0) {
-            const float* z = s.logits + ((size_t)b * D.M + parent[n]) * D.V1;
-            const int t = tok[n];
-            const float zt = z[t];
-            int cnt = 0;
-            for (int v0 = lane; v0 < D.V1; v0 += 64 * 8) {
-                float zv[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) zv[j] = v0 + 64 * j < D.V1 ? z[v0 + 64 * j] : -INFINITY;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) cnt += (v0 + 64 * j < D.V1 && before(zv[j], v0 + 64 * j, zt, t)) ? 1 : 0;
-            }
-            edge = wave_sum_i(cnt) < tau;
-        }
-        if (lane == 0) { s_edge[n] = edge; stwi(s.edge_ok + b * D.M + n, edge); }
-    }
-    __syncthreads();
     for (int n = threadIdx.x; n < D.M; n += 256) {
         int ok = 1, m = n;
         while (m > 0) { ok &= s_edge[m]; m = parent[m]; }
@@ -103,6 +93,91 @@ __device__ inline void dev_accept(const Dims& D, const DevState& s, int b, int t
         stwi(path, cnt);
     }
     __syncthreads();
+}
+
+// Algorithm 1 on every edge of sequence b at once, then Sec. 2.3's choice.
+// Edge n is accepted iff fewer than tau entries of the parent's logit row rank
+// before the node's token (one wave counts one edge).  path_ok[n] = every edge
+// from the root to n accepted; the chosen node is the deepest such node,
+// smallest index among equals (canonical order = leftmost).
+// Output: path[b] = {count, node indices...}; the count is cut after the first EOS.
+__device__ inline void dev_accept(const Dims& D, const DevState& s, int b, int tau, int ignore_eos) {
+    __shared__ int s_edge[VADUSA_MAX_TREE_NODES];
+    __shared__ int s_ok[VADUSA_MAX_TREE_NODES];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int32_t* path = s.path + (size_t)b * (VADUSA_MAX_DRAFT_HEADS + 2);
+    if (s.finished[b]) {
+        if (threadIdx.x == 0) stwi(path, 0);
+        for (int n = threadIdx.x; n < D.M; n += 256) stwi(s.edge_ok + b * D.M + n, 0);
+        return;
+    }
+    const int32_t* parent = s.t_parent[0];
+    const int32_t* depth = s.t_depth[0];
+    const int32_t* tok = s.tok + (size_t)b * D.M;
+    // Wave w owns the edges n = w + 4j.  Lane j first fetches parent, token and the token's logit
+    // of edge j, so that chain of three dependent loads is paid once per wave, not once per
+    // edge; then the wave streams the parents' rows, two edges at a time, 17 values per lane and
+    // batch (one batch covers 1088 logits).
+    const int nj = (D.M - wave + 3) / 4;   // edges of this wave, at most 32
+    int my_par = 0, my_t = 0;
+    float my_zt = 0.f;
+    if (lane < nj && wave + 4 * lane > 0) {
+        const int n = wave + 4 * lane;
+        my_par = parent[n];
+        my_t = tok[n];
+        my_zt = s.logits[((size_t)b * D.M + my_par) * D.V1 + my_t];
+    }
+    for (int j0 = 0; j0 < nj; j0 += 2) {
+        int cnt[2] = {0, 0};
+        const float* zrow[2];
+        int tt[2];
+        float ztv[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int j = j0 + e < nj ? j0 + e : j0;   // an odd tail repeats the edge (result unused)
+            zrow[e] = s.logits + ((size_t)b * D.M + __shfl(my_par, j, 64)) * D.V1;
+            tt[e] = __shfl(my_t, j, 64);
+            ztv[e] = __shfl(my_zt, j, 64);
+        }
+        for (int v0 = lane; v0 < D.V1; v0 += 64 * 17) {
+            float zv[2][17];
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                for (int q = 0; q < 17; ++q) zv[e][q] = v0 + 64 * q < D.V1 ? zrow[e][v0 + 64 * q] : -INFINITY;
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                for (int q = 0; q < 17; ++q)
+                    cnt[e] += (v0 + 64 * q < D.V1 && before(zv[e][q], v0 + 64 * q, ztv[e], tt[e])) ? 1 : 0;
+        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int n = wave + 4 * (j0 + e);
+            const int total = wave_sum_i(cnt[e]);
+            if (j0 + e < nj && lane == 0) {
+                const int edge = n == 0 ? 1 : (total < tau);
+                s_edge[n] = edge;   // stored to memory after the loop: a store inside it would
+            }                       // put a write acknowledgement into every wait for the next rows
+        }
+    }
+    __syncthreads();
+    for (int n = threadIdx.x; n < D.M; n += 256) stwi(s.edge_ok + b * D.M + n, s_edge[n]);
+    dev_choose(D, s, b, ignore_eos, s_edge, s_ok);
+}
+
+// Sec. 2.3's choice for sequence b when the edge decisions were taken by other workgroups
+// (dev_edge) and sit in edge_ok.
+__device__ inline void dev_select(const Dims& D, const DevState& s, int b, int ignore_eos) {
+    __shared__ int s_edge[VADUSA_MAX_TREE_NODES];
+    __shared__ int s_ok[VADUSA_MAX_TREE_NODES];
+    if (s.finished[b]) {
+        if (threadIdx.x == 0) stwi(s.path + (size_t)b * (VADUSA_MAX_DRAFT_HEADS + 2), 0);
+        return;
+    }
+    for (int n = threadIdx.x; n < D.M; n += 256) s_edge[n] = s.edge_ok[b * D.M + n];
+    __syncthreads();
+    dev_choose(D, s, b, ignore_eos, s_edge, s_ok);
 }
 
 // Continue from the last accepted node (Sec. 2.1): advance L, append the
@@ -203,17 +278,59 @@ __device__ inline void dev_commit_kv(const Dims& D, const DevState& s, int layer
 }
 
 // Draft list of head i, sequence b: the VADUSA_MAX_TOPK best ids of its logits,
-// descending, equal logits: lower id first (Sec. 2.1).
+// descending, equal logits: lower id first (Sec. 2.1).  Up to 4096 logits are held in
+// registers (16 per thread); every round picks the best entry not taken yet: local best,
+// wave reduction, then one exchange through LDS (double-buffered: one barrier per round).
 __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) {
+    __shared__ float t_v[8];
+    __shared__ int t_i[8];
+    __shared__ int t_out[VADUSA_MAX_TOPK];   // the list, stored to memory once at the end
     const float* z = s.zdraft + ((size_t)i * D.Bmax + b) * D.V1;
     int32_t* out = s.draft_topk + ((size_t)b * D.Hh + i) * VADUSA_MAX_TOPK;
-    float pv = INFINITY;
-    int pi = -1;
     const int kmax = D.V1 < VADUSA_MAX_TOPK ? D.V1 : VADUSA_MAX_TOPK;
-    for (int k = 0; k < kmax; ++k) {
-        float bv;
-        const int bi = block_argbest(z, D.V1, pv, pi, &bv);
-        if (threadIdx.x == 0) stwi(out + k, bi);
-        pv = bv; pi = bi;
+    if (D.V1 > 256 * 16) {   // very large vocabularies: re-scan memory every round
+        float pv = INFINITY;
+        int pi = -1;
+        for (int k = 0; k < kmax; ++k) {
+            float bv;
+            const int bi = block_argbest(z, D.V1, pv, pi, &bv);
+            if (threadIdx.x == 0) stwi(out + k, bi);
+            pv = bv; pi = bi;
+        }
+        return;
     }
+    float zr[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const int v = threadIdx.x + 256 * j;
+        zr[j] = v < D.V1 ? z[v] : -INFINITY;
+    }
+    unsigned taken = 0;   // bit j: entry threadIdx.x + 256 j is already in the list
+    for (int k = 0; k < kmax; ++k) {
+        float lv = -INFINITY;
+        int li = 0x7fffffff;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int v = threadIdx.x + 256 * j;
+            if (v < D.V1 && !((taken >> j) & 1u) && before(zr[j], v, lv, li)) { lv = zr[j]; li = v; }
+        }
+        float bv = lv;
+        int bi = li;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(bv, o, 64);
+            const int oi = __shfl_xor(bi, o, 64);
+            if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+        }
+        const int buf = (k & 1) * 4;
+        if ((threadIdx.x & 63) == 0) { t_v[buf + (threadIdx.x >> 6)] = bv; t_i[buf + (threadIdx.x >> 6)] = bi; }
+        __syncthreads();
+        bv = t_v[buf]; bi = t_i[buf];
+        for (int w = 1; w < 4; ++w)
+            if (before(t_v[buf + w], t_i[buf + w], bv, bi)) { bv = t_v[buf + w]; bi = t_i[buf + w]; }
+        if (bi == li && li != 0x7fffffff) taken |= 1u << (bi >> 8);   // the winner was mine
+        if (threadIdx.x == 0) t_out[k] = (unsigned)bi < (unsigned)D.V1 ? bi : 0;
+    }
+    __syncthreads();   // t_out complete; the exchange buffers are free for the next unit
+    if ((int)threadIdx.x < kmax) stwi(out + threadIdx.x, t_out[threadIdx.x]);
 }

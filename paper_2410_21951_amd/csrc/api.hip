@@ -529,7 +529,7 @@ extern "C" int vadusa_prefill(vadusa_ctx* c, int32_t batch, const int32_t* text_
             // bf16 model: the chunk is a causal "tree" for the step kernel; the last chunk also runs
             // the base head, the continuation and the draft heads (acceptance has no units here)
             const int H = 1 + 5 * D.Ly;
-            int rc = run_phases(c, D, 1, 1, 1, 0, last ? H + 6 : H, 0, batch);
+            int rc = run_phases(c, D, 1, 1, 1, 0, last ? H + TP_COUNT : H, 0, batch);
             if (rc) return rc;
         } else {
             forward(c, D, 1, 1, last);
@@ -628,7 +628,7 @@ static int verify_impl(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau,
     c->M = M;
     if (c->cfg.dtype) {
         const int H = 1 + 5 * D.Ly;
-        rc = run_phases(c, D, 0, 0, tau, 0, fuse_compact ? H + 6 : H + 2, 0, B);
+        rc = run_phases(c, D, 0, 0, tau, 0, fuse_compact ? H + TP_COUNT : H + TP_FINAL, 0, B);
         if (rc) return rc;
     } else {
         forward(c, D, 0, 0, true);
@@ -679,7 +679,7 @@ extern "C" int vadusa_kv_compact(vadusa_ctx* c, int32_t seq, const int32_t* path
     }
     if (c->cfg.dtype) {
         const int H = 1 + 5 * D.Ly;
-        int rc = run_phases(c, D, 0, 0, 1, H + 2, H + 6, seq0, nseq);
+        int rc = run_phases(c, D, 0, 0, 1, H + TP_FINAL, H + TP_COUNT, seq0, nseq);
         if (rc) return rc;
     } else {
         launch_finalize(D, s, seq0, nseq, 0, c->cfg.ignore_eos, 0, c->stream);

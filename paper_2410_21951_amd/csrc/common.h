@@ -196,8 +196,10 @@ struct StepParams {
     DraftW dw0;
     size_t lw_stride, dw_stride;
 };
+// Phases of the step kernel after the decoder layers, as offsets from H = 1 + 5 * n_layers.
+enum { TP_HEAD = 0, TP_EDGES, TP_SELECT, TP_FINAL, TP_COMMIT, TP_DRAFT2, TP_TOPK, TP_COUNT };
 int step_num_phases(int n_layers);
-// phase index helpers: 0 embed; 1+5l.. layer l (qkv, attn, wo, ffn1, ffn2); then head, accept, finalize, commit+draft1, draft2, topk
+// phase index: 0 embed; 1+5l.. layer l (qkv, attn, wo, ffn1, ffn2); then H + TP_*
 void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err);
 void launch_pack_w_ln(const float* src, const float* gamma, const float* beta, void* dst, float* colsum,
                       float* tvec, int N, int K, hipStream_t st);

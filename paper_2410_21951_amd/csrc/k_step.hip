@@ -6,11 +6,12 @@
 //   0                 embed: tree expansion + token/position embedding (Sec. 2.1)
 //   1+5l .. 5+5l      layer l: QKV, attention, out-projection, FFN1, FFN2
 //   H = 1+5*Ly        base head (logits of every node; Algorithm 1 line 1)
-//   H+1               acceptance: Algorithm 1 on all edges + Sec. 2.3 path choice
-//   H+2               continuation from the last accepted node (Sec. 2.1)
-//   H+3               KV compaction to the accepted path || draft heads, first map
-//   H+4               draft heads, vocabulary map
-//   H+5               draft top-k lists
+//   H+1               acceptance: Algorithm 1 on every edge, one wave per edge
+//   H+2               Sec. 2.3 path choice per sequence
+//   H+3               continuation from the last accepted node (Sec. 2.1)
+//   H+4               KV compaction to the accepted path || draft heads, first map
+//   H+5               draft heads, vocabulary map
+//   H+6               draft top-k lists
 //
 // Linear maps stream pre-tiled bf16 weights straight from HBM into the B
 // operand of v_mfma_f32_16x16x32_bf16; activations are staged in LDS.
@@ -70,7 +71,7 @@ __host__ __device__ inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 // the tile leaves HBM once.  Numbers whose column tile is padding are empty units.
 __host__ __device__ inline int pad8(int a) { return (a + 7) & ~7; }
 
-int step_num_phases(int n_layers) { return 1 + 5 * n_layers + 6; }
+int step_num_phases(int n_layers) { return 1 + 5 * n_layers + TP_COUNT; }
 
 __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     const Dims& D = P.D;
@@ -87,11 +88,12 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     }
     const int RGb = cdiv(D.B, 64);
     switch (ph - H) {
-    case 0: return pad8(cdiv(D.V1, 16)) * RG;
-    case 1: return P.prefill_mode ? 0 : D.B;
-    case 2: return P.nseq;
-    case 3: return D.Ly * D.nH * P.nseq + D.Hh * (D.d / 16) * RGb;
-    case 4: return D.Hh * cdiv(D.V1, 16) * RGb;
+    case TP_HEAD: return pad8(cdiv(D.V1, 16)) * RG;
+    case TP_EDGES: return P.prefill_mode ? 0 : cdiv(R, 4);
+    case TP_SELECT: return P.prefill_mode ? 0 : P.nseq;
+    case TP_FINAL: return P.nseq;
+    case TP_COMMIT: return D.Ly * D.nH * P.nseq + D.Hh * (D.d / 16) * RGb;
+    case TP_DRAFT2: return D.Hh * cdiv(D.V1, 16) * RGb;
     default: return D.Hh * D.B;
     }
 }
@@ -539,7 +541,7 @@ __device__ void attn_unit(const StepParams& P, int layer, int u, uint4* smem) {
 // ---------------------------------------------------------------------------
 // one unit of one phase
 // ---------------------------------------------------------------------------
-__device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float* s_stat) {
+__device__ __forceinline__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float* s_stat) {
     const Dims& D = P.D;
     const DevState& s = P.s;
     const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
@@ -594,15 +596,24 @@ __device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float*
     }
     const int RGb = cdiv(D.B, 64);
     switch (ph - H) {
-    case 0:
+    case TP_HEAD:
         g.X = s.xb + (size_t)(2 * D.Ly) * s.act_stride; g.K = D.d; g.N = D.V1; g.Wp = (const uint4*)s.W_out;
         g.bias = s.t_out; g.colsum = s.cs_out;
         g.stats = s.stats + (size_t)(2 * D.Ly) * s.stats_stride; g.epi = SE_LOGITS; g.outf = s.logits;
         if (split(cdiv(D.V1, 16))) gemm_unit<4>(P, g, nt, rb * 64, smem, s_stat);
         return;
-    case 1: dev_accept(D, s, u, P.tau, P.ignore_eos); return;
-    case 2: dev_finalize<bf16_t>(D, s, P.seq0 + u, P.prefill_mode, P.ignore_eos, 1); return;
-    case 3: {
+    case TP_EDGES: {   // one edge per wave: unit u takes edges 4u .. 4u+3 of the B * M rows
+        const int e = u * 4 + (int)(threadIdx.x >> 6);
+        if (e < R) {
+            const int b = e / D.M, n = e - b * D.M;
+            const int ok = s.finished[b] ? 0 : dev_edge(D, s, b, n, P.tau);
+            if ((threadIdx.x & 63) == 0) stwi(s.edge_ok + e, ok);
+        }
+        return;
+    }
+    case TP_SELECT: dev_select(D, s, P.seq0 + u, P.ignore_eos); return;
+    case TP_FINAL: dev_finalize<bf16_t>(D, s, P.seq0 + u, P.prefill_mode, P.ignore_eos, 1); return;
+    case TP_COMMIT: {
         const int ncommit = D.Ly * D.nH * P.nseq;
         if (u < ncommit) {
             if (threadIdx.x < 64) {
@@ -622,7 +633,7 @@ __device__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float*
         gemm_unit<4>(P, g, v / RGb, (v % RGb) * 64, smem, s_stat);
         return;
     }
-    case 4: {
+    case TP_DRAFT2: {
         const int per = cdiv(D.V1, 16) * RGb, i = u / per, v = u % per;
         DraftW dw;
         dw.W2 = (const char*)P.dw0.W2 + (size_t)i * P.dw_stride;
