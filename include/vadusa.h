@@ -210,7 +210,9 @@ enum {
     VADUSA_DBG_DRAFT_LOGITS = 9, /* float [batch][n_draft_heads][V+1], logits behind the lists */
     VADUSA_DBG_PHASE_CLOCK = 10  /* int64 [128][8]: device clock (100 MHz) of workgroup 0 in the last launch of
                                     the bf16 step kernel: [p][0] start of phase p, [p][1] its own units done,
-                                    [p][2..] points inside a unit, [127][0] end of the kernel */
+                                    [p][2..] points inside a unit, [127][0] end of the kernel.  Recorded only by
+                                    contexts created while the environment variable VADUSA_PHASE_CLOCK is set
+                                    (each point costs a few hundred ns); zero otherwise */
 };
 
 /* Copies one of the items above to host memory after synchronising the stream.

@@ -278,17 +278,74 @@ __device__ inline void dev_commit_kv(const Dims& D, const DevState& s, int layer
 }
 
 // Draft list of head i, sequence b: the VADUSA_MAX_TOPK best ids of its logits,
-// descending, equal logits: lower id first (Sec. 2.1).  Up to 4096 logits are held in
-// registers (16 per thread); every round picks the best entry not taken yet: local best,
-// wave reduction, then one exchange through LDS (double-buffered: one barrier per round).
+// descending, equal logits: lower id first (Sec. 2.1).
+// Up to 4096 logits sit in registers (16 per thread).  The 256 threads form 16 groups of 16
+// lanes; the 16 group maxima are 16 distinct entries, so the 16th best entry overall is not
+// after the last of them, T.  Every entry not after T is a candidate (a few dozen for random
+// logits); each candidate counts the candidates before it, which is its place in the list.
+// More than 256 candidates (many equal or missing values), or more than 4096 logits: the
+// list is built one entry per round by re-scanning (block_argbest).
 __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) {
-    __shared__ float t_v[8];
-    __shared__ int t_i[8];
-    __shared__ int t_out[VADUSA_MAX_TOPK];   // the list, stored to memory once at the end
+    __shared__ float c_v[256];
+    __shared__ int c_i[256];
+    __shared__ float g_v[16];
+    __shared__ int g_i[16];
+    __shared__ int c_n;
     const float* z = s.zdraft + ((size_t)i * D.Bmax + b) * D.V1;
     int32_t* out = s.draft_topk + ((size_t)b * D.Hh + i) * VADUSA_MAX_TOPK;
     const int kmax = D.V1 < VADUSA_MAX_TOPK ? D.V1 : VADUSA_MAX_TOPK;
-    if (D.V1 > 256 * 16) {   // very large vocabularies: re-scan memory every round
+    bool rescan = D.V1 > 256 * 16;
+    if (!rescan) {
+        float zr[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int v = threadIdx.x + 256 * j;
+            zr[j] = v < D.V1 ? z[v] : -INFINITY;
+        }
+        float lv = -INFINITY;
+        int li = 0x7fffffff;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int v = threadIdx.x + 256 * j;
+            if (v < D.V1 && before(zr[j], v, lv, li)) { lv = zr[j]; li = v; }
+        }
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) {   // best of each group of 16 lanes
+            const float ov = __shfl_xor(lv, o, 64);
+            const int oi = __shfl_xor(li, o, 64);
+            if (before(ov, oi, lv, li)) { lv = ov; li = oi; }
+        }
+        if ((threadIdx.x & 15) == 0) { g_v[threadIdx.x >> 4] = lv; g_i[threadIdx.x >> 4] = li; }
+        if (threadIdx.x == 0) c_n = 0;
+        __syncthreads();
+        float tv = g_v[0];
+        int ti = g_i[0];
+        for (int g = 1; g < 16; ++g)
+            if (before(tv, ti, g_v[g], g_i[g])) { tv = g_v[g]; ti = g_i[g]; }   // T = the last of the group maxima
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int v = threadIdx.x + 256 * j;
+            if (v < D.V1 && !before(tv, ti, zr[j], v)) {
+                const int slot = atomicAdd(&c_n, 1);
+                if (slot < 256) { c_v[slot] = zr[j]; c_i[slot] = v; }
+            }
+        }
+        __syncthreads();
+        const int n = c_n;
+        if (n <= 256) {
+            if ((int)threadIdx.x < n) {
+                const float mv = c_v[threadIdx.x];
+                const int mi = c_i[threadIdx.x];
+                int r = 0;
+                for (int t = 0; t < n; ++t) r += before(c_v[t], c_i[t], mv, mi) ? 1 : 0;
+                if (r < kmax) stwi(out + r, mi);
+            }
+        } else {
+            rescan = true;   // n is the same for every thread
+        }
+        __syncthreads();     // the LDS arrays are free for the next unit
+    }
+    if (rescan) {
         float pv = INFINITY;
         int pi = -1;
         for (int k = 0; k < kmax; ++k) {
@@ -297,40 +354,5 @@ __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) 
             if (threadIdx.x == 0) stwi(out + k, bi);
             pv = bv; pi = bi;
         }
-        return;
     }
-    float zr[16];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        const int v = threadIdx.x + 256 * j;
-        zr[j] = v < D.V1 ? z[v] : -INFINITY;
-    }
-    unsigned taken = 0;   // bit j: entry threadIdx.x + 256 j is already in the list
-    for (int k = 0; k < kmax; ++k) {
-        float lv = -INFINITY;
-        int li = 0x7fffffff;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int v = threadIdx.x + 256 * j;
-            if (v < D.V1 && !((taken >> j) & 1u) && before(zr[j], v, lv, li)) { lv = zr[j]; li = v; }
-        }
-        float bv = lv;
-        int bi = li;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const float ov = __shfl_xor(bv, o, 64);
-            const int oi = __shfl_xor(bi, o, 64);
-            if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-        }
-        const int buf = (k & 1) * 4;
-        if ((threadIdx.x & 63) == 0) { t_v[buf + (threadIdx.x >> 6)] = bv; t_i[buf + (threadIdx.x >> 6)] = bi; }
-        __syncthreads();
-        bv = t_v[buf]; bi = t_i[buf];
-        for (int w = 1; w < 4; ++w)
-            if (before(t_v[buf + w], t_i[buf + w], bv, bi)) { bv = t_v[buf + w]; bi = t_i[buf + w]; }
-        if (bi == li && li != 0x7fffffff) taken |= 1u << (bi >> 8);   // the winner was mine
-        if (threadIdx.x == 0) t_out[k] = (unsigned)bi < (unsigned)D.V1 ? bi : 0;
-    }
-    __syncthreads();   // t_out complete; the exchange buffers are free for the next unit
-    if ((int)threadIdx.x < kmax) stwi(out + threadIdx.x, t_out[threadIdx.x]);
 }

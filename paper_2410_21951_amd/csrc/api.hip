@@ -287,6 +287,7 @@ extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena
     c->pending.assign(cfg->max_batch, 0);
     c->epoch = 0;
     c->persistent = getenv("VADUSA_PHASE_LAUNCHES") ? 0 : 1;
+    c->profile = getenv("VADUSA_PHASE_CLOCK") ? 1 : 0;
     {
         int dev = 0;
         hipDeviceProp_t prop;
@@ -389,7 +390,7 @@ static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode,
                       int seq0, int nseq) {
     StepParams P;
     P.D = D; P.s = c->s; P.table = table; P.prefill_mode = prefill_mode; P.tau = tau;
-    P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent;
+    P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent; P.profile = c->profile;
     P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq;
     P.lw0 = c->layers[0]; P.dw0 = c->draft[0];
     P.lw_stride = c->layers.size() > 1 ? (size_t)((const char*)c->layers[1].Wqkv - (const char*)c->layers[0].Wqkv) : 0;

@@ -24,17 +24,44 @@ __device__ __forceinline__ float ldf(const bf16_t* p) { return bf2f(*p); }
 __device__ __forceinline__ void stf(float* p, float v) { *p = v; }
 __device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f2bf(v); }
 
+// Every pointer the kernels dereference points into device (global) memory.  A pointer that
+// reaches a function as an argument, or is read from a parameter block in LDS, is a generic
+// pointer to the compiler and would be accessed with FLAT instructions (slower to issue, and
+// tied to the LDS counter as well); the helpers below state the address space.
+#if defined(__HIP_DEVICE_COMPILE__)
+#define VADUSA_GLOBAL __attribute__((address_space(1)))
+#else
+#define VADUSA_GLOBAL
+#endif
+template <class T>
+__device__ __forceinline__ T ldg(const T* p) { return *(const VADUSA_GLOBAL T*)p; }   // scalar T only
+// 8- and 16-byte loads (HIP's uint2 / uint4 / float2 are classes: their copy would go back to a generic reference)
+typedef uint32_t vadusa_u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t vadusa_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 ldg4(const void* p) {
+    const vadusa_u32x4 v = *(const VADUSA_GLOBAL vadusa_u32x4*)p;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 ldg2(const void* p) {
+    const vadusa_u32x2 v = *(const VADUSA_GLOBAL vadusa_u32x2*)p;
+    return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ float2 ldgf2(const void* p) {
+    const vadusa_u32x2 v = *(const VADUSA_GLOBAL vadusa_u32x2*)p;
+    return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
+}
+
 // Stores / loads that are coherent across the whole GPU without cache maintenance
 // (write-through to / read from the memory side).  The persistent step kernel uses them
 // for every value that crosses workgroups inside one launch.
 __device__ __forceinline__ void stw32(void* p, uint32_t v) {
-    __hip_atomic_store((uint32_t*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store((VADUSA_GLOBAL uint32_t*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void stw64(void* p, uint64_t v) {
-    __hip_atomic_store((uint64_t*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store((VADUSA_GLOBAL uint64_t*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void stw16(void* p, uint16_t v) {
-    __hip_atomic_store((uint16_t*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store((VADUSA_GLOBAL uint16_t*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void stwi(int32_t* p, int32_t v) { stw32(p, (uint32_t)v); }
 __device__ __forceinline__ void stwf(float* p, float v) { stw32(p, __float_as_uint(v)); }
@@ -42,10 +69,10 @@ __device__ __forceinline__ void stwf2(float* p, float a, float b) {
     stw64(p, (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32));
 }
 __device__ __forceinline__ int32_t ldci(const int32_t* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load((const VADUSA_GLOBAL int32_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float ldcf(const float* p) {
-    return __uint_as_float(__hip_atomic_load((const uint32_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    return __uint_as_float(__hip_atomic_load((const VADUSA_GLOBAL uint32_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 }
 // Offset of element (r, k) of a bf16 activation matrix kept in MFMA-operand tiles:
 // [row tile of 16][k-step of 32][lane = (r & 15) + 16 * ((k & 31) >> 3)][k & 7], nks = K / 32.
@@ -150,6 +177,7 @@ struct vadusa_ctx {
     size_t staging_floats;
     int n_cus;                   // workgroups of the persistent step kernel (one per compute unit)
     int persistent;              // 0: one launch per phase (debugging aid)
+    int profile;                 // 1: the step kernel records timing points (environment VADUSA_PHASE_CLOCK)
     uint32_t epoch;              // grid-barrier epoch reached so far
     std::string err;
 };
@@ -187,6 +215,7 @@ struct StepParams {
     int tau, ignore_eos;
     int ph_lo, ph_hi;   // phases to run: [ph_lo, ph_hi)
     int persistent;     // 1: one cooperative launch with grid barriers between phases
+    int profile;        // 1: workgroup 0 records timing points (costs a few hundred ns each)
     uint32_t epoch;     // barrier epoch before the first barrier of this launch
     int seq0, nseq;     // sequences the compaction phases act on
     // Every layer's parameters sit at the same offsets from the previous layer's:

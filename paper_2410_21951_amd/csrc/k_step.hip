@@ -59,6 +59,10 @@ struct GemmD {
     int ph;               // phase index (timing points only)
 };
 
+// The kernel's parameters, copied once per workgroup from the kernel-argument segment (which
+// may live in host memory) into LDS.  Every device function reads them from here.
+__shared__ StepParams sP;
+
 __device__ __forceinline__ float gelu_s(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752f)); }
 __device__ __forceinline__ float silu_s(float v) { return v / (1.f + __expf(-v)); }
 
@@ -100,8 +104,9 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
 
 // Timing points of workgroup 0 (device clock, 100 MHz): tprof[phase][k]; k = 0 phase start,
 // 1 own units done, 2.. points inside a unit.  Read back through vadusa_debug_read.
-__device__ __forceinline__ void tp(const StepParams& P, int ph, int k) {
-    if (blockIdx.x == 0 && threadIdx.x == 0 && ph < 128) P.s.tprof[ph * 8 + k] = wall_clock64();
+__device__ __forceinline__ void tp(int ph, int k) {
+    const StepParams& P = sP;
+    if (P.profile && blockIdx.x == 0 && threadIdx.x == 0 && ph < 128) P.s.tprof[ph * 8 + k] = wall_clock64();
 }
 
 // ---------------------------------------------------------------------------
@@ -113,10 +118,11 @@ __device__ __forceinline__ void tp(const StepParams& P, int ph, int k) {
 // error flag, the workgroup gives up and the kernel ends (the host reports it).
 // ---------------------------------------------------------------------------
 #define BAR_GROUPS 16
-__device__ bool grid_sync(const StepParams& P, uint32_t epoch, int ph) {
+__device__ bool grid_sync(uint32_t epoch, int ph) {
+    const StepParams& P = sP;
     __shared__ int s_ok;
     __syncthreads();   // every wave's stores have completed (write-through: at the memory side)
-    tp(P, ph, 4);
+    tp(ph, 4);
     if (threadIdx.x == 0) {
         uint32_t* bar = P.s.bar;
         const int g = blockIdx.x % BAR_GROUPS;
@@ -148,12 +154,14 @@ __device__ bool grid_sync(const StepParams& P, uint32_t epoch, int ph) {
 // embed (phase 0): one unit per row.  Writes x (fp32), its bf16 copy and the
 // per-tile row statistics.
 // ---------------------------------------------------------------------------
-__device__ void embed_unit(const StepParams& P, int r) {
+__device__ __forceinline__ void embed_unit(int r_) {
+    const int r = __builtin_amdgcn_readfirstlane(r_);
+    const StepParams& P = sP;
     const Dims& D = P.D;
     const DevState& s = P.s;
     const int b = r / D.M, n = r % D.M, tid = threadIdx.x;
     int rows;
-    if (P.prefill_mode) rows = s.n_rows[b];
+    if (P.prefill_mode) rows = ldg(s.n_rows + b);
     else rows = s.finished[b] ? 0 : D.M;
     if (!P.prefill_mode && n == 0 && tid == 0) stwi(s.n_rows + b, rows);
     const bool valid = n < rows;
@@ -162,12 +170,12 @@ __device__ void embed_unit(const StepParams& P, int r) {
     if (valid) {
         if (P.prefill_mode) {
             const int t = s.chunk_tok[r];
-            pos = s.L[b] + n;
+            pos = ldg(s.L + b) + n;
             if (t < 0) { tok = -t - 1; E = (const bf16_t*)s.E_text; }
             else tok = t;
         } else {
             const int dep = s.t_depth[P.table][n];
-            pos = s.L[b] + dep;
+            pos = ldg(s.L + b) + dep;
             tok = n == 0 ? s.root[b]
                          : s.draft_topk[((size_t)b * D.Hh + (dep - 1)) * VADUSA_MAX_TOPK + s.t_rank[P.table][n]];
         }
@@ -182,7 +190,7 @@ __device__ void embed_unit(const StepParams& P, int r) {
     const int R = D.B * D.M;
     for (int c0 = tid * 4; c0 < D.d; c0 += 1024) {
         float v[4];
-        const uint2 ev = *(const uint2*)(e + c0), pv = *(const uint2*)(p + c0);
+        const uint2 ev = ldg2(e + c0), pv = ldg2(p + c0);
         v[0] = bf2f((bf16_t)ev.x) + bf2f((bf16_t)pv.x);
         v[1] = bf2f((bf16_t)(ev.x >> 16)) + bf2f((bf16_t)(pv.x >> 16));
         v[2] = bf2f((bf16_t)ev.y) + bf2f((bf16_t)pv.y);
@@ -204,6 +212,94 @@ __device__ void embed_unit(const StepParams& P, int r) {
     }
 }
 
+// Descriptor of linear-map unit u of phase ph (all values are workgroup-uniform).  Returns false
+// for an empty unit (padding of the XCD-aware numbering) and for phases that are not linear maps.
+__device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, int& row0) {
+    const StepParams& P = sP;
+    const Dims& D = P.D;
+    const DevState& s = P.s;
+    const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
+    if (ph == 0) return false;
+    g.R = R; g.stats = nullptr; g.colsum = nullptr; g.bias = nullptr; g.out = nullptr; g.outf = nullptr;
+    g.stats_out = nullptr; g.layer = 0; g.ph = ph;
+    // (column tile, row block) of unit u of a map with NT column tiles; false: empty unit
+    int rb = 0;
+    nt = 0; row0 = 0;
+    auto split = [&](int NT) { const int NTp = pad8(NT); nt = u % NTp; rb = u / NTp; return nt < NT; };
+    if (ph < H) {
+        const int l = (ph - 1) / 5, k = (ph - 1) % 5;
+        LayerW w;   // layer l = layer 0 advanced by l * lw_stride bytes
+        {
+            const size_t off = (size_t)l * P.lw_stride;
+            w.Wqkv = (const char*)P.lw0.Wqkv + off; w.Wo = (const char*)P.lw0.Wo + off;
+            w.W1 = (const char*)P.lw0.W1 + off; w.W2 = (const char*)P.lw0.W2 + off;
+            w.bo = (const float*)((const char*)P.lw0.bo + off); w.b2 = (const float*)((const char*)P.lw0.b2 + off);
+            w.t_qkv = (float*)((char*)P.lw0.t_qkv + off); w.cs_qkv = (float*)((char*)P.lw0.cs_qkv + off);
+            w.t_w1 = (float*)((char*)P.lw0.t_w1 + off); w.cs_w1 = (float*)((char*)P.lw0.cs_w1 + off);
+        }
+        g.layer = l;
+        // slots: xb / stats 2l = input of the layer, 2l+1 = after the out-projection, 2l+2 = after FFN2
+        bf16_t* xb0 = s.xb + (size_t)(2 * l) * s.act_stride;
+        float* st0 = s.stats + (size_t)(2 * l) * s.stats_stride;
+        bf16_t* q_l = (bf16_t*)s.q + (size_t)l * s.act_stride;
+        bf16_t* att_l = (bf16_t*)s.att + (size_t)l * s.act_stride;
+        bf16_t* hid_l = (bf16_t*)s.hid + (size_t)l * s.hid_stride;
+        switch (k) {
+        case 0:
+            g.X = xb0; g.K = D.d; g.N = 3 * D.d; g.Wp = (const uint4*)w.Wqkv; g.bias = w.t_qkv; g.colsum = w.cs_qkv;
+            g.stats = st0; g.epi = SE_QKV; g.out = q_l;
+            return split(3 * D.d / 16) ? (row0 = rb * 64, true) : false;
+        case 1: return false;
+        case 2:
+            g.X = att_l; g.K = D.d; g.N = D.d; g.Wp = (const uint4*)w.Wo; g.bias = w.bo;
+            g.epi = SE_RESID; g.out = xb0 + s.act_stride; g.stats_out = st0 + s.stats_stride;
+            return split(D.d / 16) ? (row0 = rb * 16, true) : false;
+        case 3:
+            g.X = xb0 + s.act_stride; g.K = D.d; g.N = D.F; g.Wp = (const uint4*)w.W1; g.bias = w.t_w1; g.colsum = w.cs_w1;
+            g.stats = st0 + s.stats_stride; g.epi = SE_GELU; g.out = hid_l;
+            return split(D.F / 16) ? (row0 = rb * 64, true) : false;
+        default:
+            g.X = hid_l; g.K = D.F; g.N = D.d; g.Wp = (const uint4*)w.W2; g.bias = w.b2;
+            g.epi = SE_RESID; g.out = xb0 + 2 * s.act_stride; g.stats_out = st0 + 2 * s.stats_stride;
+            return split(D.d / 16) ? (row0 = rb * 16, true) : false;
+        }
+    }
+    const int RGb = cdiv(D.B, 64);
+    switch (ph - H) {
+    case TP_HEAD:
+        g.X = s.xb + (size_t)(2 * D.Ly) * s.act_stride; g.K = D.d; g.N = D.V1; g.Wp = (const uint4*)s.W_out;
+        g.bias = s.t_out; g.colsum = s.cs_out;
+        g.stats = s.stats + (size_t)(2 * D.Ly) * s.stats_stride; g.epi = SE_LOGITS; g.outf = s.logits;
+        return split(cdiv(D.V1, 16)) ? (row0 = rb * 64, true) : false;
+    case TP_COMMIT: {
+        const int ncommit = D.Ly * D.nH * P.nseq;
+        if (u < ncommit) return false;
+        u -= ncommit;
+        const int per = (D.d / 16) * RGb, i = u / per, v = u % per;
+        DraftW dw;
+        dw.W1 = (const char*)P.dw0.W1 + (size_t)i * P.dw_stride;
+        dw.b1 = (const float*)((const char*)P.dw0.b1 + (size_t)i * P.dw_stride);
+        g.R = D.B; g.X = (const bf16_t*)s.hbest; g.K = D.d; g.N = D.d;
+        g.Wp = (const uint4*)dw.W1; g.bias = dw.b1; g.epi = SE_SILU_RESID;
+        g.out = (bf16_t*)s.rdraft + (size_t)i * s.draft_stride;
+        nt = v / RGb; row0 = (v % RGb) * 64;
+        return true;
+    }
+    case TP_DRAFT2: {
+        const int per = cdiv(D.V1, 16) * RGb, i = u / per, v = u % per;
+        DraftW dw;
+        dw.W2 = (const char*)P.dw0.W2 + (size_t)i * P.dw_stride;
+        g.R = D.B; g.X = (const bf16_t*)s.rdraft + (size_t)i * s.draft_stride; g.K = D.d; g.N = D.V1;
+        g.Wp = (const uint4*)dw.W2; g.epi = SE_F32;
+        g.outf = s.zdraft + (size_t)i * D.Bmax * D.V1;
+        nt = v / RGb; row0 = (v % RGb) * 64;
+        return true;
+    }
+    default: return false;
+    }
+}
+
+
 // ---------------------------------------------------------------------------
 // linear-map unit.  NRT = 4: 64 rows x one 16-column tile (QKV, FFN1, heads).
 // NRT = 1: 16 rows x one tile (out-projection, FFN2: residual update +
@@ -215,7 +311,15 @@ __device__ void embed_unit(const StepParams& P, int r) {
 // sums are combined in wave order through LDS.
 // ---------------------------------------------------------------------------
 template <int NRT>
-__device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0, uint4* smem, float* s_stat) {
+__device__ __forceinline__ void gemm_unit(int ph_, int u_) {
+    // arguments arrive in vector registers: make them (and all that follows from them) scalar
+    const int ph_u = __builtin_amdgcn_readfirstlane(ph_), u_u = __builtin_amdgcn_readfirstlane(u_);
+    const StepParams& P = sP;
+    GemmD g;
+    int nt, row0;
+    if (!describe_gemm(ph_u, u_u, g, nt, row0)) return;
+    extern __shared__ uint4 smem[];
+    float* s_stat = (float*)((char*)smem + ST_TILE_BYTES);
     constexpr int CH = NRT == 4 ? 8 : 16;     // k-steps per chunk
     constexpr int ROWS = NRT * 16;
     const Dims& D = P.D;
@@ -235,7 +339,7 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
     f32x4_t acc[NRT];
 #pragma unroll
     for (int i = 0; i < NRT; ++i) acc[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-    tp(P, g.ph, 5);
+    tp(g.ph, 5);
 
     // row statistics of the LayerNorm folded into this map: four threads per row, each
     // merges a quarter of the 16-column tiles (loads issued with the first operand chunk)
@@ -248,16 +352,16 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int ks = kb + i;
-            bw[i] = ks < ks_hi ? Wp[(size_t)ks * 64] : make_uint4(0, 0, 0, 0);
+            bw[i] = ks < ks_hi ? ldg4(Wp + (size_t)ks * 64) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
                 const int ks = kb + i;
-                aw[rt][i] = (ks < ks_hi && rowok[rt]) ? Ap[rt][(size_t)ks * 64] : make_uint4(0, 0, 0, 0);
+                aw[rt][i] = (ks < ks_hi && rowok[rt]) ? ldg4(Ap[rt] + (size_t)ks * 64) : make_uint4(0, 0, 0, 0);
             }
-        if (kb == ks_lo) tp(P, g.ph, 6);
+        if (kb == ks_lo) tp(g.ph, 6);
         if (kb == ks_lo && do_stats) {
             const int row = tid >> 2, part = tid & 3, r = row0 + row;
             if (r < g.R) {
@@ -267,14 +371,14 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         const int t = t0 + 4 * j;
-                        v[j] = t < tiles ? sp[(size_t)t * g.R] : make_float2(0.f, 0.f);
+                        v[j] = t < tiles ? ldgf2(sp + (size_t)t * g.R) : make_float2(0.f, 0.f);
                     }
 #pragma unroll
                     for (int j = 0; j < 8; ++j) { s1 += v[j].x; s2 += v[j].y; s3 += v[j].x * v[j].x; }
                 }
             }
         }
-        if (kb == ks_lo) tp(P, g.ph, 7);
+        if (kb == ks_lo) tp(g.ph, 7);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bw[i]);
@@ -284,7 +388,7 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
                                                                   acc[rt], 0, 0, 0);
         }
     }
-    tp(P, g.ph, 2);   // operands arrived, MFMAs issued
+    tp(g.ph, 2);   // operands arrived, MFMAs issued
     if (g.stats) {
         s1 += __shfl_xor(s1, 1, 64); s1 += __shfl_xor(s1, 2, 64);
         s2 += __shfl_xor(s2, 1, 64); s2 += __shfl_xor(s2, 2, 64);
@@ -304,7 +408,7 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
 #pragma unroll
         for (int i = 0; i < 4; ++i) red[((wave * NRT + rt) * 64 + lane) * 4 + i] = acc[rt][i];
     __syncthreads();
-    tp(P, g.ph, 3);   // partial sums exchanged
+    tp(g.ph, 3);   // partial sums exchanged
 
     if (NRT == 4) {
         const int row = tid >> 2, rt = row >> 4, rr = row & 15, r = row0 + row;
@@ -320,8 +424,8 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
 #pragma unroll
                 for (int w = 1; w < 4; ++w) a += red[w * 1024 + src];
                 if (n < g.N) {
-                    if (g.stats) a = rstd * (a - mu * g.colsum[n]);
-                    if (g.bias) a += g.bias[n];
+                    if (g.stats) a = rstd * (a - mu * ldg(g.colsum + n));
+                    if (g.bias) a += ldg(g.bias + n);
                 }
                 v[j] = a;
             }
@@ -339,7 +443,7 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
                     if (full || n0 + j < g.N) stwf(g.outf + (size_t)r * g.N + n0 + j, v[j]);
                 break;
             case SE_SILU_RESID: {
-                const uint2 xin = *(const uint2*)(g.X + toff(r, n0, g.K >> 5));
+                const uint2 xin = ldg2(g.X + toff(r, n0, g.K >> 5));
                 const float h0 = bf2f((bf16_t)xin.x) + silu_s(v[0]), h1 = bf2f((bf16_t)(xin.x >> 16)) + silu_s(v[1]);
                 const float h2 = bf2f((bf16_t)xin.y) + silu_s(v[2]), h3 = bf2f((bf16_t)(xin.y >> 16)) + silu_s(v[3]);
                 stw64(g.out + toff(r, n0, g.N >> 5), (uint64_t)pack_bf16(h0, h1) | ((uint64_t)pack_bf16(h2, h3) << 32));
@@ -350,8 +454,8 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
                 if (n0 < D.d) { stw64(g.out + toff(r, n0, D.d >> 5), pk); break; }
                 const int b = r / D.M, node = r - b * D.M;
                 const int which = n0 / D.d - 1, cc = n0 % D.d, head = cc >> 6, dim = cc & 63;
-                const int pos = s.L[b] + node;
-                if (pos < D.maxpos && s.n_rows[b] > 0) {
+                const int pos = ldg(s.L + b) + node;
+                if (pos < D.maxpos && ldg(s.n_rows + b) > 0) {
                     const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
                     if (which) {
                         bf16_t* vp = (bf16_t*)s.Vc + hb + (size_t)dim * D.maxpos + pos;   // V is kept [dim][pos]
@@ -376,7 +480,7 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
         const bool ok = r < g.R;
         float xn = 0.f;
         if (ok) {
-            xn = s.x[(size_t)r * g.N + n] + v + g.bias[n];
+            xn = ldg(s.x + (size_t)r * g.N + n) + v + ldg(g.bias + n);
             stwf(s.x + (size_t)r * g.N + n, xn);
         }
         {
@@ -401,7 +505,10 @@ __device__ void gemm_unit(const StepParams& P, const GemmD& g, int nt, int row0,
 // round-robin with a private online softmax (S^T = K Q^T, O^T += V^T P^T on
 // MFMA), then merge through LDS.  K is kept [pos][64], V is kept [64][pos].
 // ---------------------------------------------------------------------------
-__device__ void attn_unit(const StepParams& P, int layer, int u, uint4* smem) {
+__device__ __forceinline__ void attn_unit(int ph_, int u_) {
+    const int layer = (__builtin_amdgcn_readfirstlane(ph_) - 1) / 5, u = __builtin_amdgcn_readfirstlane(u_);
+    const StepParams& P = sP;
+    extern __shared__ uint4 smem[];
     const Dims& D = P.D;
     const DevState& s = P.s;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, gq = lane >> 4, c = lane & 15;
@@ -410,14 +517,14 @@ __device__ void attn_unit(const StepParams& P, int layer, int u, uint4* smem) {
     const int BH = pad8(D.B * D.nH), bh = u % BH, qt = u / BH;
     if (bh >= D.B * D.nH) return;
     const int h = bh % D.nH, b = bh / D.nH;
-    const int n_rows = s.n_rows[b];
+    const int n_rows = ldg(s.n_rows + b);
     bf16_t* att = (bf16_t*)s.att + (size_t)layer * s.act_stride;
     if (n_rows == 0) {
         const int q = tid >> 4, d0 = (tid & 15) * 4, node = qt * 16 + q;
         if (node < D.M) stw64(att + toff(b * D.M + node, h * 64 + d0, D.d >> 5), 0ull);
         return;
     }
-    const int L = s.L[b];
+    const int L = ldg(s.L + b);
     const int T = min(L + D.M, D.maxpos);
     const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + h) * D.maxpos) * 64;
     const bf16_t* Kh = (const bf16_t*)s.Kc + hb;
@@ -425,9 +532,9 @@ __device__ void attn_unit(const StepParams& P, int layer, int u, uint4* smem) {
     const int node = min(qt * 16 + c, D.M - 1);
     const bf16_t* ql = (const bf16_t*)s.q + (size_t)layer * s.act_stride;
     const int qrow = b * D.M + node;
-    const bf16x8_t Q0 = __builtin_bit_cast(bf16x8_t, *(const uint4*)(ql + toff(qrow, h * 64 + 8 * gq, D.d >> 5)));
-    const bf16x8_t Q1 = __builtin_bit_cast(bf16x8_t, *(const uint4*)(ql + toff(qrow, h * 64 + 32 + 8 * gq, D.d >> 5)));
-    const uint4 mw = *(const uint4*)(s.t_mask[P.table] + (size_t)node * MASK_WORDS);
+    const bf16x8_t Q0 = __builtin_bit_cast(bf16x8_t, ldg4(ql + toff(qrow, h * 64 + 8 * gq, D.d >> 5)));
+    const bf16x8_t Q1 = __builtin_bit_cast(bf16x8_t, ldg4(ql + toff(qrow, h * 64 + 32 + 8 * gq, D.d >> 5)));
+    const uint4 mw = ldg4(s.t_mask[P.table] + (size_t)node * MASK_WORDS);
     const uint32_t mword[4] = {mw.x, mw.y, mw.z, mw.w};
 
     float m_run = -1e30f, l_run = 0.f;
@@ -441,11 +548,11 @@ __device__ void attn_unit(const StepParams& P, int layer, int u, uint4* smem) {
         const int keyA = p0 + 8 * (c >> 2) + (c & 3), keyB = keyA + 4;
         const bf16_t* ka = Kh + (size_t)(keyA < T ? keyA : 0) * 64 + 8 * gq;
         const bf16_t* kb = Kh + (size_t)(keyB < T ? keyB : 0) * 64 + 8 * gq;
-        kv[0] = *(const uint4*)ka; kv[1] = *(const uint4*)(ka + 32);
-        kv[2] = *(const uint4*)kb; kv[3] = *(const uint4*)(kb + 32);
+        kv[0] = ldg4(ka); kv[1] = ldg4(ka + 32);
+        kv[2] = ldg4(kb); kv[3] = ldg4(kb + 32);
         const int v0 = p0 + 8 * gq, vv = v0 < T ? v0 : 0;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) kv[4 + dt] = *(const uint4*)(Vh + (size_t)(dt * 16 + c) * D.maxpos + vv);
+        for (int dt = 0; dt < 4; ++dt) kv[4 + dt] = ldg4(Vh + (size_t)(dt * 16 + c) * D.maxpos + vv);
     };
     uint4 cur[8], nxt[8];
     if (wave < nblk) load_block(wave, cur);
@@ -539,119 +646,81 @@ __device__ void attn_unit(const StepParams& P, int layer, int u, uint4* smem) {
 }
 
 // ---------------------------------------------------------------------------
-// one unit of one phase
+// The units after the decoder layers.  Every kind of unit is a function of its own (not
+// inlined into the kernel): each gets its own register allocation, and a change to one does
+// not move the code of the others.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void run_unit(const StepParams& P, int ph, int u, uint4* smem, float* s_stat) {
+__device__ __forceinline__ void edge_unit(int u_) {
+    const int u = __builtin_amdgcn_readfirstlane(u_);
+    const StepParams& P = sP;
     const Dims& D = P.D;
     const DevState& s = P.s;
-    const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
-    if (ph == 0) { embed_unit(P, u); return; }
-    GemmD g;
-    g.R = R; g.stats = nullptr; g.colsum = nullptr; g.bias = nullptr; g.out = nullptr; g.outf = nullptr;
-    g.stats_out = nullptr; g.layer = 0; g.ph = ph;
-    // (column tile, row block) of unit u of a map with NT column tiles; false: empty unit
-    int nt = 0, rb = 0;
-    auto split = [&](int NT) { const int NTp = pad8(NT); nt = u % NTp; rb = u / NTp; return nt < NT; };
-    if (ph < H) {
-        const int l = (ph - 1) / 5, k = (ph - 1) % 5;
-        LayerW w;   // layer l = layer 0 advanced by l * lw_stride bytes
-        {
-            const size_t off = (size_t)l * P.lw_stride;
-            w.Wqkv = (const char*)P.lw0.Wqkv + off; w.Wo = (const char*)P.lw0.Wo + off;
-            w.W1 = (const char*)P.lw0.W1 + off; w.W2 = (const char*)P.lw0.W2 + off;
-            w.bo = (const float*)((const char*)P.lw0.bo + off); w.b2 = (const float*)((const char*)P.lw0.b2 + off);
-            w.t_qkv = (float*)((char*)P.lw0.t_qkv + off); w.cs_qkv = (float*)((char*)P.lw0.cs_qkv + off);
-            w.t_w1 = (float*)((char*)P.lw0.t_w1 + off); w.cs_w1 = (float*)((char*)P.lw0.cs_w1 + off);
-        }
-        g.layer = l;
-        // slots: xb / stats 2l = input of the layer, 2l+1 = after the out-projection, 2l+2 = after FFN2
-        bf16_t* xb0 = s.xb + (size_t)(2 * l) * s.act_stride;
-        float* st0 = s.stats + (size_t)(2 * l) * s.stats_stride;
-        bf16_t* q_l = (bf16_t*)s.q + (size_t)l * s.act_stride;
-        bf16_t* att_l = (bf16_t*)s.att + (size_t)l * s.act_stride;
-        bf16_t* hid_l = (bf16_t*)s.hid + (size_t)l * s.hid_stride;
-        switch (k) {
-        case 0:
-            g.X = xb0; g.K = D.d; g.N = 3 * D.d; g.Wp = (const uint4*)w.Wqkv; g.bias = w.t_qkv; g.colsum = w.cs_qkv;
-            g.stats = st0; g.epi = SE_QKV; g.out = q_l;
-            if (split(3 * D.d / 16)) gemm_unit<4>(P, g, nt, rb * 64, smem, s_stat);
-            return;
-        case 1: attn_unit(P, l, u, smem); return;
-        case 2:
-            g.X = att_l; g.K = D.d; g.N = D.d; g.Wp = (const uint4*)w.Wo; g.bias = w.bo;
-            g.epi = SE_RESID; g.out = xb0 + s.act_stride; g.stats_out = st0 + s.stats_stride;
-            if (split(D.d / 16)) gemm_unit<1>(P, g, nt, rb * 16, smem, s_stat);
-            return;
-        case 3:
-            g.X = xb0 + s.act_stride; g.K = D.d; g.N = D.F; g.Wp = (const uint4*)w.W1; g.bias = w.t_w1; g.colsum = w.cs_w1;
-            g.stats = st0 + s.stats_stride; g.epi = SE_GELU; g.out = hid_l;
-            if (split(D.F / 16)) gemm_unit<4>(P, g, nt, rb * 64, smem, s_stat);
-            return;
-        default:
-            g.X = hid_l; g.K = D.F; g.N = D.d; g.Wp = (const uint4*)w.W2; g.bias = w.b2;
-            g.epi = SE_RESID; g.out = xb0 + 2 * s.act_stride; g.stats_out = st0 + 2 * s.stats_stride;
-            if (split(D.d / 16)) gemm_unit<1>(P, g, nt, rb * 16, smem, s_stat);
-            return;
+    const int e = u * 4 + (int)(threadIdx.x >> 6);   // one edge per wave: edges 4u .. 4u+3 of the B * M rows
+    if (e < D.B * D.M) {
+        const int b = e / D.M, n = e - b * D.M;
+        const int ok = s.finished[b] ? 0 : dev_edge(D, s, b, n, P.tau);
+        if ((threadIdx.x & 63) == 0) stwi(s.edge_ok + e, ok);
+    }
+}
+__device__ __forceinline__ void select_unit(int u_) { const int u = __builtin_amdgcn_readfirstlane(u_); const StepParams& P = sP; dev_select(P.D, P.s, P.seq0 + u, P.ignore_eos); }
+__device__ __forceinline__ void final_unit(int u_) {
+    const int u = __builtin_amdgcn_readfirstlane(u_);
+    const StepParams& P = sP;
+    dev_finalize<bf16_t>(P.D, P.s, P.seq0 + u, P.prefill_mode, P.ignore_eos, 1);
+}
+__device__ __forceinline__ void commit_unit(int u_) {
+    const int u = __builtin_amdgcn_readfirstlane(u_);
+    const StepParams& P = sP;
+    if (threadIdx.x < 64) {
+        const Dims& D = P.D;
+        const int head = u % D.nH, b = (u / D.nH) % P.nseq, layer = u / (D.nH * P.nseq);
+        dev_commit_kv<bf16_t>(D, P.s, layer, P.seq0 + b, head, threadIdx.x);
+    }
+}
+__device__ __forceinline__ void topk_unit(int u_) { const int u = __builtin_amdgcn_readfirstlane(u_); const StepParams& P = sP; dev_topk(P.D, P.s, u / P.D.B, u % P.D.B); }
+
+// ---------------------------------------------------------------------------
+// one unit of one phase
+// ---------------------------------------------------------------------------
+// ---------------------------------------------------------------------------
+// one unit of one phase: dispatch to the unit's own function
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void run_unit(int ph, int u) {
+    const StepParams& P = sP;
+    const Dims& D = P.D;
+    const int H = 1 + 5 * D.Ly;
+    // each kind of unit is instantiated once (the kernel's code has to stay small enough for the
+    // instruction cache): first decide the kind, then one call site per kind
+    enum { K_EMBED, K_ATTN, K_GEMM4, K_GEMM1, K_EDGE, K_SELECT, K_FINAL, K_COMMIT, K_TOPK };
+    int kind;
+    if (ph == 0) kind = K_EMBED;
+    else if (ph < H) {
+        const int k = (ph - 1) % 5;
+        kind = k == 1 ? K_ATTN : (k == 0 || k == 3) ? K_GEMM4 : K_GEMM1;
+    } else {
+        switch (ph - H) {
+        case TP_EDGES: kind = K_EDGE; break;
+        case TP_SELECT: kind = K_SELECT; break;
+        case TP_FINAL: kind = K_FINAL; break;
+        case TP_COMMIT: kind = u < D.Ly * D.nH * P.nseq ? K_COMMIT : K_GEMM4; break;
+        case TP_TOPK: kind = K_TOPK; break;
+        default: kind = K_GEMM4; break;   // TP_HEAD, TP_DRAFT2
         }
     }
-    const int RGb = cdiv(D.B, 64);
-    switch (ph - H) {
-    case TP_HEAD:
-        g.X = s.xb + (size_t)(2 * D.Ly) * s.act_stride; g.K = D.d; g.N = D.V1; g.Wp = (const uint4*)s.W_out;
-        g.bias = s.t_out; g.colsum = s.cs_out;
-        g.stats = s.stats + (size_t)(2 * D.Ly) * s.stats_stride; g.epi = SE_LOGITS; g.outf = s.logits;
-        if (split(cdiv(D.V1, 16))) gemm_unit<4>(P, g, nt, rb * 64, smem, s_stat);
-        return;
-    case TP_EDGES: {   // one edge per wave: unit u takes edges 4u .. 4u+3 of the B * M rows
-        const int e = u * 4 + (int)(threadIdx.x >> 6);
-        if (e < R) {
-            const int b = e / D.M, n = e - b * D.M;
-            const int ok = s.finished[b] ? 0 : dev_edge(D, s, b, n, P.tau);
-            if ((threadIdx.x & 63) == 0) stwi(s.edge_ok + e, ok);
-        }
-        return;
-    }
-    case TP_SELECT: dev_select(D, s, P.seq0 + u, P.ignore_eos); return;
-    case TP_FINAL: dev_finalize<bf16_t>(D, s, P.seq0 + u, P.prefill_mode, P.ignore_eos, 1); return;
-    case TP_COMMIT: {
-        const int ncommit = D.Ly * D.nH * P.nseq;
-        if (u < ncommit) {
-            if (threadIdx.x < 64) {
-                const int head = u % D.nH, b = (u / D.nH) % P.nseq, layer = u / (D.nH * P.nseq);
-                dev_commit_kv<bf16_t>(D, s, layer, P.seq0 + b, head, threadIdx.x);
-            }
-            return;
-        }
-        u -= ncommit;
-        const int per = (D.d / 16) * RGb, i = u / per, v = u % per;
-        DraftW dw;
-        dw.W1 = (const char*)P.dw0.W1 + (size_t)i * P.dw_stride;
-        dw.b1 = (const float*)((const char*)P.dw0.b1 + (size_t)i * P.dw_stride);
-        g.R = D.B; g.X = (const bf16_t*)s.hbest; g.K = D.d; g.N = D.d;
-        g.Wp = (const uint4*)dw.W1; g.bias = dw.b1; g.epi = SE_SILU_RESID;
-        g.out = (bf16_t*)s.rdraft + (size_t)i * s.draft_stride;
-        gemm_unit<4>(P, g, v / RGb, (v % RGb) * 64, smem, s_stat);
-        return;
-    }
-    case TP_DRAFT2: {
-        const int per = cdiv(D.V1, 16) * RGb, i = u / per, v = u % per;
-        DraftW dw;
-        dw.W2 = (const char*)P.dw0.W2 + (size_t)i * P.dw_stride;
-        g.R = D.B; g.X = (const bf16_t*)s.rdraft + (size_t)i * s.draft_stride; g.K = D.d; g.N = D.V1;
-        g.Wp = (const uint4*)dw.W2; g.epi = SE_F32;
-        g.outf = s.zdraft + (size_t)i * D.Bmax * D.V1;
-        gemm_unit<4>(P, g, v / RGb, (v % RGb) * 64, smem, s_stat);
-        return;
-    }
-    default: dev_topk(D, s, u / D.B, u % D.B); return;
+    switch (kind) {
+    case K_EMBED: embed_unit(u); break;
+    case K_ATTN: attn_unit(ph, u); break;
+    case K_GEMM4: gemm_unit<4>(ph, u); break;
+    case K_GEMM1: gemm_unit<1>(ph, u); break;
+    case K_EDGE: edge_unit(u); break;
+    case K_SELECT: select_unit(u); break;
+    case K_FINAL: final_unit(u); break;
+    case K_COMMIT: commit_unit(u); break;
+    default: topk_unit(u); break;
     }
 }
 
 __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
-    extern __shared__ uint4 smem[];
-    // The kernel-argument segment may live in host memory: a re-load of an argument in the
-    // middle of the kernel then costs microseconds.  Copy the parameters into LDS once.
-    __shared__ StepParams sP;
     {
         const uint32_t* src = (const uint32_t*)&Parg;
         uint32_t* dst = (uint32_t*)&sP;
@@ -659,22 +728,21 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
     }
     __syncthreads();
     const StepParams& P = sP;
-    float* s_stat = (float*)((char*)smem + ST_TILE_BYTES);
     uint32_t epoch = P.epoch;
     for (int ph = P.ph_lo; ph < P.ph_hi; ++ph) {
-        tp(P, ph, 0);
+        tp(ph, 0);
         const int nu = phase_units(P, ph);
         for (int u = blockIdx.x; u < nu; u += gridDim.x) {
-            run_unit(P, ph, u, smem, s_stat);
+            run_unit(ph, u);
             __syncthreads();
         }
-        tp(P, ph, 1);
+        tp(ph, 1);
         if (P.persistent && ph + 1 < P.ph_hi) {
             ++epoch;
-            if (!grid_sync(P, epoch, ph)) return;
+            if (!grid_sync(epoch, ph)) return;
         }
     }
-    tp(P, 127, 0);
+    tp(127, 0);
 }
 
 void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err) {
