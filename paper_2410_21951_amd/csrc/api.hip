@@ -145,8 +145,8 @@ static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vecto
     mat(&st.P, P, d, 1);
     auto fold = [&](const float* g, const float* b, float** cs, float** t, size_t n) {
         // call right after mat(): remembers the LayerNorm to fold into that map
-        *cs = (float*)cv.take(n * 4);
-        *t = (float*)cv.take(n * 4);
+        *cs = (float*)cv.take((size_t)pad16((int)n) * 4);   // read as whole 16-column tiles
+        *t = (float*)cv.take((size_t)pad16((int)n) * 4);
         WeightSlot& w = sl.back();
         w.gamma = g; w.beta = b; w.colsum = *cs; w.tvec = *t;
     };

@@ -121,6 +121,10 @@ __device__ __forceinline__ void tp(int ph, int k) {
 __device__ bool grid_sync(uint32_t epoch, int ph) {
     const StepParams& P = sP;
     __shared__ int s_ok;
+    // The workgroup barrier does not wait for global stores (only for LDS traffic): every thread
+    // first waits until its own write-through stores have been acknowledged, so that nothing is
+    // in flight when thread 0 announces this workgroup's arrival.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();   // every wave's stores have completed (write-through: at the memory side)
     tp(ph, 4);
     if (threadIdx.x == 0) {
@@ -324,7 +328,9 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
     constexpr int ROWS = NRT * 16;
     const Dims& D = P.D;
     const DevState& s = P.s;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, gq = lane >> 4, c = lane & 15;
+    // the wave index is the same for all lanes of a wave: say so, and everything derived from it
+    // (k-step range, loop bounds) stays in scalar registers and branches are scalar
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, gq = lane >> 4, c = lane & 15;
     const int nks = g.K >> 5;
     const int ks_lo = (nks * wave) >> 2, ks_hi = (nks * (wave + 1)) >> 2;
     const uint4* Wp = g.Wp + (size_t)nt * nks * 64 + lane;
@@ -340,6 +346,19 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
 #pragma unroll
     for (int i = 0; i < NRT; ++i) acc[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
     tp(g.ph, 5);
+    // epilogue inputs, requested now so that they arrive with the operands (the vectors are
+    // padded to whole 16-column tiles)
+    uint4 cs4 = make_uint4(0, 0, 0, 0), b4 = cs4;
+    float xres = 0.f, bres = 0.f;
+    if (NRT == 4) {
+        const int n0 = nt * 16 + (tid & 3) * 4;
+        if (g.colsum) cs4 = ldg4(g.colsum + n0);
+        if (g.bias) b4 = ldg4(g.bias + n0);
+    } else {
+        const int r = row0 + (tid >> 4), n = nt * 16 + (tid & 15);
+        if (r < g.R) xres = ldg(s.x + (size_t)r * g.N + n);
+        bres = ldg(g.bias + n);
+    }
 
     // row statistics of the LayerNorm folded into this map: four threads per row, each
     // merges a quarter of the 16-column tiles (loads issued with the first operand chunk)
@@ -423,11 +442,10 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
                 float a = red[src];
 #pragma unroll
                 for (int w = 1; w < 4; ++w) a += red[w * 1024 + src];
-                if (n < g.N) {
-                    if (g.stats) a = rstd * (a - mu * ldg(g.colsum + n));
-                    if (g.bias) a += ldg(g.bias + n);
-                }
-                v[j] = a;
+                const float csj = __uint_as_float(j == 0 ? cs4.x : j == 1 ? cs4.y : j == 2 ? cs4.z : cs4.w);
+                const float bj = __uint_as_float(j == 0 ? b4.x : j == 1 ? b4.y : j == 2 ? b4.z : b4.w);
+                if (g.stats) a = rstd * (a - mu * csj);
+                v[j] = a + bj;   // columns beyond N (ragged last tile of a vocabulary map) are never stored
             }
             const bool full = n0 + 3 < g.N;   // only the vocabulary maps have a ragged last tile
             switch (g.epi) {
@@ -480,7 +498,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
         const bool ok = r < g.R;
         float xn = 0.f;
         if (ok) {
-            xn = ldg(s.x + (size_t)r * g.N + n) + v + ldg(g.bias + n);
+            xn = xres + v + bres;
             stwf(s.x + (size_t)r * g.N + n, xn);
         }
         {
@@ -511,7 +529,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     extern __shared__ uint4 smem[];
     const Dims& D = P.D;
     const DevState& s = P.s;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, gq = lane >> 4, c = lane & 15;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, gq = lane >> 4, c = lane & 15;
     // unit = (query tile) * pad8(B * nH) + (sequence, head): the query tiles of one head run on
     // one XCD (workgroup i is on XCD i mod 8) and share its L2 for that head's K / V rows
     const int BH = pad8(D.B * D.nH), bh = u % BH, qt = u / BH;
