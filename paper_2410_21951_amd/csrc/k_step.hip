@@ -572,10 +572,11 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) kv[4 + dt] = ldg4(Vh + (size_t)(dt * 16 + c) * D.maxpos + vv);
     };
-    uint4 cur[8], nxt[8];
+    uint4 cur[8], nxt[8], nx2[8];   // two blocks in flight behind the one being computed
     if (wave < nblk) load_block(wave, cur);
+    if (wave + 4 < nblk) load_block(wave + 4, nxt);
     for (int blk = wave; blk < nblk; blk += 4) {
-        if (blk + 4 < nblk) load_block(blk + 4, nxt);   // in flight while this block is computed
+        if (blk + 8 < nblk) load_block(blk + 8, nx2);
         const int p0 = blk << 5;
         const int v0 = p0 + 8 * gq;
         const uint4 a0 = cur[0], a1 = cur[1], b0 = cur[2], b1 = cur[3];
@@ -625,7 +626,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
             O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vt[dt]), pfrag, O[dt], 0, 0, 0);
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
+        for (int i = 0; i < 8; ++i) { cur[i] = nxt[i]; nxt[i] = nx2[i]; }
     }
     // merge the four waves: sm_m / sm_l [wave][query], sm_o [wave][dim][query]
     l_run += __shfl_xor(l_run, 16, 64);
