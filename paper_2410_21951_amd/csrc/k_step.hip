@@ -32,6 +32,7 @@
 // are re-read after having been cached (L, the residual row of the accepted
 // node) are loaded at agent scope.
 #include <algorithm>
+#include <cstdlib>
 
 #include "accept_dev.h"
 
@@ -774,7 +775,17 @@ void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err
     if (p.persistent) {
         StepParams q = p;
         void* args[] = {&q};
-        *err = hipLaunchCooperativeKernel((const void*)k_step, dim3(n_cus), dim3(256), args, ST_LDS_BYTES, st);
+        // The grid barrier needs every workgroup resident.  A cooperative launch guarantees it.
+        // VADUSA_PLAIN_LAUNCH=1 uses an ordinary launch instead (less launch overhead): with one
+        // workgroup per compute unit the same holds as long as nothing else occupies the GPU,
+        // and if it does not hold the bounded barrier reports a time-out instead of hanging.
+        static const bool plain = getenv("VADUSA_PLAIN_LAUNCH") != nullptr;
+        if (plain) {
+            hipLaunchKernelGGL(k_step, dim3(n_cus), dim3(256), ST_LDS_BYTES, st, q);
+            *err = hipGetLastError();
+        } else {
+            *err = hipLaunchCooperativeKernel((const void*)k_step, dim3(n_cus), dim3(256), args, ST_LDS_BYTES, st);
+        }
         return;
     }
     for (int ph = p.ph_lo; ph < p.ph_hi; ++ph) {
