@@ -203,3 +203,74 @@ class Lockstep:
         for b, st in enumerate(self.sts):
             O.step(self.model, st, tree, tau, draft_override=None if o_lists is None else o_lists[b],
                    ignore_eos=self.ignore_eos)
+
+
+def sampled_check(cfg, weights, text, prompt, tree, tau, sample, kv_layers=(0,)):
+    """Full-batch run on the GPU, oracle on a sample of the sequences only (for batches whose
+    oracle run would take minutes): prefill, one verification, compaction.  Returns
+    (sequences compared, sequences skipped because a root or list decision sat inside the
+    margin, largest logit error).  Decisions are held to the same margin rule as Lockstep."""
+    B = len(text)
+    model = O.Model(cfg, weights)
+    tol = TOL[cfg.dtype]
+    dev = Vadusa(cfg, max_batch=B, max_tree_nodes=tree.n_nodes, ignore_eos=True)
+    dev.load_weights(weights)
+    dev.prefill(text, prompt)
+    roots = dev.debug(DBG.ROOT)
+    lists = dev.debug(DBG.DRAFT_TOPK)
+    need = tree.topk_needed(cfg.n_draft_heads)
+    sts, skipped = {}, 0
+    override = [[lists[b, i].tolist() for i in range(cfg.n_draft_heads)] for b in range(B)]
+    for b in sample:
+        st = O.prefill(model, text[b], prompt[b])
+        if roots[b] != st.root:
+            assert top_gap(st.root_logits) <= MARGIN, f"root mismatch seq {b}"
+            skipped += 1
+            continue
+        ol = O.draft_lists(model, st, tree)
+        for i, k in enumerate(need):
+            if k and lists[b, i, :k].tolist() != ol[i].tolist():
+                assert top_gap(st.draft_logits[i], k) <= MARGIN, f"draft list mismatch seq {b} head {i}"
+        override[b] = [np.asarray(a, np.int64).tolist() + [0] * (16 - len(a)) for a in ol]
+        sts[b] = (st, ol)
+    dev.verify(TreeArrays(tree.parent, tree.rank), tau, override=override)
+    tok = dev.debug(DBG.TREE_TOK)
+    logits = dev.debug(DBG.LOGITS)
+    edge = dev.debug(DBG.EDGE_OK)
+    path = dev.debug(DBG.PATH)
+    max_err, forced = 0.0, {}
+    for b, (st, ol) in sts.items():
+        r = O.step(model, st, tree, tau, draft_override=ol, ignore_eos=True)
+        assert tok[b].tolist() == r["tok"].tolist(), f"tree tokens differ seq {b}"
+        for n in range(tree.n_nodes):
+            e = rel_l2(logits[b, n], r["logits"][n])
+            max_err = max(max_err, e)
+            assert e < tol, f"logits seq {b} node {n}: rel-L2 {e}"
+        flipped = False
+        for n in range(1, tree.n_nodes):
+            z = r["logits"][tree.parent[n]]
+            t = int(r["tok"][n])
+            want = int((z > z[t]).sum() + (z[:t] == z[t]).sum()) < tau
+            if bool(edge[b, n]) != want:
+                assert edge_margin(z, t, tau) <= MARGIN, f"edge decision differs seq {b} node {n}"
+                flipped = True
+        got = path[b, 1:1 + path[b, 0]].tolist()
+        if not flipped:
+            assert got == r["path"], f"path differs seq {b}: {got} vs {r['path']}"
+        elif got != r["path"]:
+            forced[b] = r["path"]
+    for b in range(B):
+        if b in forced:
+            dev.kv_compact(b, forced[b])
+        else:
+            dev.kv_compact(b)
+    L = dev.debug(DBG.KV_LEN)
+    for b, (st, _) in sts.items():
+        assert L[b] == st.L, f"L differs seq {b}"
+        assert dev.read_output(b).tolist() == st.emitted, f"output differs seq {b}"
+        for l in kv_layers:
+            for which, ref in ((0, st.K), (1, st.V)):
+                e = rel_l2(dev.read_kv(l, b, which, 0, st.L), ref[l, :st.L])
+                assert e < tol, f"KV layer {l} seq {b} which {which}: rel-L2 {e}"
+    dev.close()
+    return len(sts), skipped, max_err

@@ -192,3 +192,56 @@ def test_throughput_shape_batch():
     s = ls.stats
     _say(f"throughput shape: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e}")
     assert s.compared >= 1
+
+
+def test_longform_b1_full_size():
+    """Configuration 4 at full size (12 layers, 5 draft heads, 128-node tree), at the start of
+    generation (L = 814) in lockstep and deep into it (L = 2914, cache past 3000 rows)
+    on one verification."""
+    from parity import sampled_check
+    wl = PRESETS["longform_b1"]
+    _say("generating longform_b1 weights")
+    W = make_weights(wl.model, wl.seed)
+    text, prompt = make_tokens(wl)
+    tree = make_tree(wl.tree_nodes, wl.topk_caps)
+    ls = _lock(wl.model, W, text, prompt, wl.tree_nodes)
+    for tau in (1, 4):
+        ls.step(tree, tau)
+    ls.check_kv(layers=[0, 11])
+    s = ls.stats
+    _say(f"longform_b1 L0={len(text[0]) + len(prompt[0])}: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e}")
+    assert s.compared >= 1
+    ls.dev.close()
+    rng = np.random.default_rng(27)
+    deep = [np.concatenate([prompt[0], rng.integers(0, wl.model.speech_vocab, 2100).astype(np.int32)])]
+    n, skipped, err = sampled_check(wl.model, W, text, deep, tree, 4, [0], kv_layers=(0, 11))
+    _say(f"longform_b1 L0={len(text[0]) + len(deep[0])}: compared {n} skipped {skipped} logit err {err:.2e}")
+    assert n + skipped == 1
+
+
+def test_hubert_b16_full_size():
+    """Configuration 3 at full size: 16 ragged sequences, vocabulary 2049, tau = 3; the oracle
+    follows four of them."""
+    from parity import sampled_check
+    wl = PRESETS["hubert_b16"]
+    _say("generating hubert_b16 weights")
+    W = make_weights(wl.model, wl.seed)
+    text, prompt = make_tokens(wl)
+    tree = make_tree(wl.tree_nodes, wl.topk_caps)
+    n, skipped, err = sampled_check(wl.model, W, text, prompt, tree, 3, [0, 5, 10, 15], kv_layers=(0, 11))
+    _say(f"hubert_b16: compared {n} skipped {skipped} logit err {err:.2e}")
+    assert n >= 3
+
+
+def test_throughput_b64_full_size():
+    """Configuration 5 at full size: 64 sequences, 32-node trees, cache for 1200 positions per
+    sequence; the oracle follows four of them."""
+    from parity import sampled_check
+    wl = PRESETS["throughput_b64"]
+    _say("generating throughput_b64 weights")
+    W = make_weights(wl.model, wl.seed)
+    text, prompt = make_tokens(wl)
+    tree = make_tree(wl.tree_nodes, wl.topk_caps)
+    n, skipped, err = sampled_check(wl.model, W, text, prompt, tree, 8, [0, 21, 42, 63], kv_layers=(0, 11))
+    _say(f"throughput_b64: compared {n} skipped {skipped} logit err {err:.2e}")
+    assert n >= 3
