@@ -35,6 +35,14 @@ __device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f2bf(v); }
 #endif
 template <class T>
 __device__ __forceinline__ T ldg(const T* p) { return *(const VADUSA_GLOBAL T*)p; }   // scalar T only
+// A pointer that is the same in every lane (read from the parameter block, derived from the unit
+// number): moved to scalar registers, so that loads can use "scalar base + lane offset" addresses.
+template <class T>
+__device__ __forceinline__ T* uniform_ptr(T* p) {
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (T*)(((uint64_t)hi << 32) | lo);
+}
 // 8- and 16-byte loads (HIP's uint2 / uint4 / float2 are classes: their copy would go back to a generic reference)
 typedef uint32_t vadusa_u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t vadusa_u32x2 __attribute__((ext_vector_type(2)));

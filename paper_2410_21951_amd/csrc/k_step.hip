@@ -334,15 +334,18 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, gq = lane >> 4, c = lane & 15;
     const int nks = g.K >> 5;
     const int ks_lo = (nks * wave) >> 2, ks_hi = (nks * (wave + 1)) >> 2;
-    const uint4* Wp = g.Wp + (size_t)nt * nks * 64 + lane;
+    // Operand addresses are kept as a workgroup-uniform base (scalar registers) plus a 32-bit
+    // per-lane index, so that a load needs no vector address arithmetic.
+    const uint4* Wp = uniform_ptr(g.Wp + (size_t)nt * nks * 64);
     // A operand: tile (row tile, k-step) of the tiled activation layout = 64 lanes x 16 bytes
     const uint4* Ap[NRT];
     bool rowok[NRT];
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
         rowok[rt] = row0 + rt * 16 < g.R;   // whole tile beyond the last row: skipped
-        Ap[rt] = (const uint4*)g.X + (size_t)(rowok[rt] ? (row0 >> 4) + rt : 0) * nks * 64 + lane;
+        Ap[rt] = uniform_ptr((const uint4*)g.X + (size_t)(rowok[rt] ? (row0 >> 4) + rt : 0) * nks * 64);
     }
+    const uint32_t ulane = (uint32_t)lane;
     f32x4_t acc[NRT];
 #pragma unroll
     for (int i = 0; i < NRT; ++i) acc[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
@@ -369,18 +372,28 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
 
     for (int kb = ks_lo; kb < ks_hi; kb += CH) {
         uint4 bw[CH], aw[NRT][CH];
+        if (kb + CH <= ks_hi) {   // a whole chunk (the usual case): straight-line loads
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int ks = kb + i;
-            bw[i] = ks < ks_hi ? ldg4(Wp + (size_t)ks * 64) : make_uint4(0, 0, 0, 0);
-        }
+            for (int i = 0; i < CH; ++i) bw[i] = ldg4((const char*)Wp + ((uint32_t)(kb + i) * 1024u + ulane * 16u));
 #pragma unroll
-        for (int rt = 0; rt < NRT; ++rt)
+            for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                for (int i = 0; i < CH; ++i)
+                    aw[rt][i] = rowok[rt] ? ldg4((const char*)Ap[rt] + ((uint32_t)(kb + i) * 1024u + ulane * 16u)) : make_uint4(0, 0, 0, 0);
+        } else {
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
                 const int ks = kb + i;
-                aw[rt][i] = (ks < ks_hi && rowok[rt]) ? ldg4(Ap[rt] + (size_t)ks * 64) : make_uint4(0, 0, 0, 0);
+                bw[i] = ks < ks_hi ? ldg4((const char*)Wp + ((uint32_t)ks * 1024u + ulane * 16u)) : make_uint4(0, 0, 0, 0);
             }
+#pragma unroll
+            for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                for (int i = 0; i < CH; ++i) {
+                    const int ks = kb + i;
+                    aw[rt][i] = (ks < ks_hi && rowok[rt]) ? ldg4((const char*)Ap[rt] + ((uint32_t)ks * 1024u + ulane * 16u)) : make_uint4(0, 0, 0, 0);
+                }
+        }
         if (kb == ks_lo) tp(g.ph, 6);
         if (kb == ks_lo && do_stats) {
             const int row = tid >> 2, part = tid & 3, r = row0 + row;
