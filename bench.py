@@ -151,6 +151,27 @@ def main():
                      "kernel": "k_step (one launch = one speculative step)",
                      "avg_launch_us": ms_step * 1e3, "algorithmic_bytes_per_launch": nbytes},
     }
+    # Plain auto-regressive decoding through the same kernels: a "tree" of the root alone, one
+    # token per step.  speedup = accepted tokens per step x t_AR / t_tree (Sec. 4.1's metric); the
+    # accepted length is a property of trained draft heads, so the line quotes what the paper's
+    # own accepted lengths (Table 1: 3.00 at tau=1, 3.87 at tau=3, four heads) would give here.
+    from synth import chain_tree
+    t1 = chain_tree(1)
+    t1arr = TreeArrays(t1.parent, t1.rank)
+    n_ar = min(a.steps, 300)
+    dev.prefill(text, prompt)
+    for _ in range(5):
+        dev.step(t1arr, 1, sync=False)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(n_ar):
+        dev.step(t1arr, 1, sync=False)
+    ev1.record()
+    torch.cuda.synchronize()
+    ar_us = ev0.elapsed_time(ev1) / n_ar * 1e3
+    out["ar_step"] = {"us_per_step": ar_us, "steps": n_ar, "tree_step_over_ar_step": ms_step * 1e3 / ar_us,
+                      "speedup_at_paper_accepted_len": {"tau1_acc3.00": 3.00 * ar_us / (ms_step * 1e3),
+                                                        "tau3_acc3.87": 3.87 * ar_us / (ms_step * 1e3)}}
     dev.close()
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, W, text, prompt, tree)

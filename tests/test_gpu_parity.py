@@ -245,3 +245,26 @@ def test_throughput_b64_full_size():
     n, skipped, err = sampled_check(wl.model, W, text, prompt, tree, 8, [0, 21, 42, 63], kv_layers=(0, 11))
     _say(f"throughput_b64: compared {n} skipped {skipped} logit err {err:.2e}")
     assert n >= 3
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_single_node_tree_is_plain_ar(dtype):
+    """A tree of the root alone: every step commits exactly one token, and the stream equals
+    the oracle's plain greedy auto-regressive decoding (the baseline of the paper's speedup)."""
+    cfg = small_cfg(dtype)
+    W = make_weights(cfg, 31, std=STD[dtype])
+    rng = np.random.default_rng(32)
+    text, prompt = rand_tokens(cfg, rng, 2, (4, 9), (17, 30))
+    tree = chain_tree(1)
+    ls = _lock(cfg, W, text, prompt, 8)
+    for _ in range(12):
+        r = ls.step(tree, 1)
+        if r is not None:
+            assert all(len(x["accepted"]) == 1 for x in r)
+    s = ls.stats
+    _say(f"single-node tree {dtype}: compared {s.compared}/{s.steps} ties {s.tie_root} logit err {s.max_logit_err:.2e}")
+    if s.tie_root == 0:
+        model = O.Model(cfg, W)
+        for b in range(2):
+            assert ls.sts[b].emitted == O.greedy_ar(model, text[b], prompt[b], len(ls.sts[b].emitted), ignore_eos=True)
+    assert s.compared >= 8
