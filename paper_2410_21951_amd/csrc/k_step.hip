@@ -603,33 +603,46 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
         sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, b0), Q0, sb, 0, 0, 0);
         sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, b1), Q1, sb, 0, 0, 0);
         // this lane: query c, keys v0 + 0..3 (sa) and v0 + 4..7 (sb)
-        float sc[8];
-        bool ok[8];
-        float mx = -1e30f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int key = v0 + j;
-            bool okj = key < L;
-            if (!okj && key < T) {
-                const int mm = key - L;
-                okj = (mword[mm >> 5] >> (mm & 31)) & 1u;
-            }
-            ok[j] = okj;
-            sc[j] = okj ? (j < 4 ? sa[j] : sb[j - 4]) * 0.125f : -1e30f;
-            mx = fmaxf(mx, sc[j]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float corr = __expf(m_run - m_new);
-        float psum = 0.f;
+        // online softmax of the block: scores -> probabilities (bf16 pairs in pk), running max / sum.
+        // Instantiated twice: blocks inside the committed cache need no mask tests at all.
         uint32_t pk[4];
+        float m_new, corr, psum = 0.f;
+        auto softmax_block = [&](const unsigned okm) {
+            float sc[8];
+            float mx = -1e30f;
 #pragma unroll
-        for (int j = 0; j < 8; j += 2) {
-            const float p0f = ok[j] ? __expf(sc[j] - m_new) : 0.f;
-            const float p1f = ok[j + 1] ? __expf(sc[j + 1] - m_new) : 0.f;
-            psum += p0f + p1f;
-            pk[j >> 1] = (uint32_t)f2bf(p0f) | ((uint32_t)f2bf(p1f) << 16);
+            for (int j = 0; j < 8; ++j) {
+                const float sv = (j < 4 ? sa[j] : sb[j - 4]) * 0.125f;
+                sc[j] = (okm >> j) & 1u ? sv : -1e30f;
+                mx = fmaxf(mx, sc[j]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            m_new = fmaxf(m_run, mx);
+            corr = __expf(m_run - m_new);
+#pragma unroll
+            for (int j = 0; j < 8; j += 2) {
+                const float p0f = (okm >> j) & 1u ? __expf(sc[j] - m_new) : 0.f;
+                const float p1f = (okm >> (j + 1)) & 1u ? __expf(sc[j + 1] - m_new) : 0.f;
+                psum += p0f + p1f;
+                pk[j >> 1] = (uint32_t)f2bf(p0f) | ((uint32_t)f2bf(p1f) << 16);
+            }
+        };
+        if (p0 + 32 > L) {   // the block reaches into the tree rows (same for the whole wave)
+            unsigned okm = 0;   // which of the lane's 8 keys the query may see
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int key = v0 + j;
+                bool okj = key < L;
+                if (!okj && key < T) {
+                    const int mm = key - L;
+                    okj = (mword[mm >> 5] >> (mm & 31)) & 1u;
+                }
+                okm |= okj ? (1u << j) : 0u;
+            }
+            softmax_block(okm);
+        } else {
+            softmax_block(0xffu);
         }
         l_run = l_run * corr + psum;
         m_run = m_new;
@@ -786,14 +799,26 @@ void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err
     }
     *err = hipSuccess;
     if (p.persistent) {
+        // every workgroup of the grid must fit on the GPU at once
+        static int resident = -1;
+        if (resident < 0) {
+            int nb = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_step, 256, ST_LDS_BYTES) != hipSuccess) nb = 0;
+            resident = nb;
+        }
+        if (resident < 1) { *err = hipErrorCooperativeLaunchTooLarge; return; }
+    }
+    if (p.persistent) {
         StepParams q = p;
         void* args[] = {&q};
-        // The grid barrier needs every workgroup resident.  A cooperative launch guarantees it.
-        // VADUSA_PLAIN_LAUNCH=1 uses an ordinary launch instead (less launch overhead): with one
-        // workgroup per compute unit the same holds as long as nothing else occupies the GPU,
-        // and if it does not hold the bounded barrier reports a time-out instead of hanging.
-        static const bool plain = getenv("VADUSA_PLAIN_LAUNCH") != nullptr;
-        if (plain) {
+        // The grid barrier needs every workgroup resident.  The grid is one workgroup per compute
+        // unit and the kernel's register use allows no second one, so an ordinary launch on an
+        // otherwise idle GPU places them all; it costs ~18 us less per step than a cooperative
+        // launch.  Should the GPU be shared and a workgroup not get its compute unit, the bounded
+        // barrier reports a time-out (VADUSA_EHIP) instead of hanging.  VADUSA_COOPERATIVE_LAUNCH=1
+        // selects the cooperative launch, which makes the runtime check residency.
+        static const bool coop = getenv("VADUSA_COOPERATIVE_LAUNCH") != nullptr;
+        if (!coop) {
             hipLaunchKernelGGL(k_step, dim3(n_cus), dim3(256), ST_LDS_BYTES, st, q);
             *err = hipGetLastError();
         } else {
