@@ -72,23 +72,36 @@ __device__ inline void dev_choose(const Dims& D, const DevState& s, int b, int i
     const int32_t* parent = s.t_parent[0];
     const int32_t* depth = s.t_depth[0];
     const int32_t* tok = s.tok + (size_t)b * D.M;
+    // the tree tables go to LDS once: the walks below would otherwise pay a memory latency per hop
+    __shared__ int s_par[VADUSA_MAX_TREE_NODES];
+    __shared__ int s_key[VADUSA_MAX_TREE_NODES];
+    for (int n = threadIdx.x; n < D.M; n += 256) s_par[n] = ldg(parent + n);
+    __syncthreads();
     for (int n = threadIdx.x; n < D.M; n += 256) {
         int ok = 1, m = n;
-        while (m > 0) { ok &= s_edge[m]; m = parent[m]; }
+        while (m > 0) { ok &= s_edge[m]; m = s_par[m]; }
         s_ok[n] = ok;
+        // deepest accepted node, smallest index among equals: largest depth * 256 + (255 - n)
+        s_key[n] = ok ? ldg(depth + n) * 256 + (255 - n) : -1;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        int best = 0;
-        for (int n = 1; n < D.M; ++n)
-            if (s_ok[n] && depth[n] > depth[best]) best = n;
-        int cnt = depth[best] + 1;
+        int key = -1;
+        for (int n0 = 0; n0 < D.M; n0 += 8) {
+            int kq[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) kq[q] = s_key[(n0 + q) & (VADUSA_MAX_TREE_NODES - 1)];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) if (n0 + q < D.M && kq[q] > key) key = kq[q];
+        }
+        const int best = key < 0 ? 0 : 255 - (key & 255);
+        int cnt = (key < 0 ? 0 : key >> 8) + 1;
         int m = best;
         int nodes[VADUSA_MAX_DRAFT_HEADS + 1];
-        for (int j = cnt - 1; j >= 0; --j) { nodes[j] = m; m = parent[m]; }
+        for (int j = cnt - 1; j >= 0; --j) { nodes[j] = m; m = s_par[m]; }
         if (!ignore_eos)
             for (int j = 0; j < cnt; ++j)
-                if (tok[nodes[j]] == D.V1 - 1) { cnt = j + 1; break; }
+                if (ldg(tok + nodes[j]) == D.V1 - 1) { cnt = j + 1; break; }
         for (int j = 0; j < cnt; ++j) stwi(path + 1 + j, nodes[j]);
         stwi(path, cnt);
     }
@@ -206,7 +219,44 @@ __device__ inline void dev_finalize(const Dims& D, const DevState& s, int b, int
     const int root = block_argbest(s.logits + (size_t)r * D.V1, D.V1, INFINITY, -1, nullptr);
     T* hb = (T*)s.hbest + (size_t)b * D.d;
     if (from_x) {
+        // final LayerNorm of the accepted node's residual row.  The row was written by other
+        // workgroups of this launch: coherent loads, once, into registers (up to 16 values per
+        // thread, d <= 4096; larger rows take the three-pass route below)
         const float* xr = s.x + (size_t)r * D.d;
+        if (D.d <= 4096) {
+            float xv[16];
+            float sum = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = threadIdx.x * 2 + 512 * j;
+                xv[2 * j] = i < D.d ? ldcf(xr + i) : 0.f;
+                xv[2 * j + 1] = i < D.d ? ldcf(xr + i + 1) : 0.f;
+                sum += xv[2 * j] + xv[2 * j + 1];
+            }
+            sum = wave_sum(sum);
+            if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = sum;
+            __syncthreads();
+            const float mu = (s_red[0] + s_red[1] + s_red[2] + s_red[3]) / D.d;
+            float sq = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = threadIdx.x * 2 + 512 * j;
+                if (i < D.d) { const float t0 = xv[2 * j] - mu, t1 = xv[2 * j + 1] - mu; sq += t0 * t0 + t1 * t1; }
+            }
+            sq = wave_sum(sq);
+            if ((threadIdx.x & 63) == 0) s_red[4 + (threadIdx.x >> 6)] = sq;
+            __syncthreads();
+            const float rstd = rsqrtf((s_red[4] + s_red[5] + s_red[6] + s_red[7]) / D.d + LN_EPS);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = threadIdx.x * 2 + 512 * j;
+                if (i < D.d) {
+                    const float a = (xv[2 * j] - mu) * rstd * ldg(s.lnf_g + i) + ldg(s.lnf_b + i);
+                    const float c2 = (xv[2 * j + 1] - mu) * rstd * ldg(s.lnf_g + i + 1) + ldg(s.lnf_b + i + 1);
+                    stw32((bf16_t*)s.hbest + toff(b, i, D.d >> 5), pack_bf16(a, c2));   // tiled for the draft maps
+                }
+            }
+        } else {
         float sum = 0.f;
         for (int i = threadIdx.x; i < D.d; i += 256) sum += ldcf(xr + i);
         sum = wave_sum(sum);
@@ -223,6 +273,7 @@ __device__ inline void dev_finalize(const Dims& D, const DevState& s, int b, int
             const float a = (ldcf(xr + i) - mu) * rstd * s.lnf_g[i] + s.lnf_b[i];
             const float c2 = (ldcf(xr + i + 1) - mu) * rstd * s.lnf_g[i + 1] + s.lnf_b[i + 1];
             stw32((bf16_t*)s.hbest + toff(b, i, D.d >> 5), pack_bf16(a, c2));   // tiled for the draft maps
+        }
         }
     } else {
         const T* h = (const T*)s.hn + (size_t)r * D.d;
@@ -300,7 +351,7 @@ __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) 
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int v = threadIdx.x + 256 * j;
-            zr[j] = v < D.V1 ? z[v] : -INFINITY;
+            zr[j] = v < D.V1 ? ldg(z + v) : -INFINITY;
         }
         float lv = -INFINITY;
         int li = 0x7fffffff;
@@ -318,10 +369,15 @@ __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) 
         if ((threadIdx.x & 15) == 0) { g_v[threadIdx.x >> 4] = lv; g_i[threadIdx.x >> 4] = li; }
         if (threadIdx.x == 0) c_n = 0;
         __syncthreads();
-        float tv = g_v[0];
-        int ti = g_i[0];
+        float gv[16];
+        int gi[16];
+#pragma unroll
+        for (int g = 0; g < 16; ++g) { gv[g] = g_v[g]; gi[g] = g_i[g]; }   // all LDS reads in flight at once
+        float tv = gv[0];
+        int ti = gi[0];
+#pragma unroll
         for (int g = 1; g < 16; ++g)
-            if (before(tv, ti, g_v[g], g_i[g])) { tv = g_v[g]; ti = g_i[g]; }   // T = the last of the group maxima
+            if (before(tv, ti, gv[g], gi[g])) { tv = gv[g]; ti = gi[g]; }   // T = the last of the group maxima
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int v = threadIdx.x + 256 * j;
@@ -337,7 +393,14 @@ __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) 
                 const float mv = c_v[threadIdx.x];
                 const int mi = c_i[threadIdx.x];
                 int r = 0;
-                for (int t = 0; t < n; ++t) r += before(c_v[t], c_i[t], mv, mi) ? 1 : 0;
+                for (int t0 = 0; t0 < n; t0 += 8) {   // eight candidates per round: LDS reads overlap
+                    float cv[8];
+                    int ci[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) { cv[q] = c_v[(t0 + q) & 255]; ci[q] = c_i[(t0 + q) & 255]; }
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) r += (t0 + q < n && before(cv[q], ci[q], mv, mi)) ? 1 : 0;
+                }
                 if (r < kmax) stwi(out + r, mi);
             }
         } else {
