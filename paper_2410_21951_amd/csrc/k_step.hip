@@ -230,7 +230,13 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
     // (column tile, row block) of unit u of a map with NT column tiles; false: empty unit
     int rb = 0;
     nt = 0; row0 = 0;
-    auto split = [&](int NT) { const int NTp = pad8(NT); nt = u % NTp; rb = u / NTp; return nt < NT; };
+    auto split = [&](int NT) {
+        const int NTp = pad8(NT);
+        if (u < NTp) { nt = u; rb = 0; }                                            // a single row block
+        else if ((NTp & (NTp - 1)) == 0) { nt = u & (NTp - 1); rb = u >> __builtin_ctz(NTp); }   // power of two
+        else { nt = u % NTp; rb = u / NTp; }
+        return nt < NT;
+    };
     if (ph < H) {
         const int l = (ph - 1) / 5, k = (ph - 1) % 5;
         LayerW w;   // layer l = layer 0 advanced by l * lw_stride bytes
@@ -775,9 +781,14 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
     __syncthreads();
     const StepParams& P = sP;
     uint32_t epoch = P.epoch;
+    // unit counts of the five layer phases and of the phases after the layers, once per launch
+    __shared__ int s_nu[5 + TP_COUNT];
+    const int H = 1 + 5 * P.D.Ly;
+    if (threadIdx.x < 5 + TP_COUNT) s_nu[threadIdx.x] = phase_units(P, threadIdx.x < 5 ? 1 + (int)threadIdx.x : H + (int)threadIdx.x - 5);
+    __syncthreads();
     for (int ph = P.ph_lo; ph < P.ph_hi; ++ph) {
         tp(ph, 0);
-        const int nu = phase_units(P, ph);
+        const int nu = ph == 0 ? P.D.B * P.D.M : ph < H ? s_nu[(ph - 1) % 5] : s_nu[5 + ph - H];
         for (int u = blockIdx.x; u < nu; u += gridDim.x) {
             run_unit(ph, u);
             __syncthreads();
