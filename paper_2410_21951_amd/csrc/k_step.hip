@@ -552,21 +552,17 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, gq = lane >> 4, c = lane & 15;
     // unit = (query tile) * pad8(B * nH) + (sequence, head): the query tiles of one head run on
     // one XCD (workgroup i is on XCD i mod 8) and share its L2 for that head's K / V rows
-    const int BH = pad8(D.B * D.nH), bh = u % BH, qt = u / BH;
+    const int BH = pad8(D.B * D.nH);
+    int bh, qt, h, b;
+    if ((BH & (BH - 1)) == 0) { bh = u & (BH - 1); qt = u >> __builtin_ctz(BH); }   // no division in the usual case
+    else { bh = u % BH; qt = u / BH; }
     if (bh >= D.B * D.nH) return;
-    const int h = bh % D.nH, b = bh / D.nH;
+    if ((D.nH & (D.nH - 1)) == 0) { h = bh & (D.nH - 1); b = bh >> __builtin_ctz(D.nH); }
+    else { h = bh % D.nH; b = bh / D.nH; }
+    // everything the unit needs before its first key block is requested at once: row count,
+    // committed length, the queries, the mask words (one memory latency instead of three)
     const int n_rows = ldg(s.n_rows + b);
-    bf16_t* att = (bf16_t*)s.att + (size_t)layer * s.act_stride;
-    if (n_rows == 0) {
-        const int q = tid >> 4, d0 = (tid & 15) * 4, node = qt * 16 + q;
-        if (node < D.M) stw64(att + toff(b * D.M + node, h * 64 + d0, D.d >> 5), 0ull);
-        return;
-    }
     const int L = ldg(s.L + b);
-    const int T = min(L + D.M, D.maxpos);
-    const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + h) * D.maxpos) * 64;
-    const bf16_t* Kh = (const bf16_t*)s.Kc + hb;
-    const bf16_t* Vh = (const bf16_t*)s.Vc + hb;
     const int node = min(qt * 16 + c, D.M - 1);
     const bf16_t* ql = (const bf16_t*)s.q + (size_t)layer * s.act_stride;
     const int qrow = b * D.M + node;
@@ -574,6 +570,16 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     const bf16x8_t Q1 = __builtin_bit_cast(bf16x8_t, ldg4(ql + toff(qrow, h * 64 + 32 + 8 * gq, D.d >> 5)));
     const uint4 mw = ldg4(s.t_mask[P.table] + (size_t)node * MASK_WORDS);
     const uint32_t mword[4] = {mw.x, mw.y, mw.z, mw.w};
+    bf16_t* att = (bf16_t*)s.att + (size_t)layer * s.act_stride;
+    if (n_rows == 0) {
+        const int q = tid >> 4, d0 = (tid & 15) * 4, nd = qt * 16 + q;
+        if (nd < D.M) stw64(att + toff(b * D.M + nd, h * 64 + d0, D.d >> 5), 0ull);
+        return;
+    }
+    const int T = min(L + D.M, D.maxpos);
+    const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + h) * D.maxpos) * 64;
+    const bf16_t* Kh = (const bf16_t*)s.Kc + hb;
+    const bf16_t* Vh = (const bf16_t*)s.Vc + hb;
 
     float m_run = -1e30f, l_run = 0.f;
     f32x4_t O[4];
