@@ -133,6 +133,24 @@ def main():
         L_sum += k * (np.mean(L0) + np.mean(n_out) / 2.0)
         done += k
     ms_step = total_ms / a.steps
+    # the same step binned by committed length (untimed for the headline figure): five equal
+    # slices of one generation, each timed with its own pair of events
+    by_L = []
+    if a.steps >= 50:
+        dev.prefill(text, prompt)
+        nb = 5
+        per = min(seg, a.steps) // nb
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(nb + 1)]
+        torch.cuda.synchronize()
+        evs[0].record()
+        for i in range(nb):
+            for _ in range(per):
+                dev.step(tarr, a.tau, sync=False)
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        for i in range(nb):
+            by_L.append({"L_from": int(np.mean(L0)) + i * per, "L_to": int(np.mean(L0)) + (i + 1) * per,
+                         "us_per_step": evs[i].elapsed_time(evs[i + 1]) / per * 1e3})
     L_mean = L_sum / a.steps
     nbytes = algorithmic_bytes(m, B, M, L_mean)
     achieved = nbytes / (ms_step * 1e-3) / 1e9
@@ -150,6 +168,7 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name),
                      "kernel": "k_step (one launch = one speculative step)",
                      "avg_launch_us": ms_step * 1e3, "algorithmic_bytes_per_launch": nbytes},
+        "by_committed_length": by_L,
     }
     # Plain auto-regressive decoding through the same kernels: a "tree" of the root alone, one
     # token per step.  speedup = accepted tokens per step x t_AR / t_tree (Sec. 4.1's metric); the
