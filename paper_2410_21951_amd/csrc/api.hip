@@ -390,7 +390,7 @@ static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode,
                       int seq0, int nseq) {
     StepParams P;
     P.D = D; P.s = c->s; P.table = table; P.prefill_mode = prefill_mode; P.tau = tau;
-    P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent; P.profile = c->profile;
+    P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent; P.profile = c->profile; P.wide = D.B * D.M >= 256;
     P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq;
     P.lw0 = c->layers[0]; P.dw0 = c->draft[0];
     P.lw_stride = c->layers.size() > 1 ? (size_t)((const char*)c->layers[1].Wqkv - (const char*)c->layers[0].Wqkv) : 0;

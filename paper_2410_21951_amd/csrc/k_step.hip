@@ -41,6 +41,8 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 #define ST_TILE_BYTES (20 * 1024)           // reduction buffer of the linear maps (16 KiB), attention merge buffers
 #define ST_LDS_BYTES (ST_TILE_BYTES + 1024)  // + row statistics
+#define ST_WIDE_TILE_BYTES (64 * 1024)      // reduction buffer of the 64 x 64 units: 4 waves x 16 tiles x 1 KiB
+#define ST_WIDE_LDS_BYTES (ST_WIDE_TILE_BYTES + 1024)
 #define ST_SPIN_LIMIT (1 << 22)
 
 enum { SE_QKV = 0, SE_GELU, SE_LOGITS, SE_RESID, SE_SILU_RESID, SE_F32 };
@@ -82,6 +84,11 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     const Dims& D = P.D;
     const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
     if (ph == 0) return R;
+    if (P.wide && ph >= 1 && ph <= H && (ph == H || (ph - 1) % 5 != 1)) {
+        // 64 x 64 output tiles: groups of four column tiles
+        const int N = ph == H ? D.V1 : (ph - 1) % 5 == 0 ? 3 * D.d : (ph - 1) % 5 == 3 ? D.F : D.d;
+        return pad8(cdiv(cdiv(N, 16), 4)) * RG;
+    }
     if (ph < H) {
         switch ((ph - 1) % 5) {
         case 0: return pad8(3 * D.d / 16) * RG;
@@ -230,7 +237,14 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
     // (column tile, row block) of unit u of a map with NT column tiles; false: empty unit
     int rb = 0;
     nt = 0; row0 = 0;
+    const bool wide = P.wide && ph <= H;   // the draft maps have only B rows: always narrow
     auto split = [&](int NT) {
+        if (wide) {   // unit = (64-row block) * pad8(tile groups) + group of four column tiles
+            const int NG = cdiv(NT, 4), NGp = pad8(NG), gidx = u % NGp;
+            rb = u / NGp;
+            nt = gidx * 4;
+            return gidx < NG;
+        }
         const int NTp = pad8(NT);
         if (u < NTp) { nt = u; rb = 0; }                                            // a single row block
         else if ((NTp & (NTp - 1)) == 0) { nt = u & (NTp - 1); rb = u >> __builtin_ctz(NTp); }   // power of two
@@ -264,7 +278,7 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
         case 2:
             g.X = att_l; g.K = D.d; g.N = D.d; g.Wp = (const uint4*)w.Wo; g.bias = w.bo;
             g.epi = SE_RESID; g.out = xb0 + s.act_stride; g.stats_out = st0 + s.stats_stride;
-            return split(D.d / 16) ? (row0 = rb * 16, true) : false;
+            return split(D.d / 16) ? (row0 = rb * (wide ? 64 : 16), true) : false;
         case 3:
             g.X = xb0 + s.act_stride; g.K = D.d; g.N = D.F; g.Wp = (const uint4*)w.W1; g.bias = w.t_w1; g.colsum = w.cs_w1;
             g.stats = st0 + s.stats_stride; g.epi = SE_GELU; g.out = hid_l;
@@ -272,7 +286,7 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
         default:
             g.X = hid_l; g.K = D.F; g.N = D.d; g.Wp = (const uint4*)w.W2; g.bias = w.b2;
             g.epi = SE_RESID; g.out = xb0 + 2 * s.act_stride; g.stats_out = st0 + 2 * s.stats_stride;
-            return split(D.d / 16) ? (row0 = rb * 16, true) : false;
+            return split(D.d / 16) ? (row0 = rb * (wide ? 64 : 16), true) : false;
         }
     }
     const int RGb = cdiv(D.B, 64);
@@ -537,6 +551,191 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
 }
 
 // ---------------------------------------------------------------------------
+// linear-map unit for many rows (B * M >= 256): 64 rows x 64 columns (four column tiles).
+// Same scheme as above (wave w owns a quarter of the k-steps, operands straight into MFMA
+// registers, partial sums added in wave order through LDS), but every A fragment is used for
+// four column tiles, so a compute unit ingests 256 KB per 64 x 64 outputs instead of 640 KB.
+// All epilogues, including the residual update with the statistics of the new rows.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
+    constexpr int NRT = 4, NCT = 4, CH = 2;
+    const int ph_u = __builtin_amdgcn_readfirstlane(ph_), u_u = __builtin_amdgcn_readfirstlane(u_);
+    const StepParams& P = sP;
+    GemmD g;
+    int nt, row0;
+    if (!describe_gemm(ph_u, u_u, g, nt, row0)) return;
+    extern __shared__ uint4 smem[];
+    float* s_stat = (float*)((char*)smem + ST_WIDE_TILE_BYTES);
+    const Dims& D = P.D;
+    const DevState& s = P.s;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int nks = g.K >> 5, NT = cdiv(g.N, 16);
+    const int ks_lo = (nks * wave) >> 2, ks_hi = (nks * (wave + 1)) >> 2;
+    const uint4* Wp[NCT];
+    bool tile_ok[NCT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+        tile_ok[ct] = nt + ct < NT;   // a tile beyond the last one: skipped
+        Wp[ct] = uniform_ptr(g.Wp + (size_t)(tile_ok[ct] ? nt + ct : nt) * nks * 64);
+    }
+    const uint4* Ap[NRT];
+    bool rowok[NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+        rowok[rt] = row0 + rt * 16 < g.R;
+        Ap[rt] = uniform_ptr((const uint4*)g.X + (size_t)(rowok[rt] ? (row0 >> 4) + rt : 0) * nks * 64);
+    }
+    const uint32_t ulane = (uint32_t)lane;
+    f32x4_t acc[NCT][NRT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) acc[ct][rt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    // epilogue inputs of this thread: row tid / 4, columns 4 (tid % 4) .. + 3 of every tile
+    const int erow = tid >> 2, er = row0 + erow;
+    uint4 cs4[NCT], b4[NCT], xr4[NCT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+        const int n0 = (nt + ct) * 16 + (tid & 3) * 4;
+        cs4[ct] = b4[ct] = xr4[ct] = make_uint4(0, 0, 0, 0);
+        if (tile_ok[ct]) {
+            if (g.colsum) cs4[ct] = ldg4(g.colsum + n0);
+            if (g.bias) b4[ct] = ldg4(g.bias + n0);
+            if (g.epi == SE_RESID && er < g.R) xr4[ct] = ldg4(s.x + (size_t)er * g.N + n0);
+        }
+    }
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    const int tiles = g.K >> 4;
+    const bool do_stats = g.stats != nullptr;
+    if (do_stats && er < g.R) {   // four threads per row, each merges a quarter of the row's tile statistics
+        const float2* sp = (const float2*)g.stats + er;
+        for (int t0 = tid & 3; t0 < tiles; t0 += 32) {
+            float2 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int t = t0 + 4 * j;
+                v[j] = t < tiles ? ldgf2(sp + (size_t)t * g.R) : make_float2(0.f, 0.f);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { s1 += v[j].x; s2 += v[j].y; s3 += v[j].x * v[j].x; }
+        }
+    }
+    for (int kb = ks_lo; kb < ks_hi; kb += CH) {
+        uint4 bw[NCT][CH], aw[NRT][CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const bool kok = kb + i < ks_hi;
+            const uint32_t off = (uint32_t)(kok ? kb + i : kb) * 1024u + ulane * 16u;
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct)
+                bw[ct][i] = (kok && tile_ok[ct]) ? ldg4((const char*)Wp[ct] + off) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int rt = 0; rt < NRT; ++rt)
+                aw[rt][i] = (kok && rowok[rt]) ? ldg4((const char*)Ap[rt] + off) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bw[ct][i]);
+#pragma unroll
+                for (int rt = 0; rt < NRT; ++rt)
+                    acc[ct][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aw[rt][i]), bfrag,
+                                                                          acc[ct][rt], 0, 0, 0);
+            }
+    }
+    if (do_stats) {
+        s1 += __shfl_xor(s1, 1, 64); s1 += __shfl_xor(s1, 2, 64);
+        s2 += __shfl_xor(s2, 1, 64); s2 += __shfl_xor(s2, 2, 64);
+        s3 += __shfl_xor(s3, 1, 64); s3 += __shfl_xor(s3, 2, 64);
+        if ((tid & 3) == 0) {
+            const float mean = s1 / tiles;
+            const float m2 = s2 + 16.f * fmaxf(s3 - tiles * mean * mean, 0.f);
+            s_stat[erow] = mean;
+            s_stat[64 + erow] = rsqrtf(m2 / g.K + LN_EPS);
+        }
+    }
+    __syncthreads();
+    float* red = (float*)smem;   // [wave][ct][rt][lane][4]
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[(((wave * NCT + ct) * NRT + rt) * 64 + lane) * 4 + i] = acc[ct][rt][i];
+    __syncthreads();
+
+    const int rt = erow >> 4, rr = erow & 15, r = er;
+    if (r >= g.R) return;
+    const float mu = do_stats ? s_stat[erow] : 0.f, rstd = do_stats ? s_stat[64 + erow] : 1.f;
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+        const int n0 = (nt + ct) * 16 + (tid & 3) * 4;
+        if (!tile_ok[ct] || n0 >= g.N) continue;
+        float v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = (tid & 3) * 4 + j;
+            const int src = ((ct * NRT + rt) * 64 + (rr >> 2) * 16 + col) * 4 + (rr & 3);
+            float a = red[src];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) a += red[w * (NCT * NRT * 256) + src];
+            const float csj = __uint_as_float(j == 0 ? cs4[ct].x : j == 1 ? cs4[ct].y : j == 2 ? cs4[ct].z : cs4[ct].w);
+            const float bj = __uint_as_float(j == 0 ? b4[ct].x : j == 1 ? b4[ct].y : j == 2 ? b4[ct].z : b4[ct].w);
+            if (do_stats) a = rstd * (a - mu * csj);
+            v[j] = a + bj;
+        }
+        const bool full = n0 + 3 < g.N;
+        switch (g.epi) {
+        case SE_GELU:
+            stw64(g.out + toff(r, n0, g.N >> 5),
+                  (uint64_t)pack_bf16(gelu_s(v[0]), gelu_s(v[1])) | ((uint64_t)pack_bf16(gelu_s(v[2]), gelu_s(v[3])) << 32));
+            break;
+        case SE_LOGITS:
+        case SE_F32:
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (full || n0 + j < g.N) stwf(g.outf + (size_t)r * g.N + n0 + j, v[j]);
+            break;
+        case SE_RESID: {
+            // residual update; the statistics of the tile's 16 columns come from the four threads of the row
+            const float x0 = __uint_as_float(xr4[ct].x) + v[0], x1 = __uint_as_float(xr4[ct].y) + v[1];
+            const float x2 = __uint_as_float(xr4[ct].z) + v[2], x3 = __uint_as_float(xr4[ct].w) + v[3];
+            stwf2(s.x + (size_t)r * g.N + n0, x0, x1);
+            stwf2(s.x + (size_t)r * g.N + n0 + 2, x2, x3);
+            stw64(g.out + toff(r, n0, g.N >> 5), (uint64_t)pack_bf16(x0, x1) | ((uint64_t)pack_bf16(x2, x3) << 32));
+            float sum = x0 + x1 + x2 + x3;
+            sum += __shfl_xor(sum, 1, 64); sum += __shfl_xor(sum, 2, 64);
+            const float mean = sum * (1.f / 16.f);
+            float m2 = (x0 - mean) * (x0 - mean) + (x1 - mean) * (x1 - mean) + (x2 - mean) * (x2 - mean) + (x3 - mean) * (x3 - mean);
+            m2 += __shfl_xor(m2, 1, 64); m2 += __shfl_xor(m2, 2, 64);
+            if ((tid & 3) == 0) stwf2(g.stats_out + ((size_t)(nt + ct) * g.R + r) * 2, mean, m2);
+            break;
+        }
+        case SE_QKV: {
+            const uint64_t pk = (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32);
+            if (n0 < D.d) { stw64(g.out + toff(r, n0, D.d >> 5), pk); break; }
+            const int b = r / D.M, node = r - b * D.M;
+            const int which = n0 / D.d - 1, cc = n0 % D.d, head = cc >> 6, dim = cc & 63;
+            const int pos = ldg(s.L + b) + node;
+            if (pos < D.maxpos && ldg(s.n_rows + b) > 0) {
+                const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
+                if (which) {
+                    bf16_t* vp = (bf16_t*)s.Vc + hb + (size_t)dim * D.maxpos + pos;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) stw16(vp + (size_t)j * D.maxpos, f2bf(v[j]));
+                } else {
+                    stw64((bf16_t*)s.Kc + hb + (size_t)pos * 64 + dim, pk);
+                }
+            }
+            break;
+        }
+        default: break;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // tree-masked attention unit (Sec. 2.1): one head, 16 query rows of one
 // sequence.  Keys: cache positions [0, L) and the rows of this forward at
 // L + m where the query's mask bit m is set.  The four waves take 32-key blocks
@@ -749,12 +948,12 @@ __device__ __forceinline__ void run_unit(int ph, int u) {
     const int H = 1 + 5 * D.Ly;
     // each kind of unit is instantiated once (the kernel's code has to stay small enough for the
     // instruction cache): first decide the kind, then one call site per kind
-    enum { K_EMBED, K_ATTN, K_GEMM4, K_GEMM1, K_EDGE, K_SELECT, K_FINAL, K_COMMIT, K_TOPK };
+    enum { K_EMBED, K_ATTN, K_GEMM4, K_GEMM1, K_GEMMW, K_EDGE, K_SELECT, K_FINAL, K_COMMIT, K_TOPK };
     int kind;
     if (ph == 0) kind = K_EMBED;
     else if (ph < H) {
         const int k = (ph - 1) % 5;
-        kind = k == 1 ? K_ATTN : (k == 0 || k == 3) ? K_GEMM4 : K_GEMM1;
+        kind = k == 1 ? K_ATTN : P.wide ? K_GEMMW : (k == 0 || k == 3) ? K_GEMM4 : K_GEMM1;
     } else {
         switch (ph - H) {
         case TP_EDGES: kind = K_EDGE; break;
@@ -762,7 +961,7 @@ __device__ __forceinline__ void run_unit(int ph, int u) {
         case TP_FINAL: kind = K_FINAL; break;
         case TP_COMMIT: kind = u < D.Ly * D.nH * P.nseq ? K_COMMIT : K_GEMM4; break;
         case TP_TOPK: kind = K_TOPK; break;
-        default: kind = K_GEMM4; break;   // TP_HEAD, TP_DRAFT2
+        default: kind = (P.wide && ph == H) ? K_GEMMW : K_GEMM4; break;   // TP_HEAD, TP_DRAFT2
         }
     }
     switch (kind) {
@@ -770,6 +969,7 @@ __device__ __forceinline__ void run_unit(int ph, int u) {
     case K_ATTN: attn_unit(ph, u); break;
     case K_GEMM4: gemm_unit<4>(ph, u); break;
     case K_GEMM1: gemm_unit<1>(ph, u); break;
+    case K_GEMMW: gemm_wide_unit(ph, u); break;
     case K_EDGE: edge_unit(u); break;
     case K_SELECT: select_unit(u); break;
     case K_FINAL: final_unit(u); break;
@@ -811,16 +1011,17 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
 void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err) {
     static bool once = false;
     if (!once) {
-        (void)hipFuncSetAttribute((const void*)k_step, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step, hipFuncAttributeMaxDynamicSharedMemorySize, ST_WIDE_LDS_BYTES);
         once = true;
     }
     *err = hipSuccess;
+    const size_t lds = p.wide ? ST_WIDE_LDS_BYTES : ST_LDS_BYTES;
     if (p.persistent) {
         // every workgroup of the grid must fit on the GPU at once
         static int resident = -1;
         if (resident < 0) {
             int nb = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_step, 256, ST_LDS_BYTES) != hipSuccess) nb = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_step, 256, ST_WIDE_LDS_BYTES) != hipSuccess) nb = 0;
             resident = nb;
         }
         if (resident < 1) { *err = hipErrorCooperativeLaunchTooLarge; return; }
@@ -836,10 +1037,10 @@ void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err
         // selects the cooperative launch, which makes the runtime check residency.
         static const bool coop = getenv("VADUSA_COOPERATIVE_LAUNCH") != nullptr;
         if (!coop) {
-            hipLaunchKernelGGL(k_step, dim3(n_cus), dim3(256), ST_LDS_BYTES, st, q);
+            hipLaunchKernelGGL(k_step, dim3(n_cus), dim3(256), lds, st, q);
             *err = hipGetLastError();
         } else {
-            *err = hipLaunchCooperativeKernel((const void*)k_step, dim3(n_cus), dim3(256), args, ST_LDS_BYTES, st);
+            *err = hipLaunchCooperativeKernel((const void*)k_step, dim3(n_cus), dim3(256), args, lds, st);
         }
         return;
     }
@@ -848,7 +1049,7 @@ void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err
         q.ph_lo = ph; q.ph_hi = ph + 1;
         const int nu = phase_units(q, ph);
         if (nu <= 0) continue;
-        hipLaunchKernelGGL(k_step, dim3(std::min(nu, 4096)), dim3(256), ST_LDS_BYTES, st, q);
+        hipLaunchKernelGGL(k_step, dim3(std::min(nu, 4096)), dim3(256), lds, st, q);
     }
     *err = hipGetLastError();
 }
