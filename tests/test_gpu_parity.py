@@ -268,3 +268,53 @@ def test_single_node_tree_is_plain_ar(dtype):
         for b in range(2):
             assert ls.sts[b].emitted == O.greedy_ar(model, text[b], prompt[b], len(ls.sts[b].emitted), ignore_eos=True)
     assert s.compared >= 8
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_degenerate_lengths(dtype):
+    """Sequences at the edge of what the boundary accepts: no text at all with a one-token
+    prompt, text only (the first root is predicted from a text position), next to an ordinary
+    one; a sequence with neither text nor prompt is refused."""
+    from paper_2410_21951_amd import VadusaError
+    cfg = small_cfg(dtype)
+    W = make_weights(cfg, 51, std=STD[dtype])
+    rng = np.random.default_rng(52)
+    text = [np.zeros(0, np.int32), rng.integers(0, cfg.text_vocab, 3).astype(np.int32),
+            rng.integers(0, cfg.text_vocab, 5).astype(np.int32)]
+    prompt = [rng.integers(0, cfg.speech_vocab, 1).astype(np.int32), np.zeros(0, np.int32),
+              rng.integers(0, cfg.speech_vocab, 17).astype(np.int32)]
+    tree = make_tree(16, (4, 2, 2))
+    ls = _lock(cfg, W, text, prompt, 16)
+    for tau in (1, 3, 2):
+        ls.step(tree, tau)
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    _say(f"degenerate lengths {dtype}: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e}")
+    assert s.compared >= 2
+    with pytest.raises(VadusaError) as e:
+        ls.dev.prefill([np.zeros(0, np.int32)] * 3, [np.zeros(0, np.int32)] * 3)
+    assert e.value.code == -1
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_maximum_heads_ranks_and_path_length(dtype):
+    """The limits of the boundary at once: 8 draft heads, candidates of rank 15 (the last entry
+    of a 16-wide list), and tau above the vocabulary size, which accepts every edge, so every
+    step commits the deepest leftmost path of 9 nodes and compacts 9 cache rows."""
+    from synth.trees import tree_from_paths
+    cfg = small_cfg(dtype, heads=8)
+    W = make_weights(cfg, 61, std=STD[dtype])
+    rng = np.random.default_rng(62)
+    text, prompt = rand_tokens(cfg, rng, 2, (3, 6), (20, 33))
+    paths = [tuple([0] * d) for d in range(9)] + [(15,), (0, 15), (15, 0), (15, 15), (7,), (0, 0, 15)]
+    paths = sorted(set(paths), key=lambda p: (len(p), p))
+    tree = tree_from_paths(paths)
+    ls = _lock(cfg, W, text, prompt, len(paths))
+    for _ in range(3):
+        r = ls.step(tree, cfg.n_logits + 1)
+        if r is not None:
+            assert all(len(x["accepted"]) == 9 for x in r)
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    _say(f"max heads/ranks {dtype}: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e}")
+    assert s.compared >= 2
