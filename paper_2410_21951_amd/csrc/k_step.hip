@@ -226,6 +226,7 @@ __device__ __forceinline__ void embed_unit(int r_) {
 
 // Descriptor of linear-map unit u of phase ph (all values are workgroup-uniform).  Returns false
 // for an empty unit (padding of the XCD-aware numbering) and for phases that are not linear maps.
+template <bool WIDE>
 __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, int& row0) {
     const StepParams& P = sP;
     const Dims& D = P.D;
@@ -237,7 +238,7 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
     // (column tile, row block) of unit u of a map with NT column tiles; false: empty unit
     int rb = 0;
     nt = 0; row0 = 0;
-    const bool wide = P.wide && ph <= H;   // the draft maps have only B rows: always narrow
+    const bool wide = WIDE && ph <= H;   // the draft maps have only B rows: always narrow
     auto split = [&](int NT) {
         if (wide) {   // unit = (64-row block) * pad8(tile groups) + group of four column tiles
             const int NG = cdiv(NT, 4), NGp = pad8(NG), gidx = u % NGp;
@@ -342,7 +343,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
     const StepParams& P = sP;
     GemmD g;
     int nt, row0;
-    if (!describe_gemm(ph_u, u_u, g, nt, row0)) return;
+    if (!describe_gemm<false>(ph_u, u_u, g, nt, row0)) return;
     extern __shared__ uint4 smem[];
     float* s_stat = (float*)((char*)smem + ST_TILE_BYTES);
     constexpr int CH = NRT == 4 ? 8 : 16;     // k-steps per chunk
@@ -390,7 +391,25 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
     const int tiles = g.K >> 4;
     const bool do_stats = g.stats != nullptr && tid < ROWS * 4;
 
-    for (int kb = ks_lo; kb < ks_hi; kb += CH) {
+    auto merge_stats = [&]() {
+        const int row = tid >> 2, part = tid & 3, r = row0 + row;
+        if (r < g.R) {
+            const float2* sp = (const float2*)g.stats + r;
+            for (int t0 = part; t0 < tiles; t0 += 32) {
+                float2 v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int t = t0 + 4 * j;
+                    v[j] = t < tiles ? ldgf2(sp + (size_t)t * g.R) : make_float2(0.f, 0.f);
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) { s1 += v[j].x; s2 += v[j].y; s3 += v[j].x * v[j].x; }
+            }
+        }
+    };
+    // the first pass always runs: a wave without k-steps (K < 128) loads nothing in it but still
+    // merges the statistics of its rows
+    for (int kb = ks_lo; kb == ks_lo || kb < ks_hi; kb += CH) {
         uint4 bw[CH], aw[NRT][CH];
         if (kb + CH <= ks_hi) {   // a whole chunk (the usual case): straight-line loads
 #pragma unroll
@@ -415,22 +434,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
                 }
         }
         if (kb == ks_lo) tp(g.ph, 6);
-        if (kb == ks_lo && do_stats) {
-            const int row = tid >> 2, part = tid & 3, r = row0 + row;
-            if (r < g.R) {
-                const float2* sp = (const float2*)g.stats + r;
-                for (int t0 = part; t0 < tiles; t0 += 32) {
-                    float2 v[8];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const int t = t0 + 4 * j;
-                        v[j] = t < tiles ? ldgf2(sp + (size_t)t * g.R) : make_float2(0.f, 0.f);
-                    }
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) { s1 += v[j].x; s2 += v[j].y; s3 += v[j].x * v[j].x; }
-                }
-            }
-        }
+        if (kb == ks_lo && do_stats) merge_stats();
         if (kb == ks_lo) tp(g.ph, 7);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
@@ -563,7 +567,7 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
     const StepParams& P = sP;
     GemmD g;
     int nt, row0;
-    if (!describe_gemm(ph_u, u_u, g, nt, row0)) return;
+    if (!describe_gemm<true>(ph_u, u_u, g, nt, row0)) return;
     extern __shared__ uint4 smem[];
     float* s_stat = (float*)((char*)smem + ST_WIDE_TILE_BYTES);
     const Dims& D = P.D;
@@ -942,6 +946,7 @@ __device__ __forceinline__ void topk_unit(int u_) { const int u = __builtin_amdg
 // ---------------------------------------------------------------------------
 // one unit of one phase: dispatch to the unit's own function
 // ---------------------------------------------------------------------------
+template <bool WIDE>
 __device__ __forceinline__ void run_unit(int ph, int u) {
     const StepParams& P = sP;
     const Dims& D = P.D;
@@ -953,7 +958,7 @@ __device__ __forceinline__ void run_unit(int ph, int u) {
     if (ph == 0) kind = K_EMBED;
     else if (ph < H) {
         const int k = (ph - 1) % 5;
-        kind = k == 1 ? K_ATTN : P.wide ? K_GEMMW : (k == 0 || k == 3) ? K_GEMM4 : K_GEMM1;
+        kind = k == 1 ? K_ATTN : WIDE ? K_GEMMW : (k == 0 || k == 3) ? K_GEMM4 : K_GEMM1;
     } else {
         switch (ph - H) {
         case TP_EDGES: kind = K_EDGE; break;
@@ -961,15 +966,15 @@ __device__ __forceinline__ void run_unit(int ph, int u) {
         case TP_FINAL: kind = K_FINAL; break;
         case TP_COMMIT: kind = u < D.Ly * D.nH * P.nseq ? K_COMMIT : K_GEMM4; break;
         case TP_TOPK: kind = K_TOPK; break;
-        default: kind = (P.wide && ph == H) ? K_GEMMW : K_GEMM4; break;   // TP_HEAD, TP_DRAFT2
+        default: kind = (WIDE && ph == H) ? K_GEMMW : K_GEMM4; break;   // TP_HEAD, TP_DRAFT2
         }
     }
     switch (kind) {
     case K_EMBED: embed_unit(u); break;
     case K_ATTN: attn_unit(ph, u); break;
     case K_GEMM4: gemm_unit<4>(ph, u); break;
-    case K_GEMM1: gemm_unit<1>(ph, u); break;
-    case K_GEMMW: gemm_wide_unit(ph, u); break;
+    case K_GEMM1: if constexpr (!WIDE) gemm_unit<1>(ph, u); break;
+    case K_GEMMW: if constexpr (WIDE) gemm_wide_unit(ph, u); break;
     case K_EDGE: edge_unit(u); break;
     case K_SELECT: select_unit(u); break;
     case K_FINAL: final_unit(u); break;
@@ -978,6 +983,9 @@ __device__ __forceinline__ void run_unit(int ph, int u) {
     }
 }
 
+// Two kernels from one body: the ordinary one (up to 255 rows) and the one whose layer maps and
+// base head run as 64 x 64 units (StepParams::wide); each carries only the unit code it uses.
+template <bool WIDE>
 __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
     {
         const uint32_t* src = (const uint32_t*)&Parg;
@@ -996,7 +1004,7 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
         tp(ph, 0);
         const int nu = ph == 0 ? P.D.B * P.D.M : ph < H ? s_nu[(ph - 1) % 5] : s_nu[5 + ph - H];
         for (int u = blockIdx.x; u < nu; u += gridDim.x) {
-            run_unit(ph, u);
+            run_unit<WIDE>(ph, u);
             __syncthreads();
         }
         tp(ph, 1);
@@ -1011,17 +1019,22 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
 void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err) {
     static bool once = false;
     if (!once) {
-        (void)hipFuncSetAttribute((const void*)k_step, hipFuncAttributeMaxDynamicSharedMemorySize, ST_WIDE_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step<true>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_WIDE_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step<false>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS_BYTES);
         once = true;
     }
     *err = hipSuccess;
     const size_t lds = p.wide ? ST_WIDE_LDS_BYTES : ST_LDS_BYTES;
+    void (*kfn)(StepParams) = p.wide ? k_step<true> : k_step<false>;
     if (p.persistent) {
         // every workgroup of the grid must fit on the GPU at once
         static int resident = -1;
         if (resident < 0) {
             int nb = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_step, 256, ST_WIDE_LDS_BYTES) != hipSuccess) nb = 0;
+            int nw = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_step<false>, 256, ST_LDS_BYTES) != hipSuccess) nb = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nw, k_step<true>, 256, ST_WIDE_LDS_BYTES) != hipSuccess) nw = 0;
+            nb = std::min(nb, nw);
             resident = nb;
         }
         if (resident < 1) { *err = hipErrorCooperativeLaunchTooLarge; return; }
@@ -1037,10 +1050,10 @@ void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err
         // selects the cooperative launch, which makes the runtime check residency.
         static const bool coop = getenv("VADUSA_COOPERATIVE_LAUNCH") != nullptr;
         if (!coop) {
-            hipLaunchKernelGGL(k_step, dim3(n_cus), dim3(256), lds, st, q);
+            hipLaunchKernelGGL(kfn, dim3(n_cus), dim3(256), lds, st, q);
             *err = hipGetLastError();
         } else {
-            *err = hipLaunchCooperativeKernel((const void*)k_step, dim3(n_cus), dim3(256), args, lds, st);
+            *err = hipLaunchCooperativeKernel((const void*)kfn, dim3(n_cus), dim3(256), args, lds, st);
         }
         return;
     }
@@ -1049,7 +1062,7 @@ void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err
         q.ph_lo = ph; q.ph_hi = ph + 1;
         const int nu = phase_units(q, ph);
         if (nu <= 0) continue;
-        hipLaunchKernelGGL(k_step, dim3(std::min(nu, 4096)), dim3(256), lds, st, q);
+        hipLaunchKernelGGL(kfn, dim3(std::min(nu, 4096)), dim3(256), lds, st, q);
     }
     *err = hipGetLastError();
 }

@@ -1,0 +1,33 @@
+"""Child process of tests/test_emulated_kernel.py: one lockstep run of the emulated kernels
+against the oracle.  usage: run_case.py <libvadusa_emu.so> <dtype>"""
+import os
+import sys
+import time
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, HERE)
+sys.path.insert(0, os.path.dirname(HERE))
+import emulate
+emulate.install(sys.argv[1])
+import numpy as np
+from synth import ModelConfig, make_weights, make_tree
+from parity import Lockstep
+
+dtype = sys.argv[2]
+cfg = ModelConfig(n_layers=1, d_model=64, n_heads=1, head_dim=64, d_ffn=128, speech_vocab=70, text_vocab=20,
+                  n_draft_heads=2, max_positions=64, dtype=dtype)
+W = make_weights(cfg, 71, std=0.08)
+rng = np.random.default_rng(72)
+text = [rng.integers(0, cfg.text_vocab, 2).astype(np.int32), rng.integers(0, cfg.text_vocab, 3).astype(np.int32)]
+prompt = [rng.integers(0, cfg.speech_vocab, 9).astype(np.int32), rng.integers(0, cfg.speech_vocab, 5).astype(np.int32)]
+tree = make_tree(8, (3, 2))
+t0 = time.time()
+ls = Lockstep(cfg, W, text, prompt, 8)
+for tau in (1, 3):
+    ls.step(tree, tau)
+ls.check_kv(layers=[0])
+s = ls.stats
+print(f"emulated {dtype}: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e} in {time.time() - t0:.0f} s", flush=True)
+assert s.compared >= 1
+sys.stdout.flush()
+os._exit(0)   # the emulation's worker threads never end

@@ -318,3 +318,21 @@ def test_maximum_heads_ranks_and_path_length(dtype):
     s = ls.stats
     _say(f"max heads/ranks {dtype}: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e}")
     assert s.compared >= 2
+
+
+def test_smallest_width_bf16():
+    """d = 64 (one head): a linear map has two k-steps, so two of the four waves of a workgroup
+    have none and only merge the LayerNorm statistics of their rows."""
+    cfg = ModelConfig(n_layers=2, d_model=64, n_heads=1, head_dim=64, d_ffn=128, speech_vocab=70, text_vocab=20,
+                      n_draft_heads=2, max_positions=64, dtype="bf16")
+    W = make_weights(cfg, 71, std=0.08)
+    rng = np.random.default_rng(72)
+    text, prompt = rand_tokens(cfg, rng, 2, (2, 4), (5, 12))
+    tree = make_tree(8, (3, 2))
+    ls = _lock(cfg, W, text, prompt, 8)
+    for tau in (1, 3, 2):
+        ls.step(tree, tau)
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    _say(f"d=64 bf16: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e}")
+    assert s.compared >= 2
