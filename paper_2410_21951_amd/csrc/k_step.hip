@@ -624,12 +624,13 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
             for (int j = 0; j < 8; ++j) { s1 += v[j].x; s2 += v[j].y; s3 += v[j].x * v[j].x; }
         }
     }
-    for (int kb = ks_lo; kb < ks_hi; kb += CH) {
-        uint4 bw[NCT][CH], aw[NRT][CH];
+    // two chunks of CH k-steps in flight alternately: the loads of one chunk overlap the MFMAs of
+    // the other (chunks beyond the wave's range load nothing and multiply zeros)
+    auto load_chunk = [&](int kb, uint4 (&bw)[NCT][CH], uint4 (&aw)[NRT][CH]) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const bool kok = kb + i < ks_hi;
-            const uint32_t off = (uint32_t)(kok ? kb + i : kb) * 1024u + ulane * 16u;
+            const uint32_t off = (uint32_t)(kok ? kb + i : ks_lo) * 1024u + ulane * 16u;
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct)
                 bw[ct][i] = (kok && tile_ok[ct]) ? ldg4((const char*)Wp[ct] + off) : make_uint4(0, 0, 0, 0);
@@ -637,6 +638,8 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
             for (int rt = 0; rt < NRT; ++rt)
                 aw[rt][i] = (kok && rowok[rt]) ? ldg4((const char*)Ap[rt] + off) : make_uint4(0, 0, 0, 0);
         }
+    };
+    auto mfma_chunk = [&](const uint4 (&bw)[NCT][CH], const uint4 (&aw)[NRT][CH]) {
 #pragma unroll
         for (int i = 0; i < CH; ++i)
 #pragma unroll
@@ -647,6 +650,16 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
                     acc[ct][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aw[rt][i]), bfrag,
                                                                           acc[ct][rt], 0, 0, 0);
             }
+    };
+    {
+        uint4 bw0[NCT][CH], aw0[NRT][CH], bw1[NCT][CH], aw1[NRT][CH];
+        load_chunk(ks_lo, bw0, aw0);
+        for (int kb = ks_lo; kb < ks_hi; kb += 2 * CH) {
+            load_chunk(kb + CH, bw1, aw1);
+            mfma_chunk(bw0, aw0);
+            load_chunk(kb + 2 * CH, bw0, aw0);
+            mfma_chunk(bw1, aw1);
+        }
     }
     if (do_stats) {
         s1 += __shfl_xor(s1, 1, 64); s1 += __shfl_xor(s1, 2, 64);
