@@ -33,6 +33,19 @@ def algorithmic_bytes(m, B, M, L_mean):
     return w_layers + w_out + w_draft + B * L_mean * kv_pos + B * M * kv_pos
 
 
+def algorithmic_flops(m, B, M, L_mean):
+    """Multiply-adds x 2 of one step: the linear maps on all B * M rows, the draft heads on B rows,
+    attention of every row over the committed keys and (on average half of) the tree rows."""
+    d, F, V1, R = m.d_model, m.d_ffn, m.n_logits, B * M
+    maps = 2.0 * R * (m.n_layers * (3 * d * d + d * d + 2 * d * F) + V1 * d)
+    draft = 2.0 * B * m.n_draft_heads * (d * d + V1 * d)
+    attn = 4.0 * R * (L_mean + M / 2.0) * d * m.n_layers
+    return maps + draft + attn
+
+
+MFMA_PEAK_TFLOPS = 2500.0   # dense bf16
+
+
 def measured_traffic(workload):
     """HBM bytes per k_step launch from the rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by a
     copy kernel of known size); the summary under profiles/ carries the figure on a `traffic_bytes_per_launch:`
@@ -154,6 +167,8 @@ def main():
     L_mean = L_sum / a.steps
     nbytes = algorithmic_bytes(m, B, M, L_mean)
     achieved = nbytes / (ms_step * 1e-3) / 1e9
+    nflops = algorithmic_flops(m, B, M, L_mean)
+    tflops = nflops / (ms_step * 1e-3) / 1e12
     out = {
         "metric": "verified_tree_tokens_per_s", "value": B * M / (ms_step * 1e-3), "unit": "tree tokens/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
@@ -164,10 +179,19 @@ def main():
                    "mean_committed_per_step": float(np.mean(n_out)) / min(seg, a.steps)},
         # dominant kernel: k_step, the persistent kernel that runs a whole step; one launch per step,
         # so its average launch duration is the event-timed region divided by the number of steps
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name),
-                     "kernel": "k_step (one launch = one speculative step)",
-                     "avg_launch_us": ms_step * 1e3, "algorithmic_bytes_per_launch": nbytes},
+        # the roof that bounds the step: HBM bytes at batch 1 (64 flop per weight byte); from ~1000
+        # rows on the contractions at MFMA peak take longer than the bytes at HBM peak
+        "roofline": ({"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name),
+                      "kernel": "k_step (one launch = one speculative step)",
+                      "avg_launch_us": ms_step * 1e3, "algorithmic_bytes_per_launch": nbytes,
+                      "algorithmic_flops_per_launch": nflops, "tflops": tflops}
+                     if nbytes / (HBM_PEAK_GBS * 1e9) >= nflops / (MFMA_PEAK_TFLOPS * 1e12) else
+                     {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                      "frac": tflops / MFMA_PEAK_TFLOPS, "traffic": measured_traffic(wl.name),
+                      "kernel": "k_step (one launch = one speculative step)",
+                      "avg_launch_us": ms_step * 1e3, "algorithmic_bytes_per_launch": nbytes,
+                      "algorithmic_flops_per_launch": nflops, "hbm_gbs": achieved}),
         "by_committed_length": by_L,
     }
     # Plain auto-regressive decoding through the same kernels: a "tree" of the root alone, one
