@@ -125,7 +125,6 @@ __device__ inline void dev_accept(const Dims& D, const DevState& s, int b, int t
         return;
     }
     const int32_t* parent = s.t_parent[0];
-    const int32_t* depth = s.t_depth[0];
     const int32_t* tok = s.tok + (size_t)b * D.M;
     // Wave w owns the edges n = w + 4j.  Lane j first fetches parent, token and the token's logit
     // of edge j, so that chain of three dependent loads is paid once per wave, not once per

@@ -449,7 +449,6 @@ static void forward(vadusa_ctx* c, const Dims& D, int table, int prefill_mode, b
 // Draft heads on the hidden state of the last accepted node (Sec. 2.1,
 // Sec. 3.1.1): z_i = W2_i (h + SiLU(W1_i h + b1_i)), then the top-k lists.
 static void draft_heads(vadusa_ctx* c, const Dims& D, int seq0, int nseq) {
-    const int dt = c->cfg.dtype;
     const DevState& s = c->s;
     for (int i = 0; i < D.Hh; ++i) {
         char* r = (char*)s.rdraft + ((size_t)i * D.Bmax + seq0) * D.d * c->elem;

@@ -231,7 +231,7 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
     const StepParams& P = sP;
     const Dims& D = P.D;
     const DevState& s = P.s;
-    const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
+    const int R = D.B * D.M, H = 1 + 5 * D.Ly;
     if (ph == 0) return false;
     g.R = R; g.stats = nullptr; g.colsum = nullptr; g.bias = nullptr; g.out = nullptr; g.outf = nullptr;
     g.stats_out = nullptr; g.layer = 0; g.ph = ph;
@@ -352,7 +352,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
     const DevState& s = P.s;
     // the wave index is the same for all lanes of a wave: say so, and everything derived from it
     // (k-step range, loop bounds) stays in scalar registers and branches are scalar
-    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, gq = lane >> 4, c = lane & 15;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int nks = g.K >> 5;
     const int ks_lo = (nks * wave) >> 2, ks_hi = (nks * (wave + 1)) >> 2;
     // Operand addresses are kept as a workgroup-uniform base (scalar registers) plus a 32-bit
@@ -475,7 +475,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
             float v[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int col = (tid & 3) * 4 + j, n = n0 + j;
+                const int col = (tid & 3) * 4 + j;
                 const int src = ((rt * 64) + (rr >> 2) * 16 + col) * 4 + (rr & 3);
                 float a = red[src];
 #pragma unroll
