@@ -215,6 +215,63 @@ def main():
     out["ar_step"] = {"us_per_step": ar_us, "steps": n_ar, "tree_step_over_ar_step": ms_step * 1e3 / ar_us,
                       "speedup_at_paper_accepted_len": {"tau1_acc3.00": 3.00 * ar_us / (ms_step * 1e3),
                                                         "tau3_acc3.87": 3.87 * ar_us / (ms_step * 1e3)}}
+    # Acceptance dial (batch 1 only).  Random-init draft heads are never right, so the timed run
+    # above commits one token per step.  To time acceptance and compaction with paper-shaped path
+    # lengths, the draft lists are planted: the greedy continuation is recorded first (tau = 1 is
+    # lossless, so the stream of the run above is that continuation), then head i's list gets
+    # the true token i steps ahead at rank 0 with probability alpha (seeded), a wrong one
+    # otherwise.  alpha = 0.755 gives sum_k alpha^k = 3.0 accepted tokens per step with four
+    # heads (the paper's Table 1 at tau = 1).  Each step returns its accepted tokens to the host
+    # (one synchronisation per step, included in the time).
+    # bf16 rounding differs between a token verified as a tree node and the same token decoded as
+    # a root, so an arg-max inside a near-tie can flip and the planted run then leaves the
+    # recorded continuation: it is recorded again from there (untimed) and the run goes on.
+    if B == 1 and a.tau == 1 and a.steps >= 50:
+        rng = np.random.default_rng(wl.seed + 99)
+        alpha, Hh, V = 0.755, m.n_draft_heads, m.speech_vocab
+        cur = np.asarray(prompt[0], np.int32)
+
+        def record(p, n):
+            dev.prefill(text, [p])
+            for _ in range(n):
+                dev.step(tarr, 1, sync=False)
+            f = dev.read_output(0).tolist()
+            dev.prefill(text, [p])
+            return f
+
+        future = record(cur, 150)
+        pos = n_steps = n_tok = rerecorded = 0
+        el = 0.0
+        while n_steps < 200 and len(cur) + pos + 160 < m.max_positions - M - len(text[0]):
+            if pos + Hh + 2 >= len(future):
+                cur = np.concatenate([cur, np.asarray(future[:pos], np.int32)])
+                future, pos = record(cur, 150), 0
+            lists = []
+            for i in range(1, Hh + 1):      # the root is future[pos]; head i must propose future[pos + i]
+                true = future[pos + i]
+                ids = [(true + 1 + j) % V for j in range(16)]          # 16 wrong candidates
+                if rng.random() < alpha:
+                    ids[0] = true
+                lists.append(ids)
+            t0 = time.perf_counter()
+            acc = dev.step(tarr, 1, override=[lists], sync=True)[0]
+            el += time.perf_counter() - t0
+            n_steps += 1
+            n_tok += len(acc)
+            if acc == future[pos:pos + len(acc)]:
+                pos += len(acc)
+            else:
+                rerecorded += 1
+                cur = np.concatenate([cur, np.asarray(dev.read_output(0), np.int32)])
+                future, pos = record(cur, 150), 0
+        out["acceptance_dial"] = {"alpha": alpha, "steps": n_steps, "mean_accepted_per_step": n_tok / max(n_steps, 1),
+                                  "us_per_step_incl_host_sync": el / max(n_steps, 1) * 1e6,
+                                  "accepted_tokens_per_s": n_tok / el if el else 0.0,
+                                  "ar_tokens_per_s": 1e6 / ar_us,
+                                  "speedup_over_ar_incl_host_sync": (n_tok / el) / (1e6 / ar_us) if el else 0.0,
+                                  # device time only: accepted tokens per step x t_AR / t_tree, both without host round trips
+                                  "speedup_over_ar_device_time": (n_tok / max(n_steps, 1)) * ar_us / (ms_step * 1e3),
+                                  "continuation_recorded_again": rerecorded}
     dev.close()
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, W, text, prompt, tree)
