@@ -88,6 +88,21 @@ typedef struct {
  * is non-null a description of the first problem is written (at most msg_bytes). */
 int vadusa_config_check(const vadusa_config* cfg, char* msg, size_t msg_bytes);
 
+/* Builds a sparse candidate tree (Sec. 2.4: within a fixed number of nodes, maximise the
+ * expected accepted length).  acc is host memory [n_heads][width]: acc[i][r] is the measured
+ * probability that draft head i+1's rank-r candidate is accepted given that its parent was
+ * (from a calibration run with the full tree); every value must lie in [0, 1].  A node's path
+ * probability is the product of the acc values along its rank path; the n_nodes nodes (root
+ * included) of largest path probability are kept, which is the ancestor-closed set of that
+ * size with the largest expected accepted length.  Equal probabilities: the shallower node
+ * first, then the lexicographically smaller rank path.  Output in canonical order into the
+ * caller's arrays parent[n_nodes], rank[n_nodes]; *n_out receives the number of nodes (less
+ * than n_nodes only if the full tree is smaller).  VADUSA_EINVAL for bad arguments
+ * (n_heads outside 1..VADUSA_MAX_DRAFT_HEADS, width outside 1..VADUSA_MAX_TOPK, n_nodes
+ * outside 1..VADUSA_MAX_TREE_NODES, a value outside [0, 1], null pointers). */
+int vadusa_build_tree(int32_t n_heads, int32_t width, const float* acc, int32_t n_nodes,
+                      int32_t* parent, int32_t* rank, int32_t* n_out);
+
 /* Checks a tree against a configuration (rules above). */
 int vadusa_tree_check(const vadusa_config* cfg, const vadusa_tree_spec* tree,
                       char* msg, size_t msg_bytes);

@@ -92,6 +92,59 @@ static int tree_depths(const vadusa_config* c, const vadusa_tree_spec* t, std::v
     return VADUSA_OK;
 }
 
+// Sec. 2.4's greedy construction: best-first expansion of the full top-k tree by path
+// probability.  A child's probability never exceeds its parent's, so the set taken is
+// ancestor-closed, and taking the largest probabilities maximises their sum, the expected
+// number of accepted draft tokens.
+extern "C" int vadusa_build_tree(int32_t n_heads, int32_t width, const float* acc, int32_t n_nodes,
+                                 int32_t* parent, int32_t* rank, int32_t* n_out) {
+    if (!acc || !parent || !rank || !n_out) return VADUSA_EINVAL;
+    if (n_heads < 1 || n_heads > VADUSA_MAX_DRAFT_HEADS || width < 1 || width > VADUSA_MAX_TOPK ||
+        n_nodes < 1 || n_nodes > VADUSA_MAX_TREE_NODES)
+        return VADUSA_EINVAL;
+    for (int i = 0; i < n_heads * width; ++i)
+        if (!(acc[i] >= 0.f && acc[i] <= 1.f)) return VADUSA_EINVAL;
+    struct Cand { double p; std::vector<int32_t> path; };
+    // "a goes before b": larger probability, then shallower, then smaller rank path
+    auto before = [](const Cand& a, const Cand& b) {
+        if (a.p != b.p) return a.p > b.p;
+        if (a.path.size() != b.path.size()) return a.path.size() < b.path.size();
+        return a.path < b.path;
+    };
+    std::vector<Cand> open{Cand{1.0, {}}}, chosen;
+    while (!open.empty() && (int)chosen.size() < n_nodes) {
+        size_t best = 0;
+        for (size_t i = 1; i < open.size(); ++i)
+            if (before(open[i], open[best])) best = i;
+        Cand c = open[best];
+        open.erase(open.begin() + (long)best);
+        if ((int)c.path.size() < n_heads)
+            for (int r = 0; r < width; ++r) {
+                Cand ch{c.p * (double)acc[c.path.size() * (size_t)width + r], c.path};
+                ch.path.push_back(r);
+                open.push_back(ch);
+            }
+        chosen.push_back(c);
+    }
+    // canonical order: depth, then rank path
+    std::sort(chosen.begin(), chosen.end(), [](const Cand& a, const Cand& b) {
+        if (a.path.size() != b.path.size()) return a.path.size() < b.path.size();
+        return a.path < b.path;
+    });
+    for (size_t i = 0; i < chosen.size(); ++i) {
+        const auto& p = chosen[i].path;
+        rank[i] = p.empty() ? 0 : p.back();
+        parent[i] = -1;
+        if (!p.empty()) {
+            const std::vector<int32_t> pp(p.begin(), p.end() - 1);
+            for (size_t j = 0; j < i; ++j)
+                if (chosen[j].path == pp) { parent[i] = (int32_t)j; break; }
+        }
+    }
+    *n_out = (int32_t)chosen.size();
+    return VADUSA_OK;
+}
+
 extern "C" int vadusa_tree_check(const vadusa_config* c, const vadusa_tree_spec* t, char* msg, size_t n) {
     int rc = vadusa_config_check(c, msg, n);
     if (rc) return rc;

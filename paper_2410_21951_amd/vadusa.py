@@ -42,6 +42,8 @@ class DBG:
 EXPORTS = {
     "vadusa_config_check": (C.c_int, [C.POINTER(_Config), C.c_char_p, C.c_size_t]),
     "vadusa_tree_check": (C.c_int, [C.POINTER(_Config), C.POINTER(_Tree), C.c_char_p, C.c_size_t]),
+    "vadusa_build_tree": (C.c_int, [C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                    C.POINTER(C.c_int32)]),
     "vadusa_arena_bytes": (C.c_size_t, [C.POINTER(_Config)]),
     "vadusa_blob_floats": (C.c_size_t, [C.POINTER(_Config)]),
     "vadusa_create": (C.c_int, [C.POINTER(_Config), C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]),
@@ -92,6 +94,20 @@ class TreeArrays:
         self.n_nodes = int(self.parent.shape[0])
         self.c = _Tree(self.n_nodes, self.parent.ctypes.data_as(C.POINTER(C.c_int32)),
                        self.rank.ctypes.data_as(C.POINTER(C.c_int32)))
+
+
+def build_tree(acc, n_nodes):
+    """Sparse candidate tree from per-head, per-rank acceptance probabilities acc [n_heads][width]
+    (vadusa_build_tree; needs no GPU).  Returns TreeArrays."""
+    lib = load_library()
+    acc = np.ascontiguousarray(acc, dtype=np.float32)
+    parent = np.zeros(n_nodes, np.int32)
+    rank = np.zeros(n_nodes, np.int32)
+    n = C.c_int32(0)
+    rc = lib.vadusa_build_tree(acc.shape[0], acc.shape[1], _ptr(acc), int(n_nodes), _ptr(parent), _ptr(rank), C.byref(n))
+    if rc:
+        raise VadusaError(rc, "vadusa_build_tree: bad arguments")
+    return TreeArrays(parent[:n.value], rank[:n.value])
 
 
 def make_config(model, max_batch, max_tree_nodes, ignore_eos=False):

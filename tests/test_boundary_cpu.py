@@ -86,3 +86,53 @@ def test_blob_order_matches_generator():
     from synth import weight_names
     for wl in (PRESETS["tiny"], PRESETS["longform_b1"]):
         assert [n for n, _, _ in weight_names(wl.model)] == V.blob_order(wl.model)
+
+
+def test_build_tree_matches_bruteforce_and_reference_generator():
+    """vadusa_build_tree (Sec. 2.4): the chosen set is ancestor-closed, canonical, and has the
+    largest expected accepted length of all ancestor-closed sets of its size (brute force on a
+    small full tree); on larger tables it picks the same nodes as an independent best-first
+    search written in Python."""
+    import heapq
+    import itertools
+    import numpy as np
+    from paper_2410_21951_amd import build_tree, VadusaError
+    rng = np.random.default_rng(5)
+    # brute force: 2 heads x 3 ranks -> 1 + 3 + 9 = 13 nodes, choose the best 6
+    acc = rng.uniform(0.05, 0.9, (2, 3)).astype(np.float32)
+    t = build_tree(acc, 6)
+    paths = [()] + [(r,) for r in range(3)] + [(a, b) for a in range(3) for b in range(3)]
+    prob = {p: float(np.prod([np.float64(acc[i][r]) for i, r in enumerate(p)])) for p in paths}
+    best = max((sum(prob[p] for p in sub), sub) for sub in itertools.combinations(paths, 6)
+               if () in sub and all(p[:-1] in sub for p in sub if p))
+    got = []
+    for n in range(t.n_nodes):
+        p, m = [], n
+        while m > 0:
+            p.append(int(t.rank[m])); m = int(t.parent[m])
+        got.append(tuple(reversed(p)))
+    assert sorted(got) == sorted(best[1])
+    assert got == sorted(got, key=lambda p: (len(p), p))          # canonical order
+    # larger: 4 heads x 10 ranks, 64 nodes, against a heap-based search
+    acc = np.sort(rng.uniform(0.01, 0.8, (4, 10)).astype(np.float32), axis=1)[:, ::-1].copy()
+    t = build_tree(acc, 64)
+    heap, chosen = [(-1.0, 0, ())], []
+    while len(chosen) < 64:
+        negp, dep, path = heapq.heappop(heap)
+        chosen.append(path)
+        if dep < 4:
+            for r in range(10):
+                heapq.heappush(heap, (negp * float(np.float64(acc[dep][r])), dep + 1, path + (r,)))
+    want = sorted(chosen, key=lambda p: (len(p), p))
+    got = []
+    for n in range(t.n_nodes):
+        p, m = [], n
+        while m > 0:
+            p.append(int(t.rank[m])); m = int(t.parent[m])
+        got.append(tuple(reversed(p)))
+    assert got == want
+    # the library accepts its own tree, and refuses bad arguments
+    with pytest.raises(VadusaError):
+        build_tree(np.full((2, 3), 1.5, np.float32), 4)
+    with pytest.raises(VadusaError):
+        build_tree(acc, 500)
