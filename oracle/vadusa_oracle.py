@@ -17,6 +17,11 @@ Parity status of the functions below
   * generate at tau > 1      replay property only; the exact token stream at
                              tau > 1 is defined by the readings stated here:
                              parity unpinned beyond that property.
+  * nucleus / gumbel / perturbed_scores / step(sample=...)
+                             pinned (hand-worked nucleus cases, brute-force set
+                             definition, draw frequencies against the closed-form
+                             probabilities of sampling without replacement, limits
+                             that reduce to the deterministic rule)
 """
 from dataclasses import dataclass, field
 from typing import List, Optional, Sequence
@@ -263,13 +268,72 @@ def select_path(tree, tok, logits, tau):
     return best
 
 
-def step(model, st, tree, tau, draft_override=None, ignore_eos=False):
+# --------------------------------------------------------------------------
+# Stochastic verification: Algorithm 1 as printed draws, at every position i of
+# a branch, tau tokens from the nucleus of the temperature-scaled distribution
+# of L(i) and accepts the next candidate iff it is among the draws (Sec. 3.1.2:
+# nucleus sampling with a temperature).
+# Readings where the paper is silent: the tau draws are without replacement; a
+# nucleus smaller than tau is widened to the tau most probable tokens so that
+# tau draws exist; the continuation token after the accepted sequence is the
+# first draw at its last position.
+# The draws come from uniforms u in (0, 1) handed in by the caller, one per
+# (position, token): with g = -log(-log u), ordering the kept tokens by
+# s + g (s = logit / temperature) lists them in the order successive draws
+# without replacement from softmax(s) would produce them (the "Gumbel top-k"
+# identity), so "among the tau draws" is "among the tau largest s + g".
+# --------------------------------------------------------------------------
+def nucleus(s, top_p, min_keep=1):
+    """Which tokens nucleus sampling keeps (bool per token) for scores s.
+
+    Token v is kept iff the tokens with a strictly larger score hold less than
+    top_p of softmax(s)'s probability, i.e. the most probable tokens are taken
+    until their mass reaches top_p; tokens of equal score are kept or dropped
+    together.  A token with fewer than min_keep tokens strictly above it is kept
+    in any case.  top_p >= 1 keeps every token.
+    """
+    s = np.asarray(s, dtype=np.float64)
+    if top_p >= 1.0:
+        return np.ones(s.shape, bool)
+    p = softmax_rows(s)
+    order = np.argsort(-s, kind="stable")
+    ss, ps = s[order], p[order]
+    before_me = np.concatenate([[0.0], np.cumsum(ps)[:-1]])     # mass of the tokens sorted ahead
+    first_equal = np.searchsorted(-ss, -ss, side="left")          # start of each run of equal scores
+    mass_above = before_me[first_equal]
+    keep_sorted = (mass_above < top_p) | (first_equal < min_keep)
+    keep = np.empty(s.shape, bool)
+    keep[order] = keep_sorted
+    return keep
+
+
+def gumbel(u):
+    """Standard Gumbel variate from a uniform u in (0, 1)."""
+    with np.errstate(divide="ignore"):
+        return -np.log(-np.log(np.asarray(u, dtype=np.float64)))
+
+
+def perturbed_scores(z, u, temperature, top_p, tau):
+    """Row(s) of s + g over the kept tokens, -inf elsewhere; z, u [..., V+1].
+    The tau largest entries of a row are that position's tau draws, in order."""
+    z = np.asarray(z, dtype=np.float64)
+    s = z / temperature
+    g = gumbel(u)
+    flat_s = s.reshape(-1, s.shape[-1])
+    keep = np.stack([nucleus(r, top_p, min_keep=tau) for r in flat_s]).reshape(s.shape)
+    return np.where(keep, s + g, -np.inf)
+
+
+def step(model, st, tree, tau, draft_override=None, ignore_eos=False, sample=None):
     """One speculative step (Sec. 2.1 decoding pass + Sec. 2.3): expand, verify the
     whole tree in one forward, accept, commit the accepted path's keys/values and
     continue from the last accepted node's prediction.
 
     draft_override: optional per-head id lists used in place of the draft heads'
     own top-k (test hook to plant longer accepted paths).
+    sample: None for the deterministic rule, or (temperature, top_p, u) with
+    uniforms u [M, V+1] for the stochastic rule of Algorithm 1: the same choice
+    among branches, taken on the perturbed scores instead of the logits.
     Returns a dict with everything a lockstep comparison needs.
     """
     cfg = model.cfg
@@ -279,7 +343,8 @@ def step(model, st, tree, tau, draft_override=None, ignore_eos=False):
         [np.asarray(a, np.int64) for a in draft_override]
     tok = expand_tree(st.root, lists, tree)
     logits, h, k, v = tree_forward(model, st, tok, tree)
-    path = select_path(tree, tok, logits, tau)
+    scores = logits if sample is None else perturbed_scores(logits, sample[2], sample[0], sample[1], tau)
+    path = select_path(tree, tok, scores, tau)
     accepted = [int(tok[n]) for n in path]
     # EOS (id V): paper silent; reading: the path is cut after the first EOS and
     # the sequence stops, unless the fixed-length benchmarks ask to ignore it.
@@ -292,11 +357,11 @@ def step(model, st, tree, tau, draft_override=None, ignore_eos=False):
     st.V[:, st.L:st.L + n] = v[:, path]
     st.L += n
     last = path[-1]
-    st.root = int(top_k(logits[last], 1)[0])          # prediction of the last accepted token
-    st.root_logits = logits[last]
+    st.root = int(top_k(scores[last], 1)[0])          # prediction of the last accepted token (first draw)
+    st.root_logits = scores[last]
     st.draft_logits = draft_heads(model, h[last])     # new drafts from that position
     st.emitted += accepted
-    return dict(accepted=accepted, path=path, tok=tok, logits=logits, lists=lists,
+    return dict(accepted=accepted, path=path, tok=tok, logits=logits, scores=scores, lists=lists,
                 h=h, next_root=st.root)
 
 
