@@ -215,6 +215,32 @@ def main():
     out["ar_step"] = {"us_per_step": ar_us, "steps": n_ar, "tree_step_over_ar_step": ms_step * 1e3 / ar_us,
                       "speedup_at_paper_accepted_len": {"tau1_acc3.00": 3.00 * ar_us / (ms_step * 1e3),
                                                         "tau3_acc3.87": 3.87 * ar_us / (ms_step * 1e3)}}
+    # The stochastic form of Algorithm 1 (temperature 0.9, top_p 0.9 as in Sec. 3.1.2's sampling runs):
+    # the same step with the perturbed-score kernel between the base head and the acceptance; the
+    # uniforms are drawn on the device beforehand (their generation is not part of the step).
+    n_st = min(a.steps, 300)
+    u_dev = torch.rand(B * M * (m.speech_vocab + 1), device="cuda").clamp_(2.0 ** -24, 1.0 - 2.0 ** -24)
+    dev.prefill(text, prompt)
+    for _ in range(5):
+        dev.step(tarr, a.tau, sync=False, sample=(0.9, 0.9, u_dev))
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(n_st):
+        dev.step(tarr, a.tau, sync=False, sample=(0.9, 0.9, u_dev))
+    ev1.record()
+    torch.cuda.synchronize()
+    st_us = ev0.elapsed_time(ev1) / n_st * 1e3
+    dev.prefill(text, prompt)                    # the deterministic step over the same span of lengths
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(n_st):
+        dev.step(tarr, a.tau, sync=False)
+    ev1.record()
+    torch.cuda.synchronize()
+    det_us = ev0.elapsed_time(ev1) / n_st * 1e3
+    out["stochastic_step"] = {"temperature": 0.9, "top_p": 0.9, "us_per_step": st_us, "steps": n_st,
+                              "deterministic_us_per_step_same_lengths": det_us,
+                              "over_deterministic_step": st_us / det_us}
     # Acceptance dial (batch 1 only).  Random-init draft heads are never right, so the timed run
     # above commits one token per step.  To time acceptance and compaction with paper-shaped path
     # lengths, the draft lists are planted: the greedy continuation is recorded first (tau = 1 is

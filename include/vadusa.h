@@ -205,6 +205,42 @@ int vadusa_step(vadusa_ctx* ctx, const vadusa_tree_spec* tree, int32_t tau,
                 const int32_t* draft_override,
                 int32_t* accepted_tok, int32_t* accepted_len);
 
+/*
+ * Stochastic form of Algorithm 1 (the verification as printed: at every position of a branch
+ * tau tokens are drawn from the nucleus of the temperature-scaled distribution, Sec. 3.1.2,
+ * and the next candidate is accepted iff it is among the draws).
+ * With s = logit / temperature, the nucleus of a position keeps token v iff the tokens of
+ * strictly larger s hold less than top_p of softmax(s) (equal s: kept or dropped together);
+ * it is widened to the tau most probable tokens where it would hold fewer, so that tau draws
+ * exist; top_p >= 1 keeps every token.  The tau draws are without replacement and come from
+ * the caller's uniforms: the kept tokens are ordered by s - log(-log u), which lists them in
+ * the order successive draws would, and the first tau are the draws.  The continuation token
+ * after the accepted path is the first draw at its last node.
+ * uniforms: [batch][tree->n_nodes][V+1] floats, each strictly inside (0, 1), independent;
+ * host memory (copied before the call returns) or, with uniforms_on_device = 1, device memory
+ * (copied on the stream).  The prefill's first root stays the most probable token.
+ * Needs (V+1) * 4 <= 65536 bytes (VADUSA_ESHAPE otherwise).
+ */
+typedef struct {
+    float        temperature;        /* > 0 */
+    float        top_p;              /* > 0; >= 1 keeps every token */
+    const float* uniforms;
+    int32_t      uniforms_on_device; /* 0: host pointer, 1: device pointer */
+} vadusa_sampling;
+
+/* vadusa_verify with the stochastic rule; vadusa_kv_compact then continues from the first
+ * draw at the last committed node.  Same state rules and errors as vadusa_verify, plus
+ * VADUSA_EINVAL for a bad temperature / top_p or null pointers.  Does not synchronise
+ * unless the uniforms come from host memory. */
+int vadusa_verify_sampled(vadusa_ctx* ctx, const vadusa_tree_spec* tree, int32_t tau,
+                          const vadusa_sampling* sampling, const int32_t* draft_override);
+
+/* vadusa_step with the stochastic rule (= vadusa_verify_sampled + vadusa_kv_compact(-1, NULL, 0));
+ * outputs as in vadusa_step. */
+int vadusa_step_sampled(vadusa_ctx* ctx, const vadusa_tree_spec* tree, int32_t tau,
+                        const vadusa_sampling* sampling, const int32_t* draft_override,
+                        int32_t* accepted_tok, int32_t* accepted_len);
+
 /* All tokens committed so far for `seq` (after synchronising the stream).
  * tok: host [capacity] out (may be NULL to query the count); *n_out: count. */
 int vadusa_read_output(vadusa_ctx* ctx, int32_t seq, int32_t* tok, int32_t capacity,
@@ -223,11 +259,14 @@ enum {
     VADUSA_DBG_PATH       = 7,  /* int32 [batch][n_draft_heads+2]: count, then node indices */
     VADUSA_DBG_FINISHED   = 8,  /* int32 [batch] */
     VADUSA_DBG_DRAFT_LOGITS = 9, /* float [batch][n_draft_heads][V+1], logits behind the lists */
-    VADUSA_DBG_PHASE_CLOCK = 10  /* int64 [128][8]: device clock (100 MHz) of workgroup 0 in the last launch of
+    VADUSA_DBG_PHASE_CLOCK = 10, /* int64 [128][8]: device clock (100 MHz) of workgroup 0 in the last launch of
                                     the bf16 step kernel: [p][0] start of phase p, [p][1] its own units done,
                                     [p][2..] points inside a unit, [127][0] end of the kernel.  Recorded only by
                                     contexts created while the environment variable VADUSA_PHASE_CLOCK is set
                                     (each point costs a few hundred ns); zero otherwise */
+    VADUSA_DBG_SCORES     = 11  /* float [batch][M][V+1]: the perturbed scores (s - log(-log u) on the nucleus,
+                                    -inf elsewhere) of the last stochastic verification; VADUSA_ESTATE if the
+                                    last verification was a deterministic one */
 };
 
 /* Copies one of the items above to host memory after synchronising the stream.

@@ -1,6 +1,7 @@
 // C ABI of libvadusa: argument checks, arena layout, weight loading and the
 // order in which the kernels of a prefill / verification / compaction run.
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -174,7 +175,8 @@ struct WeightSlot {
 };
 
 static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vector<LayerW>* layers,
-                     std::vector<DraftW>* draft, std::vector<WeightSlot>* slots, size_t* staging_floats) {
+                     std::vector<DraftW>* draft, std::vector<WeightSlot>* slots, size_t* staging_floats,
+                     float** uniforms = nullptr, float** scores = nullptr) {
     Carver cv{base};
     const size_t e = c.dtype ? 2 : 4;
     const size_t d = c.d_model, F = c.d_ffn, V1 = c.speech_vocab + 1, Hh = c.n_draft_heads;
@@ -265,6 +267,10 @@ static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vecto
         st.t_mask[t] = (uint32_t*)cv.take(VADUSA_MAX_TREE_NODES * MASK_WORDS * 4);
     }
     st.staging = (float*)cv.take(biggest * 4);
+    float* un = (float*)cv.take(R * V1 * 4);
+    float* sc = (float*)cv.take(R * V1 * 4);
+    if (uniforms) *uniforms = un;
+    if (scores) *scores = sc;
     if (s) *s = st;
     if (layers) *layers = lw;
     if (draft) *draft = dw;
@@ -317,7 +323,8 @@ extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena
     c->state = 0;
     c->batch = 0;
     c->M = 0;
-    layout(*cfg, c->arena, &c->s, &c->layers, &c->draft, nullptr, &c->staging_floats);
+    layout(*cfg, c->arena, &c->s, &c->layers, &c->draft, nullptr, &c->staging_floats, &c->uniforms, &c->scores);
+    c->sampled = 0;
     if (cfg->dtype) {
         // the step kernel addresses layer l as layer 0 + l * stride: the layout must be that regular
         auto off = [](const void* a, const void* b) { return (const char*)a - (const char*)b; };
@@ -440,9 +447,11 @@ static void gemm(vadusa_ctx* c, const GemmArgs& a) { launch_gemm_simple(a, 0, c-
 
 // bf16 model: run phases [lo, hi) of the step kernel (see k_step.hip)
 static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode, int tau, int lo, int hi,
-                      int seq0, int nseq) {
+                      int seq0, int nseq, float* rank_rows = nullptr) {
     StepParams P;
-    P.D = D; P.s = c->s; P.table = table; P.prefill_mode = prefill_mode; P.tau = tau;
+    P.D = D; P.s = c->s;
+    if (rank_rows) P.s.logits = rank_rows;   // acceptance and continuation rank these rows instead of the logits
+    P.table = table; P.prefill_mode = prefill_mode; P.tau = tau;
     P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent; P.profile = c->profile; P.wide = D.B * D.M >= 256;
     P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq;
     P.lw0 = c->layers[0]; P.dw0 = c->draft[0];
@@ -643,10 +652,18 @@ static void mark_compacted(vadusa_ctx* c, int seq0, int nseq, int n_forced) {
 // Verification; with fuse_compact the compaction of every sequence's chosen path and the
 // draft heads follow in the same launch (bf16 model) or right behind (fp32 model).
 static int verify_impl(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau, const int32_t* draft_override,
-                       bool fuse_compact) {
+                       bool fuse_compact, const vadusa_sampling* sp = nullptr) {
     if (!c) return VADUSA_EINVAL;
     if (c->state != 2) return fail(c, VADUSA_ESTATE, c->state == 3 ? "a verification is still waiting for vadusa_kv_compact" : "prefill first");
     if (tau < 1) return fail(c, VADUSA_EINVAL, "tau must be >= 1 (got %d)", tau);
+    if (sp) {
+        if (!(sp->temperature > 0.f) || !std::isfinite(sp->temperature))
+            return fail(c, VADUSA_EINVAL, "temperature must be positive and finite");
+        if (!(sp->top_p > 0.f)) return fail(c, VADUSA_EINVAL, "top_p must be positive");
+        if (!sp->uniforms) return fail(c, VADUSA_EINVAL, "uniforms is null");
+        if ((size_t)(c->cfg.speech_vocab + 1) * sizeof(float) > 65536)
+            return fail(c, VADUSA_ESHAPE, "stochastic verification keeps one row of V+1 floats in 64 KiB of LDS: vocabulary too large");
+    }
     char msg[256];
     std::vector<int32_t> depth;
     int rc = tree_depths(&c->cfg, tree, &depth, msg, sizeof msg);
@@ -679,15 +696,35 @@ static int verify_impl(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau,
     }
     const Dims D = make_dims(c, B, M);
     c->M = M;
+    c->sampled = sp != nullptr;
+    if (sp) {
+        const size_t bytes = (size_t)B * M * D.V1 * sizeof(float);
+        HIP_TRY(c, hipMemcpyAsync(c->uniforms, sp->uniforms, bytes,
+                                  sp->uniforms_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, c->stream));
+        if (!sp->uniforms_on_device) HIP_TRY(c, hipStreamSynchronize(c->stream));   // the caller's buffer is not kept
+    }
+    // Stochastic rule: the forward stops after the base head, the logits become perturbed scores,
+    // and acceptance, choice and continuation rank the scores in place of the logits.
+    DevState sr = s;
+    if (sp) sr.logits = c->scores;
     if (c->cfg.dtype) {
         const int H = 1 + 5 * D.Ly;
-        rc = run_phases(c, D, 0, 0, tau, 0, fuse_compact ? H + TP_COUNT : H + TP_FINAL, 0, B);
+        const int end = fuse_compact ? H + TP_COUNT : H + TP_FINAL;
+        if (sp) {
+            rc = run_phases(c, D, 0, 0, tau, 0, H + TP_EDGES, 0, B);
+            if (rc) return rc;
+            launch_perturb(s.logits, c->uniforms, c->scores, B * M, D.V1, sp->temperature, sp->top_p, tau, c->stream);
+            rc = run_phases(c, D, 0, 0, tau, H + TP_EDGES, end, 0, B, c->scores);
+        } else {
+            rc = run_phases(c, D, 0, 0, tau, 0, end, 0, B);
+        }
         if (rc) return rc;
     } else {
         forward(c, D, 0, 0, true);
-        launch_accept(D, s, tau, c->cfg.ignore_eos, c->stream);
+        if (sp) launch_perturb(s.logits, c->uniforms, c->scores, B * M, D.V1, sp->temperature, sp->top_p, tau, c->stream);
+        launch_accept(D, sr, tau, c->cfg.ignore_eos, c->stream);
         if (fuse_compact) {
-            launch_finalize(D, s, 0, B, 0, c->cfg.ignore_eos, 0, c->stream);
+            launch_finalize(D, sr, 0, B, 0, c->cfg.ignore_eos, 0, c->stream);
             launch_commit_kv(D, s, 0, B, 0, c->stream);
             draft_heads(c, D, 0, B);
         }
@@ -701,6 +738,13 @@ static int verify_impl(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau,
 
 extern "C" int vadusa_verify(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau, const int32_t* draft_override) {
     return verify_impl(c, tree, tau, draft_override, false);
+}
+
+extern "C" int vadusa_verify_sampled(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau,
+                                     const vadusa_sampling* sampling, const int32_t* draft_override) {
+    if (!c) return VADUSA_EINVAL;
+    if (!sampling) return fail(c, VADUSA_EINVAL, "sampling is null");
+    return verify_impl(c, tree, tau, draft_override, false, sampling);
 }
 
 extern "C" int vadusa_kv_compact(vadusa_ctx* c, int32_t seq, const int32_t* path_nodes, int32_t n) {
@@ -732,10 +776,12 @@ extern "C" int vadusa_kv_compact(vadusa_ctx* c, int32_t seq, const int32_t* path
     }
     if (c->cfg.dtype) {
         const int H = 1 + 5 * D.Ly;
-        int rc = run_phases(c, D, 0, 0, 1, H + TP_FINAL, H + TP_COUNT, seq0, nseq);
+        int rc = run_phases(c, D, 0, 0, 1, H + TP_FINAL, H + TP_COUNT, seq0, nseq, c->sampled ? c->scores : nullptr);
         if (rc) return rc;
     } else {
-        launch_finalize(D, s, seq0, nseq, 0, c->cfg.ignore_eos, 0, c->stream);
+        DevState sr = s;
+        if (c->sampled) sr.logits = c->scores;   // the next root is the first draw at the last committed node
+        launch_finalize(D, sr, seq0, nseq, 0, c->cfg.ignore_eos, 0, c->stream);
         launch_commit_kv(D, s, seq0, nseq, 0, c->stream);
         draft_heads(c, D, seq0, nseq);
         HIP_TRY(c, hipGetLastError());
@@ -744,12 +790,11 @@ extern "C" int vadusa_kv_compact(vadusa_ctx* c, int32_t seq, const int32_t* path
     return VADUSA_OK;
 }
 
-extern "C" int vadusa_step(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau, const int32_t* draft_override,
-                           int32_t* accepted_tok, int32_t* accepted_len) {
-    if (!c) return VADUSA_EINVAL;
+static int step_impl(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau, const vadusa_sampling* sp,
+                     const int32_t* draft_override, int32_t* accepted_tok, int32_t* accepted_len) {
     if ((accepted_tok == nullptr) != (accepted_len == nullptr))
         return fail(c, VADUSA_EINVAL, "accepted_tok and accepted_len must both be given or both be null");
-    int rc = verify_impl(c, tree, tau, draft_override, true);
+    int rc = verify_impl(c, tree, tau, draft_override, true, sp);
     if (rc) return rc;
     if (accepted_tok) {
         const int B = c->batch, W = VADUSA_MAX_DRAFT_HEADS + 1, Hh1 = c->cfg.n_draft_heads + 1;
@@ -767,6 +812,20 @@ extern "C" int vadusa_step(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t 
         }
     }
     return VADUSA_OK;
+}
+
+extern "C" int vadusa_step(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau, const int32_t* draft_override,
+                           int32_t* accepted_tok, int32_t* accepted_len) {
+    if (!c) return VADUSA_EINVAL;
+    return step_impl(c, tree, tau, nullptr, draft_override, accepted_tok, accepted_len);
+}
+
+extern "C" int vadusa_step_sampled(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau,
+                                   const vadusa_sampling* sampling, const int32_t* draft_override,
+                                   int32_t* accepted_tok, int32_t* accepted_len) {
+    if (!c) return VADUSA_EINVAL;
+    if (!sampling) return fail(c, VADUSA_EINVAL, "sampling is null");
+    return step_impl(c, tree, tau, sampling, draft_override, accepted_tok, accepted_len);
 }
 
 extern "C" int vadusa_read_output(vadusa_ctx* c, int32_t seq, int32_t* tok, int32_t capacity, int32_t* n_out) {
@@ -799,6 +858,9 @@ extern "C" int vadusa_debug_read(vadusa_ctx* c, int32_t what, void* host, size_t
     size_t need = 0;
     switch (what) {
     case VADUSA_DBG_LOGITS: src = s.logits; need = B * M * V1 * 4; break;
+    case VADUSA_DBG_SCORES:
+        if (!c->sampled) return fail(c, VADUSA_ESTATE, "the last verification was not a stochastic one");
+        src = c->scores; need = B * M * V1 * 4; break;
     case VADUSA_DBG_TREE_TOK: src = s.tok; need = B * M * 4; break;
     case VADUSA_DBG_DRAFT_TOPK: src = s.draft_topk; need = B * Hh * VADUSA_MAX_TOPK * 4; break;
     case VADUSA_DBG_KV_LEN: src = s.L; need = B * 4; break;

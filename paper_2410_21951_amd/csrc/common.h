@@ -186,6 +186,9 @@ struct vadusa_ctx {
     int n_cus;                   // workgroups of the persistent step kernel (one per compute unit)
     int persistent;              // 0: one launch per phase (debugging aid)
     int profile;                 // 1: the step kernel records timing points (environment VADUSA_PHASE_CLOCK)
+    float* uniforms;             // [max_batch * max_tree_nodes][V+1]: the caller's random numbers of a stochastic step
+    float* scores;               // same shape: perturbed scores that replace the logits in such a step
+    int sampled;                 // the pending / last verification was a stochastic one
     uint32_t epoch;              // grid-barrier epoch reached so far
     std::string err;
 };
@@ -253,6 +256,8 @@ void launch_accept(const Dims& D, const DevState& s, int tau, int ignore_eos, hi
 void launch_commit_kv(const Dims& D, const DevState& s, int seq0, int nseq, int dtype, hipStream_t st);
 void launch_finalize(const Dims& D, const DevState& s, int seq0, int nseq, int prefill_mode, int ignore_eos, int dtype, hipStream_t st);
 void launch_topk(const Dims& D, const DevState& s, int seq0, int nseq, hipStream_t st);
+void launch_perturb(const float* logits, const float* u, float* scores, int rows, int V1, float temperature,
+                    float top_p, int tau, hipStream_t st);
 void launch_convert(const float* src, void* dst, size_t n, int dtype, hipStream_t st);
 void launch_advance(const DevState& s, int B, hipStream_t st);
 void launch_read_kv(const Dims& D, const void* cache_layer, int seq, int which, int pos0, int npos, float* out, int dtype, hipStream_t st);

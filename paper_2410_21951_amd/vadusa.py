@@ -35,8 +35,14 @@ class _Tree(C.Structure):
     _fields_ = [("n_nodes", C.c_int32), ("parent", C.POINTER(C.c_int32)), ("rank", C.POINTER(C.c_int32))]
 
 
+class _Sampling(C.Structure):
+    _fields_ = [("temperature", C.c_float), ("top_p", C.c_float), ("uniforms", C.c_void_p),
+                ("uniforms_on_device", C.c_int32)]
+
+
 class DBG:
-    LOGITS, H_NODES, TREE_TOK, DRAFT_TOPK, KV_LEN, ROOT, EDGE_OK, PATH, FINISHED, DRAFT_LOGITS, PHASE_CLOCK = range(11)
+    (LOGITS, H_NODES, TREE_TOK, DRAFT_TOPK, KV_LEN, ROOT, EDGE_OK, PATH, FINISHED, DRAFT_LOGITS, PHASE_CLOCK,
+     SCORES) = range(12)
 
 
 EXPORTS = {
@@ -54,6 +60,9 @@ EXPORTS = {
     "vadusa_verify": (C.c_int, [C.c_void_p, C.POINTER(_Tree), C.c_int32, C.c_void_p]),
     "vadusa_kv_compact": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32]),
     "vadusa_step": (C.c_int, [C.c_void_p, C.POINTER(_Tree), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "vadusa_verify_sampled": (C.c_int, [C.c_void_p, C.POINTER(_Tree), C.c_int32, C.POINTER(_Sampling), C.c_void_p]),
+    "vadusa_step_sampled": (C.c_int, [C.c_void_p, C.POINTER(_Tree), C.c_int32, C.POINTER(_Sampling), C.c_void_p,
+                                      C.c_void_p, C.c_void_p]),
     "vadusa_read_output": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]),
     "vadusa_debug_read": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t]),
     "vadusa_debug_read_kv": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
@@ -211,9 +220,25 @@ class Vadusa:
                 buf[b, i, :len(ids)] = ids
         return buf
 
-    def verify(self, tree, tau, override=None):
+    def _sampling(self, tree, sample):
+        """sample = (temperature, top_p, uniforms): uniforms a host array [batch][n_nodes][V+1]
+        or a CUDA tensor of that many floats.  Returns (struct, object to keep alive)."""
+        temperature, top_p, u = sample
+        if hasattr(u, "data_ptr"):
+            assert u.is_cuda and u.is_contiguous() and u.numel() == self.batch * tree.n_nodes * self.V1
+            return _Sampling(float(temperature), float(top_p), C.c_void_p(u.data_ptr()), 1), u
+        u = np.ascontiguousarray(u, dtype=np.float32)
+        assert u.size == self.batch * tree.n_nodes * self.V1, "uniforms must be [batch][n_nodes][V+1]"
+        return _Sampling(float(temperature), float(top_p), u.ctypes.data_as(C.c_void_p), 0), u
+
+    def verify(self, tree, tau, override=None, sample=None):
+        """sample = None: deterministic tolerance; (temperature, top_p, uniforms): the stochastic rule."""
         buf = self._override(override)
-        self._check(self.lib.vadusa_verify(self.h, C.byref(tree.c), int(tau), _ptr(buf)))
+        if sample is None:
+            self._check(self.lib.vadusa_verify(self.h, C.byref(tree.c), int(tau), _ptr(buf)))
+        else:
+            sp, keep = self._sampling(tree, sample)
+            self._check(self.lib.vadusa_verify_sampled(self.h, C.byref(tree.c), int(tau), C.byref(sp), _ptr(buf)))
         self.M = tree.n_nodes
 
     def kv_compact(self, seq=-1, path=None):
@@ -223,16 +248,21 @@ class Vadusa:
             p = _i32(path)
             self._check(self.lib.vadusa_kv_compact(self.h, int(seq), _ptr(p), len(p)))
 
-    def step(self, tree, tau, override=None, sync=True):
-        """One speculative step.  sync=True returns a list of accepted-token lists."""
+    def step(self, tree, tau, override=None, sync=True, sample=None):
+        """One speculative step.  sync=True returns a list of accepted-token lists.
+        sample = (temperature, top_p, uniforms) selects the stochastic rule."""
         buf = self._override(override)
         self.M = tree.n_nodes
+        tok = np.zeros((self.batch, self.Hh + 1), np.int32) if sync else None
+        ln = np.zeros(self.batch, np.int32) if sync else None
+        if sample is None:
+            self._check(self.lib.vadusa_step(self.h, C.byref(tree.c), int(tau), _ptr(buf), _ptr(tok), _ptr(ln)))
+        else:
+            sp, keep = self._sampling(tree, sample)
+            self._check(self.lib.vadusa_step_sampled(self.h, C.byref(tree.c), int(tau), C.byref(sp), _ptr(buf),
+                                                     _ptr(tok), _ptr(ln)))
         if not sync:
-            self._check(self.lib.vadusa_step(self.h, C.byref(tree.c), int(tau), _ptr(buf), None, None))
             return None
-        tok = np.zeros((self.batch, self.Hh + 1), np.int32)
-        ln = np.zeros(self.batch, np.int32)
-        self._check(self.lib.vadusa_step(self.h, C.byref(tree.c), int(tau), _ptr(buf), _ptr(tok), _ptr(ln)))
         return [tok[b, :ln[b]].tolist() for b in range(self.batch)]
 
     def read_output(self, seq=0):
@@ -246,7 +276,7 @@ class Vadusa:
     def debug(self, what):
         B, M, Hh, V1, d = self.batch, self.M, self.Hh, self.V1, self.cfg.d_model
         shapes = {
-            DBG.LOGITS: ((B, M, V1), np.float32), DBG.H_NODES: ((B, M, d), np.float32),
+            DBG.LOGITS: ((B, M, V1), np.float32), DBG.SCORES: ((B, M, V1), np.float32), DBG.H_NODES: ((B, M, d), np.float32),
             DBG.TREE_TOK: ((B, M), np.int32), DBG.DRAFT_TOPK: ((B, Hh, MAX_TOPK), np.int32),
             DBG.KV_LEN: ((B,), np.int32), DBG.ROOT: ((B,), np.int32), DBG.EDGE_OK: ((B, M), np.int32),
             DBG.PATH: ((B, Hh + 2), np.int32), DBG.FINISHED: ((B,), np.int32),

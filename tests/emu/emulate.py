@@ -32,6 +32,7 @@ def build(out_dir, extra_flags=()):
         text = open(os.path.join(CSRC, name)).read()
         # dynamic LDS, the one inline-asm wait, and the cooperative launch have host stand-ins
         text = text.replace("extern __shared__ uint4 smem[];", "uint4* smem = (uint4*)emu_dyn_lds;")
+        text = text.replace("extern __shared__ float s_s[];", "float* s_s = (float*)emu_dyn_lds;")
         text = "\n".join(l for l in text.split("\n") if "s_waitcnt" not in l)
         text = re.sub(r"hipLaunchCooperativeKernel\(\(const void\*\)(\w+), (.*), st\);", r"emu_launch_coop(\1, \2);", text)
         dst = os.path.join(gen, name[:-4] + ".cpp" if name.endswith(".hip") else name)

@@ -10,7 +10,7 @@ sys.path.insert(0, os.path.dirname(HERE))
 import emulate
 emulate.install(sys.argv[1])
 import numpy as np
-from synth import ModelConfig, make_weights, make_tree
+from synth import ModelConfig, make_weights, make_tree, make_uniforms
 from parity import Lockstep
 
 dtype = sys.argv[2]
@@ -25,9 +25,13 @@ t0 = time.time()
 ls = Lockstep(cfg, W, text, prompt, 8)
 for tau in (1, 3):
     ls.step(tree, tau)
+# the stochastic rule: every token kept, a nucleus cut, and a nucleus smaller than tau
+for i, (tau, T, top_p) in enumerate(((2, 0.9, 1.0), (3, 1.0, 0.7), (4, 0.5, 0.02))):
+    ls.step(tree, tau, sample=(T, top_p, make_uniforms(73, i, 2, tree.n_nodes, cfg.speech_vocab + 1)))
 ls.check_kv(layers=[0])
 s = ls.stats
-print(f"emulated {dtype}: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e} in {time.time() - t0:.0f} s", flush=True)
+print(f"emulated {dtype}: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e} score err "
+      f"{s.max_score_err:.2e} nucleus sizes {[round(x, 1) for x in s.nucleus_sizes]} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} in {time.time() - t0:.0f} s", flush=True)
 assert s.compared >= 1
 sys.stdout.flush()
 os._exit(0)   # the emulation's worker threads never end

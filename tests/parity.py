@@ -21,6 +21,10 @@ from paper_2410_21951_amd import Vadusa, TreeArrays, DBG
 
 MARGIN = 1e-2
 TOL = {"fp32": 1e-4, "bf16": 1e-2}
+# Stochastic rule: a decision is held to bit-exactness only if the oracle takes the same one with
+# the nucleus bound moved by this much either way (the kept probability mass carries the logits'
+# error) and with a score margin above MARGIN / temperature.
+TOP_P_SLACK = {"fp32": 1e-4, "bf16": 2e-2}
 
 
 def rel_l2(a, b):
@@ -42,6 +46,38 @@ def edge_margin(z, t, tau):
     return float(s[tau - 1] - z[t])
 
 
+def score_variants(logits, sample, tau, slack):
+    """The oracle's perturbed scores for top_p - slack, top_p, top_p + slack (one entry if top_p >= 1)."""
+    T, top_p, u = sample
+    if top_p >= 1.0:
+        return [O.perturbed_scores(logits, u, T, top_p, tau)]
+    return [O.perturbed_scores(logits, u, T, min(max(p, 1e-6), 0.999999), tau) for p in (top_p - slack, top_p, top_p + slack)]
+
+
+def firm_edge(variants, parent, t, tau, margin):
+    """(decision, firm): the oracle's decision for candidate t under its parent's row, and whether
+    every variant takes it with more than `margin` to spare."""
+    ds, ms = [], []
+    kept = [int(np.isfinite(y[parent]).sum()) for y in variants]
+    if min(kept) <= tau:      # the "tau most probable" clause shapes this row: its own near-ties are not modelled
+        z = variants[len(variants) // 2][parent]
+        return int((z > z[t]).sum() + (z[:t] == z[t]).sum()) < tau, False
+    for y in variants:
+        z = y[parent]
+        ds.append(int((z > z[t]).sum() + (z[:t] == z[t]).sum()) < tau)
+        ms.append(edge_margin(z, t, tau))
+    mid = ds[len(ds) // 2]
+    return mid, all(d == mid for d in ds) and min(ms) > margin
+
+
+def firm_top(variants, row, margin):
+    """Margin of the first draw at `row`: 0 if the variants disagree, else the smallest top-2 gap."""
+    tops = [int(O.top_k(y[row], 1)[0]) for y in variants]
+    if any(t != tops[0] for t in tops):
+        return 0.0
+    return min(top_gap(y[row]) for y in variants)
+
+
 @dataclass
 class Stats:
     steps: int = 0
@@ -52,6 +88,8 @@ class Stats:
     max_logit_err: float = 0.0
     max_h_err: float = 0.0
     max_kv_err: float = 0.0
+    max_score_err: float = 0.0
+    nucleus_sizes: list = field(default_factory=list)
     accepted_hist: list = field(default_factory=list)
 
 
@@ -67,6 +105,7 @@ class Lockstep:
         self.dev.load_weights(weights)
         self.stats = Stats()
         self.sts = [O.prefill(self.model, t, p) for t, p in zip(text, prompt)]
+        self.root_gap = {}     # per sequence: margin of the root when it came from a stochastic step
         self.out_base = [0] * self.B
         self.dev.prefill(text, prompt)
         self.check_prefill()
@@ -101,9 +140,11 @@ class Lockstep:
         self.dev.prefill(self.text, prompts)
         self.out_base = [len(st.emitted) for st in self.sts]
 
-    def step(self, tree, tau, override=None):
-        """One lockstep step.  override: per-sequence per-head candidate lists (or None)."""
+    def step(self, tree, tau, override=None, sample=None):
+        """One lockstep step.  override: per-sequence per-head candidate lists (or None).
+        sample: None, or (temperature, top_p, uniforms [B][M][V+1]) for the stochastic rule."""
         cfg, dev, S = self.cfg, self.dev, self.stats
+        margin = MARGIN if sample is None else MARGIN / min(sample[0], 1.0)
         tarr = TreeArrays(tree.parent, tree.rank)
         need = tree.topk_needed(cfg.n_draft_heads)
         S.steps += 1
@@ -123,8 +164,8 @@ class Lockstep:
                 continue
             if roots[b] != st.root:
                 # the root came from the previous last-accepted row: margin on that row
-                gap = top_gap(st.root_logits)
-                assert gap <= MARGIN, f"root mismatch seq {b}: {roots[b]} vs {st.root}, gap {gap}"
+                gap = self.root_gap.get(b, top_gap(st.root_logits))
+                assert gap <= max(MARGIN, margin), f"root mismatch seq {b}: {roots[b]} vs {st.root}, gap {gap}"
                 S.tie_root += 1
                 root_diverged = True
             if override is None:
@@ -139,14 +180,15 @@ class Lockstep:
             roots = dev.debug(DBG.ROOT)
             if any(roots[b] != st.root for b, st in enumerate(self.sts)):
                 # same tie again: this step cannot be compared; advance the oracle and resync after
-                self._oracle_only(tree, tau, o_lists if override is not None else None)
+                self._oracle_only(tree, tau, o_lists if override is not None else None, sample)
                 self.resync()
                 return None
             use_override = True
         # (b) verification
-        dev.verify(tarr, tau, override=o_lists if use_override else None)
+        dev.verify(tarr, tau, override=o_lists if use_override else None, sample=sample)
         tok = dev.debug(DBG.TREE_TOK)
         logits = dev.debug(DBG.LOGITS)
+        scores = dev.debug(DBG.SCORES) if sample is not None else None
         h = dev.debug(DBG.H_NODES)
         edge = dev.debug(DBG.EDGE_OK)
         path = dev.debug(DBG.PATH)
@@ -157,7 +199,8 @@ class Lockstep:
                 assert path[b, 0] == 0
                 results.append(O.step(self.model, st, tree, tau))
                 continue
-            r = O.step(self.model, st, tree, tau, draft_override=o_lists[b], ignore_eos=self.ignore_eos)
+            smp = None if sample is None else (sample[0], sample[1], sample[2][b])
+            r = O.step(self.model, st, tree, tau, draft_override=o_lists[b], ignore_eos=self.ignore_eos, sample=smp)
             results.append(r)
             assert tok[b].tolist() == r["tok"].tolist(), f"tree tokens differ seq {b}"
             for n in range(tree.n_nodes):
@@ -165,15 +208,22 @@ class Lockstep:
                 S.max_logit_err = max(S.max_logit_err, e)
                 assert e < self.tol, f"logits seq {b} node {n}: rel-L2 {e}"
             S.max_h_err = max(S.max_h_err, rel_l2(h[b], r["h"]))
+            variants = None
+            if sample is not None:
+                variants = score_variants(r["logits"], smp, tau, TOP_P_SLACK[cfg.dtype])
+                self.check_scores(b, scores[b], variants, r["logits"], smp, tau)
             # edges
             flipped = False
             for n in range(1, tree.n_nodes):
-                z = r["logits"][tree.parent[n]]
                 t = int(r["tok"][n])
-                want = int((z > z[t]).sum() + (z[:t] == z[t]).sum()) < tau
+                if sample is None:
+                    z = r["logits"][tree.parent[n]]
+                    want = int((z > z[t]).sum() + (z[:t] == z[t]).sum()) < tau
+                    firm = edge_margin(z, t, tau) > MARGIN
+                else:
+                    want, firm = firm_edge(variants, tree.parent[n], t, tau, margin)
                 if bool(edge[b, n]) != want:
-                    mg = edge_margin(z, t, tau)
-                    assert mg <= MARGIN, f"edge decision differs seq {b} node {n}, margin {mg}"
+                    assert not firm, f"edge decision differs seq {b} node {n}"
                     S.tie_edge += 1
                     flipped = True
             got_path = path[b, 1:1 + path[b, 0]].tolist()
@@ -182,6 +232,10 @@ class Lockstep:
             elif got_path != r["path"]:
                 forced[b] = r["path"]
             S.accepted_hist.append(len(r["path"]))
+            if sample is not None:
+                self.root_gap[b] = firm_top(variants, r["path"][-1], margin)
+            else:
+                self.root_gap.pop(b, None)
         # (c) compaction (forced to the oracle's path where a tie flipped an edge)
         if forced:
             for b in range(self.B):
@@ -199,10 +253,41 @@ class Lockstep:
         S.compared += 1
         return results
 
-    def _oracle_only(self, tree, tau, o_lists):
+    def _oracle_only(self, tree, tau, o_lists, sample=None):
         for b, st in enumerate(self.sts):
-            O.step(self.model, st, tree, tau, draft_override=None if o_lists is None else o_lists[b],
-                   ignore_eos=self.ignore_eos)
+            smp = None if sample is None else (sample[0], sample[1], sample[2][b])
+            r = O.step(self.model, st, tree, tau, draft_override=None if o_lists is None else o_lists[b],
+                       ignore_eos=self.ignore_eos, sample=smp)
+            if sample is not None and r["path"]:
+                variants = score_variants(r["logits"], smp, tau, TOP_P_SLACK[self.cfg.dtype])
+                self.root_gap[b] = firm_top(variants, r["path"][-1], MARGIN / min(sample[0], 1.0))
+            else:
+                self.root_gap.pop(b, None)
+
+    def check_scores(self, b, got, variants, logits, sample, tau):
+        """The library's perturbed scores against the oracle's: a token that every variant of the
+        nucleus bound keeps (drops) must be kept (dropped), and the kept values must agree.
+        Tokens whose scaled logit lies within the margin of the tau-th / (tau+1)-th largest are
+        exempt: the "tau most probable" clause may go either way for them."""
+        T = sample[0]
+        mid = variants[len(variants) // 2]
+        firm_in = np.all([np.isfinite(y) for y in variants], axis=0)
+        firm_out = np.all([np.isinf(y) for y in variants], axis=0)
+        sc = np.asarray(logits) / T
+        srt = -np.sort(-sc, axis=1)
+        V1 = sc.shape[1]
+        m = MARGIN / min(T, 1.0)
+        lo = srt[:, min(tau, V1 - 1)] - m
+        hi = srt[:, min(tau, V1) - 1] + m
+        fragile = (sc >= lo[:, None]) & (sc <= hi[:, None])
+        g = np.isfinite(got)
+        bad = ((firm_in & ~g) | (firm_out & g)) & ~fragile
+        assert not bad.any(), f"nucleus differs seq {b}: nodes {np.unique(np.nonzero(bad)[0]).tolist()}"
+        self.stats.nucleus_sizes.append(float(np.isfinite(mid).sum(axis=1).mean()))
+        both = g & np.isfinite(mid)
+        e = rel_l2(got[both], mid[both])
+        self.stats.max_score_err = max(self.stats.max_score_err, e)
+        assert e < self.tol, f"scores seq {b}: rel-L2 {e}"
 
 
 def sampled_check(cfg, weights, text, prompt, tree, tau, sample, kv_layers=(0,)):

@@ -123,3 +123,52 @@ def test_step_equals_verify_plus_compact_and_async_and_reproducible():
     for l in logits[1:]:
         assert np.array_equal(logits[0], l)             # bit-reproducible
     assert all(len(o) >= 12 for o in outs[0])
+
+
+def test_stochastic_entry_points():
+    """vadusa_step_sampled = vadusa_verify_sampled + vadusa_kv_compact; uniforms from host or
+    device memory give the same stream; argument errors are reported, not run."""
+    import ctypes as C
+    import torch
+    from paper_2410_21951_amd import DBG, VadusaError
+    from paper_2410_21951_amd.vadusa import _Sampling
+    from synth import make_uniforms
+    print("stochastic entry points", flush=True)
+    W = make_weights(CFG, 4, std=0.08)
+    rng = np.random.default_rng(6)
+    text, prompt = _inputs(rng)
+    tree = _tree(make_tree(16, (4, 2, 2)))
+    outs = []
+    for mode in ("step", "split", "device"):
+        dev = _dev(max_batch=2, max_tree_nodes=16, ignore_eos=True)
+        dev.load_weights(W)
+        dev.prefill(text, prompt)
+        for i in range(8):
+            u = make_uniforms(9, i, 2, 16, CFG.n_logits)
+            smp = (0.9, 0.9, u)
+            if mode == "step":
+                dev.step(tree, 1 + 5 * (i % 3), sample=smp)
+            elif mode == "split":
+                dev.verify(tree, 1 + 5 * (i % 3), sample=smp)
+                dev.kv_compact(-1)
+            else:
+                dev.step(tree, 1 + 5 * (i % 3), sample=(0.9, 0.9, torch.from_numpy(u).cuda()), sync=False)
+        outs.append([dev.read_output(b).tolist() for b in range(2)])
+        if mode == "step":
+            sc = dev.debug(DBG.SCORES)
+            assert np.isfinite(sc).any() and np.isinf(sc).any()
+            # errors: nothing runs, the context stays usable
+            u = make_uniforms(9, 99, 2, 16, CFG.n_logits)
+            for bad in ((0.0, 0.9), (-1.0, 0.9), (float("nan"), 0.9), (1.0, 0.0), (1.0, -0.5)):
+                with pytest.raises(VadusaError) as e:
+                    dev.step(tree, 1, sample=(bad[0], bad[1], u))
+                assert e.value.code != 0
+            sp = _Sampling(1.0, 1.0, None, 0)
+            assert dev.lib.vadusa_step_sampled(dev.h, C.byref(tree.c), 1, C.byref(sp), None, None, None) != 0
+            assert dev.lib.vadusa_step_sampled(dev.h, C.byref(tree.c), 1, None, None, None, None) != 0
+            dev.step(tree, 1)                       # a deterministic step: no scores to read afterwards
+            with pytest.raises(VadusaError):
+                dev.debug(DBG.SCORES)
+        dev.close()
+    assert outs[0] == outs[1] == outs[2]
+    assert all(len(o) >= 8 for o in outs[0])

@@ -336,3 +336,50 @@ def test_smallest_width_bf16():
     s = ls.stats
     _say(f"d=64 bf16: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e}")
     assert s.compared >= 2
+
+
+SAMPLING_MIX = ((1, 1.0, 1.0), (4, 0.9, 0.9), (32, 1.0, 0.6), (100, 0.9, 1.0), (8, 0.5, 0.05), (2, 1.0, 0.95))
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_stochastic_rule_small_models(dtype):
+    """Algorithm 1 with sampling (temperature, nucleus, tau draws from the caller's uniforms):
+    every temperature / top_p / tau regime, batch of two, paths of several lengths."""
+    from synth import make_uniforms
+    cfg = small_cfg(dtype)
+    _say(f"stochastic rule {dtype}")
+    W = make_weights(cfg, 15, std=STD[dtype], ln_jitter=0.1)
+    rng = np.random.default_rng(41)
+    text, prompt = rand_tokens(cfg, rng, 2, (5, 9), (17, 30))
+    tree = make_tree(24, (3, 3, 2), alpha0=0.9, decay=1.0)
+    ls = _lock(cfg, W, text, prompt, 24)
+    for i in range(12):
+        tau, T, top_p = SAMPLING_MIX[i % len(SAMPLING_MIX)]
+        ls.step(tree, tau, sample=(T, top_p, make_uniforms(77, i, 2, tree.n_nodes, cfg.n_logits)))
+    ls.step(tree, 2)                      # a deterministic step after stochastic ones
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    _say(f"  compared {s.compared}/{s.steps} accepted lengths {np.bincount(s.accepted_hist).tolist()} "
+         f"ties {s.tie_root}/{s.tie_list}/{s.tie_edge} logit err {s.max_logit_err:.2e} score err {s.max_score_err:.2e} "
+         f"mean kept {[round(x) for x in s.nucleus_sizes[:12:2]]}")
+    assert s.compared >= 10
+    assert max(s.accepted_hist) >= 3 and min(s.accepted_hist) == 1
+    assert min(s.nucleus_sizes) < 16 and max(s.nucleus_sizes) == cfg.n_logits
+
+
+def test_valle_b1_stochastic_steps(valle):
+    """The stochastic rule at configuration 2's full size, in the launch shape the benchmark times."""
+    from synth import make_uniforms
+    wl, W = valle
+    text, prompt = make_tokens(wl)
+    tree = make_tree(wl.tree_nodes, wl.topk_caps)
+    _say("valle_b1 stochastic")
+    ls = _lock(wl.model, W, text, prompt, wl.tree_nodes)
+    for i, (tau, T, top_p) in enumerate(((1, 0.9, 0.9), (8, 1.0, 1.0), (64, 0.9, 0.95))):
+        ls.step(tree, tau, sample=(T, top_p, make_uniforms(78, i, 1, tree.n_nodes, wl.model.n_logits)))
+        _say(f"  step {i} tau {tau} T {T} top_p {top_p}: kept {ls.stats.nucleus_sizes[-1]:.0f} score err {ls.stats.max_score_err:.2e}")
+    ls.check_kv(layers=[0, 11])
+    s = ls.stats
+    _say(f"  compared {s.compared}/{s.steps} accepted lengths {np.bincount(s.accepted_hist).tolist()} "
+         f"ties {s.tie_root}/{s.tie_list}/{s.tie_edge}")
+    assert s.compared >= 2
