@@ -334,7 +334,10 @@ __device__ inline void dev_commit_kv(const Dims& D, const DevState& s, int layer
 // after the last of them, T.  Every entry not after T is a candidate (a few dozen for random
 // logits); each candidate counts the candidates before it, which is its place in the list.
 // More than 256 candidates (many equal or missing values), or more than 4096 logits: the
-// list is built one entry per round by re-scanning (block_argbest).
+// list is built one entry per round by re-scanning (block_argbest); with SLICED, rows of up to
+// 65536 logits first try the candidate scheme slice by slice (used by the stand-alone top-k
+// kernel, which serves large vocabularies).
+template <bool SLICED = false>
 __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) {
     __shared__ float c_v[256];
     __shared__ int c_i[256];
@@ -345,7 +348,75 @@ __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) 
     int32_t* out = s.draft_topk + ((size_t)b * D.Hh + i) * VADUSA_MAX_TOPK;
     const int kmax = D.V1 < VADUSA_MAX_TOPK ? D.V1 : VADUSA_MAX_TOPK;
     bool rescan = D.V1 > 256 * 16;
-    if (!rescan) {
+    if constexpr (SLICED) {
+        if (rescan) {
+            // More than 4096 logits: the same scheme over slices of 4096.  First pass: the 16 group
+            // maxima of every slice go to LDS (at most 256 of them: V1 <= 65536) and T is the 16th
+            // best of these, again an entry of the row with at least 15 others before it.  Second
+            // pass: every entry not after T is a candidate.
+            const int nsl = (D.V1 + 4095) / 4096;
+            if (nsl <= 16) {
+                for (int sl = 0; sl < nsl; ++sl) {
+                    float lv = -INFINITY;
+                    int li = 0x7fffffff;
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const int v = sl * 4096 + (int)threadIdx.x + 256 * j;
+                        const float zv = v < D.V1 ? ldg(z + v) : -INFINITY;
+                        if (v < D.V1 && before(zv, v, lv, li)) { lv = zv; li = v; }
+                    }
+#pragma unroll
+                    for (int o = 1; o < 16; o <<= 1) {
+                        const float ov = __shfl_xor(lv, o, 64);
+                        const int oi = __shfl_xor(li, o, 64);
+                        if (before(ov, oi, lv, li)) { lv = ov; li = oi; }
+                    }
+                    if ((threadIdx.x & 15) == 0) { c_v[sl * 16 + (threadIdx.x >> 4)] = lv; c_i[sl * 16 + (threadIdx.x >> 4)] = li; }
+                }
+                if (threadIdx.x == 0) c_n = 0;
+                __syncthreads();
+                // thread t ranks maximum t among the nsl * 16 maxima; the one 15 are before is T
+                // (a slice tail without entries leaves (-inf, 0x7fffffff), which ranks last)
+                const int nm = nsl * 16;
+                if ((int)threadIdx.x < nm) {
+                    const float mv = c_v[threadIdx.x];
+                    const int mi = c_i[threadIdx.x];
+                    int r = 0;
+                    for (int t = 0; t < nm; ++t) r += before(c_v[t], c_i[t], mv, mi) ? 1 : 0;
+                    if (r == 15) { g_v[0] = mv; g_i[0] = mi; }
+                }
+                __syncthreads();
+                const float tv = g_v[0];
+                const int ti = g_i[0];
+                __syncthreads();   // every thread holds T: the candidate list may overwrite the maxima
+                for (int sl = 0; sl < nsl; ++sl) {
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const int v = sl * 4096 + (int)threadIdx.x + 256 * j;
+                        const float zv = v < D.V1 ? ldg(z + v) : -INFINITY;
+                        if (v < D.V1 && !before(tv, ti, zv, v)) {
+                            const int slot = atomicAdd(&c_n, 1);
+                            if (slot < 256) { c_v[slot] = zv; c_i[slot] = v; }
+                        }
+                    }
+                }
+                __syncthreads();
+                const int n = c_n;
+                if (n <= 256) {
+                    rescan = false;
+                    if ((int)threadIdx.x < n) {
+                        const float mv = c_v[threadIdx.x];
+                        const int mi = c_i[threadIdx.x];
+                        int r = 0;
+                        for (int t = 0; t < n; ++t) r += before(c_v[t], c_i[t], mv, mi) ? 1 : 0;
+                        if (r < kmax) stwi(out + r, mi);
+                    }
+                }
+                __syncthreads();
+            }
+        }
+    }
+    if (D.V1 <= 256 * 16) {
         float zr[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {

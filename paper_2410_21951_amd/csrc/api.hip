@@ -448,6 +448,11 @@ static void gemm(vadusa_ctx* c, const GemmArgs& a) { launch_gemm_simple(a, 0, c-
 // bf16 model: run phases [lo, hi) of the step kernel (see k_step.hip)
 static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode, int tau, int lo, int hi,
                       int seq0, int nseq, float* rank_rows = nullptr) {
+    // Rows of more than 4096 logits: the draft lists come from the stand-alone top-k kernel (it
+    // handles such rows slice by slice; the step kernel's own top-k phase would re-scan the row
+    // once per list entry)
+    const bool topk_apart = D.V1 > 4096 && hi == 1 + 5 * D.Ly + TP_COUNT;
+    if (topk_apart) --hi;
     StepParams P;
     P.D = D; P.s = c->s;
     if (rank_rows) P.s.logits = rank_rows;   // acceptance and continuation rank these rows instead of the logits
@@ -461,6 +466,7 @@ static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode,
     launch_step(P, c->n_cus, c->stream, &e);
     if (e != hipSuccess) return fail(c, VADUSA_EHIP, "step kernel launch failed: %s", hipGetErrorString(e));
     if (c->persistent) c->epoch += (uint32_t)(hi - lo - 1);
+    if (topk_apart) launch_topk(D, c->s, seq0, nseq, c->stream);
     return VADUSA_OK;
 }
 

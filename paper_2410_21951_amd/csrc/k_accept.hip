@@ -30,7 +30,7 @@ void launch_commit_kv(const Dims& D, const DevState& s, int seq0, int nseq, int 
 }
 
 __global__ __launch_bounds__(256) void k_topk(Dims D, DevState s, int seq0) {
-    dev_topk(D, s, blockIdx.x, seq0 + blockIdx.y);
+    dev_topk<true>(D, s, blockIdx.x, seq0 + blockIdx.y);
 }
 void launch_topk(const Dims& D, const DevState& s, int seq0, int nseq, hipStream_t st) {
     hipLaunchKernelGGL(k_topk, dim3(D.Hh, nseq), dim3(256), 0, st, D, s, seq0);

@@ -80,6 +80,12 @@ PRESETS = {
         name="throughput_b64", model=_vall_e(1024, 4, 1200),
         batch=64, text_len=(64, 64), prompt_len=(225, 225), n_generate=750,
         tree_nodes=32, topk_caps=(10, 10, 10, 10), taus=(1, 2, 4, 8)),
+    # beyond the five configurations: configuration 2 with a 16k-entry speech vocabulary (the
+    # vocabulary map and every draft head's second map grow to 32.8 MB, top-k over 16001 logits)
+    "vocab16k_b1": Workload(
+        name="vocab16k_b1", model=_vall_e(16000, 4, 1280),
+        batch=1, text_len=(64, 64), prompt_len=(225, 225), n_generate=750,
+        tree_nodes=64, topk_caps=(10, 10, 10, 10), taus=(1, 4)),
 }
 
 

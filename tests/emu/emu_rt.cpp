@@ -50,7 +50,10 @@ struct Barrier {
         const uint64_t g = gen;
         if (++count >= n) { count = 0; ++gen; cv.notify_all(); return; }
         if (what[0] == 's' && what[1] == 't') { cv.wait(lk, [&] { return gen != g; }); return; }   // idle pool
-        if (!cv.wait_for(lk, std::chrono::seconds(60), [&] { return gen != g; })) {
+        // a wait that outlasts the limit is taken for a deadlock; the end-of-launch wait of a large
+        // case legitimately takes long (EMU_WAIT_SECONDS raises the limit)
+        static const int limit = getenv("EMU_WAIT_SECONDS") ? atoi(getenv("EMU_WAIT_SECONDS")) : 60;
+        if (!cv.wait_for(lk, std::chrono::seconds(limit), [&] { return gen != g; })) {
             fprintf(stderr, "[emu] barrier '%s' timed out: %d of %d arrived (thread %d)\n", what, count, n, t_id);
             dump_all("deadlock");
             abort();

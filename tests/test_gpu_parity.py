@@ -383,3 +383,26 @@ def test_valle_b1_stochastic_steps(valle):
     _say(f"  compared {s.compared}/{s.steps} accepted lengths {np.bincount(s.accepted_hist).tolist()} "
          f"ties {s.tie_root}/{s.tie_list}/{s.tie_edge}")
     assert s.compared >= 2
+
+
+def test_large_vocabulary_16k():
+    """A 16 000-entry speech vocabulary (16 001 logits per row: the draft lists come from the
+    re-scanning top-k, the stochastic rule holds a whole row in LDS) on a 3-layer d = 1024 model."""
+    from synth import make_uniforms
+    m = PRESETS["vocab16k_b1"].model
+    cfg = dataclasses.replace(m, n_layers=3, max_positions=512)
+    _say("vocabulary 16k")
+    W = make_weights(cfg, 19)
+    rng = np.random.default_rng(45)
+    text, prompt = rand_tokens(cfg, rng, 1, (32, 32), (100, 100))
+    tree = make_tree(64, (10,) * 4)
+    ls = _lock(cfg, W, text, prompt, 64)
+    for i, tau in enumerate((1, 4, 64)):
+        ls.step(tree, tau)
+    ls.step(tree, 16, sample=(0.9, 0.9, make_uniforms(79, 0, 1, 64, cfg.n_logits)))
+    ls.step(tree, 2, sample=(1.0, 1.0, make_uniforms(79, 1, 1, 64, cfg.n_logits)))
+    ls.check_kv(layers=[0, 2])
+    s = ls.stats
+    _say(f"  compared {s.compared}/{s.steps} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} logit err {s.max_logit_err:.2e} "
+         f"score err {s.max_score_err:.2e} kept {[round(x) for x in s.nucleus_sizes]}")
+    assert s.compared >= 4
