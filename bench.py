@@ -91,6 +91,10 @@ def main():
     ap.add_argument("--workload", default="valle_b1")
     ap.add_argument("--tau", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-timed", action="store_true",
+                    help="run the warm-up and the timed steps only (no by-length pass, AR / stochastic / dial legs, "
+                         "no CPU baseline): every k_step launch of the run is then a step of the workload or a "
+                         "prefill chunk, which is what a per-kernel profile should average over")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain copy kernel of known size (256 MiB read + 256 MiB written, 8 launches): "
                          "under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` its counters give the scale of the HBM byte counters")
@@ -149,7 +153,7 @@ def main():
     # the same step binned by committed length (untimed for the headline figure): five equal
     # slices of one generation, each timed with its own pair of events
     by_L = []
-    if a.steps >= 50:
+    if a.steps >= 50 and not a.only_timed:
         dev.prefill(text, prompt)
         nb = 5
         per = min(seg, a.steps) // nb
@@ -194,6 +198,10 @@ def main():
                       "algorithmic_flops_per_launch": nflops, "hbm_gbs": achieved}),
         "by_committed_length": by_L,
     }
+    if a.only_timed:
+        dev.close()
+        print(json.dumps(out))
+        return
     # Plain auto-regressive decoding through the same kernels: a "tree" of the root alone, one
     # token per step.  speedup = accepted tokens per step x t_AR / t_tree (Sec. 4.1's metric); the
     # accepted length is a property of trained draft heads, so the line quotes what the paper's

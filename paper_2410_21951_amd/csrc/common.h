@@ -106,6 +106,31 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// The same sums without LDS traffic: DPP lane permutations inside each row of 16 lanes (swap
+// with the quad neighbour, the other pair of the quad, the mirrored half row, the mirrored row:
+// after each step twice as many lanes hold the same partial sum), then the four row sums are
+// read from lanes 0, 16, 32 and 48.  Every lane returns the total; all 64 lanes must be active.
+template <int CTRL>
+__device__ __forceinline__ int dpp_perm(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false); }
+__device__ __forceinline__ int wave_sum_i_dpp(int v) {
+    v += dpp_perm<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_perm<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_perm<0x141>(v);   // row_half_mirror
+    v += dpp_perm<0x140>(v);   // row_mirror
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
+           __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
+}
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+    v += __int_as_float(dpp_perm<0xB1>(__float_as_int(v)));
+    v += __int_as_float(dpp_perm<0x4E>(__float_as_int(v)));
+    v += __int_as_float(dpp_perm<0x141>(__float_as_int(v)));
+    v += __int_as_float(dpp_perm<0x140>(__float_as_int(v)));
+    return (__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0)) +
+            __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16))) +
+           (__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32)) +
+            __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48)));
+}
+
 // Shapes that every kernel needs (passed by value).
 struct Dims {
     int Ly, d, nH, F, V1, Hh, maxpos, Bmax, Mmax;   // model / capacity

@@ -15,15 +15,16 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 }
 
 // One workgroup of 256 threads per row; the scaled row sits in LDS (V1 floats).
-// The kept set is {v : s_v >= s*}; s* is found by bisection over the 32-bit keys of the
-// predicate "the tokens above this key hold less than top_p, or are fewer than tau", which is
-// monotone in the key and changes only at values that occur in the row.
+// The kept set is {v : s_v >= s*}; s* is found by a 16-way interval search over the 32-bit keys
+// of the predicate "the tokens above this key hold less than top_p, or are fewer than tau",
+// which is monotone in the key and changes only at values that occur in the row.
 __global__ __launch_bounds__(256) void k_perturb(const float* __restrict__ logits, const float* __restrict__ u,
                                                  float* __restrict__ scores, int V1, float temperature,
                                                  float top_p, int tau) {
     extern __shared__ float s_s[];
-    __shared__ float s_f[2][4];
-    __shared__ int s_i[2][4];
+    constexpr int NT = 15;
+    __shared__ float s_f[2][4][NT + 1];
+    __shared__ int s_i[2][4][NT + 1];
     const size_t row = blockIdx.x;
     const float* z = logits + row * V1;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -34,33 +35,64 @@ __global__ __launch_bounds__(256) void k_perturb(const float* __restrict__ logit
         m = fmaxf(m, s);
     }
     m = wave_max(m);
-    if (lane == 0) s_f[0][wave] = m;
+    if (lane == 0) s_f[0][wave][0] = m;
     __syncthreads();
-    m = fmaxf(fmaxf(s_f[0][0], s_f[0][1]), fmaxf(s_f[0][2], s_f[0][3]));
+    m = fmaxf(fmaxf(s_f[0][0][0], s_f[0][1][0]), fmaxf(s_f[0][2][0], s_f[0][3][0]));
     uint32_t kmin = 0;   // keep everything
     if (top_p < 1.f) {
         float zsum = 0.f;
         for (int v = tid; v < V1; v += 256) zsum += expf(s_s[v] - m);
         zsum = wave_sum(zsum);
-        if (lane == 0) s_f[1][wave] = zsum;
+        if (lane == 0) s_f[1][wave][0] = zsum;
         __syncthreads();
-        const float target = top_p * (s_f[1][0] + s_f[1][1] + s_f[1][2] + s_f[1][3]);
-        uint32_t lo = 0, hi = 0xffffffffu;   // the predicate holds at hi (nothing lies above it)
-        for (int it = 0; it < 32; ++it) {    // every thread sees the same sums: uniform control flow
-            const uint32_t mid = lo + ((hi - lo) >> 1);
-            float a = 0.f;
-            int cnt = 0;
+        const float target = top_p * (s_f[1][0][0] + s_f[1][1][0] + s_f[1][2][0] + s_f[1][3][0]);
+        // Search for the smallest key at which the predicate holds.  It holds at hi (nothing lies
+        // above the largest key) and is monotone; each round tries NT keys that cut [lo, hi] into
+        // NT + 1 parts (their NT pairs of sums are reduced side by side, which costs little more
+        // than one pair), so the interval shrinks 16-fold per round.  Every thread sees the same
+        // sums, hence the same lo and hi: uniform control flow.
+        uint32_t lo = 0, hi = 0xffffffffu;
+        for (int it = 0; lo < hi; ++it) {
+            const uint64_t span = (uint64_t)hi - lo;
+            uint32_t mid[NT];
+            float a[NT];
+            int cnt[NT];
+#pragma unroll
+            for (int q = 0; q < NT; ++q) {
+                mid[q] = lo + (uint32_t)((span * (uint64_t)(q + 1)) / (NT + 1));   // lo <= mid[q] < hi, non-decreasing
+                a[q] = 0.f;
+                cnt[q] = 0;
+            }
             for (int v = tid; v < V1; v += 256) {
                 const float s = s_s[v];
-                if (order_key(s) > mid) { a += expf(s - m); ++cnt; }
+                const float e = expf(s - m);
+                const uint32_t k = order_key(s);
+#pragma unroll
+                for (int q = 0; q < NT; ++q)
+                    if (k > mid[q]) { a[q] += e; ++cnt[q]; }
             }
-            a = wave_sum(a);
-            cnt = wave_sum_i(cnt);
-            if (lane == 0) { s_f[it & 1][wave] = a; s_i[it & 1][wave] = cnt; }
+#pragma unroll
+            for (int q = 0; q < NT; ++q) { a[q] = wave_sum_dpp(a[q]); cnt[q] = wave_sum_i_dpp(cnt[q]); }
+            if (lane == 0) {
+#pragma unroll
+                for (int q = 0; q < NT; ++q) { s_f[it & 1][wave][q] = a[q]; s_i[it & 1][wave][q] = cnt[q]; }
+            }
             __syncthreads();
-            const float A = s_f[it & 1][0] + s_f[it & 1][1] + s_f[it & 1][2] + s_f[it & 1][3];
-            const int C = s_i[it & 1][0] + s_i[it & 1][1] + s_i[it & 1][2] + s_i[it & 1][3];
-            if (A < target || C < tau) hi = mid; else lo = mid + 1;
+            // the first key of the round at which the predicate holds bounds the answer from above,
+            // the key before it (where it fails) from below
+            uint32_t nlo = lo, nhi = hi;
+            bool found = false;
+#pragma unroll
+            for (int q = 0; q < NT; ++q) {
+                const float A = s_f[it & 1][0][q] + s_f[it & 1][1][q] + s_f[it & 1][2][q] + s_f[it & 1][3][q];
+                const int C = s_i[it & 1][0][q] + s_i[it & 1][1][q] + s_i[it & 1][2][q] + s_i[it & 1][3][q];
+                const bool holds = A < target || C < tau;
+                if (!found) {
+                    if (holds) { nhi = mid[q]; found = true; }
+                    else nlo = mid[q] + 1;
+                }
+            }
+            lo = nlo; hi = nhi;
         }
         kmin = hi;
     }

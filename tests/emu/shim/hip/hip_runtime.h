@@ -127,10 +127,27 @@ template <class T> static inline T emu_atomic_load(const T* p) { T v; __atomic_l
 static inline int atomicAdd(int* p, int v) { return __atomic_fetch_add(p, v, __ATOMIC_SEQ_CST); }
 
 #define __builtin_amdgcn_readfirstlane(x) (x)
+// every lane reads lane l of its wave
+#define __builtin_amdgcn_readlane(v, l) (EMU_MARK, (int)emu_shfl_idx32((uint32_t)(v), (l)))
+// DPP lane permutations used by the kernels (all lanes active, full row and bank masks):
+// quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror
+static inline int emu_dpp_src(int lane, int ctrl) {
+    switch (ctrl) {
+    case 0xB1: return lane ^ 1;
+    case 0x4E: return lane ^ 2;
+    case 0x141: return (lane & ~7) | (7 - (lane & 7));
+    case 0x140: return (lane & ~15) | (15 - (lane & 15));
+    default: __builtin_trap();
+    }
+}
+#define __builtin_amdgcn_update_dpp(old, v, ctrl, rm, bm, bc) \
+    (EMU_MARK, (int)emu_shfl_idx32((uint32_t)(v), emu_dpp_src((int)(threadIdx.x & 63), (ctrl))))
 
 // ---- math / bits ----
 static inline float __uint_as_float(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
 static inline uint32_t __float_as_uint(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+static inline float __int_as_float(int u) { float f; memcpy(&f, &u, 4); return f; }
+static inline int __float_as_int(float f) { int u; memcpy(&u, &f, 4); return u; }
 #define __expf(x) expf(x)
 static inline float rsqrtf(float x) { return 1.0f / sqrtf(x); }
 static inline int min(int a, int b) { return a < b ? a : b; }
