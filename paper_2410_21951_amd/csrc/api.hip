@@ -348,6 +348,7 @@ extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena
     c->epoch = 0;
     c->persistent = getenv("VADUSA_PHASE_LAUNCHES") ? 0 : 1;
     c->profile = getenv("VADUSA_PHASE_CLOCK") ? 1 : 0;
+    c->big_min = getenv("VADUSA_BIG_MIN_UNITS") ? std::max(1, atoi(getenv("VADUSA_BIG_MIN_UNITS"))) : 256;
     {
         int dev = 0;
         hipDeviceProp_t prop;
@@ -458,7 +459,7 @@ static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode,
     if (rank_rows) P.s.logits = rank_rows;   // acceptance and continuation rank these rows instead of the logits
     P.table = table; P.prefill_mode = prefill_mode; P.tau = tau;
     P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent; P.profile = c->profile; P.wide = D.B * D.M >= 256;
-    P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq;
+    P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq; P.big_min = c->big_min;
     P.lw0 = c->layers[0]; P.dw0 = c->draft[0];
     P.lw_stride = c->layers.size() > 1 ? (size_t)((const char*)c->layers[1].Wqkv - (const char*)c->layers[0].Wqkv) : 0;
     P.dw_stride = c->draft.size() > 1 ? (size_t)((const char*)c->draft[1].W1 - (const char*)c->draft[0].W1) : 0;

@@ -88,7 +88,17 @@ __device__ __forceinline__ float ldcf(const float* p) {
 __device__ __forceinline__ size_t toff(int r, int k, int nks) {
     return ((size_t)((r >> 4) * nks + (k >> 5)) * 64 + (r & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
 }
+// Two floats to a pair of bf16 (round to nearest even): one v_cvt_pk_bf16_f32 on the device.
+#if defined(__HIP_DEVICE_COMPILE__)
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2_cvt;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_cvt;
+    const f32x2_cvt v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_cvt));
+}
+#else
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) { return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16); }
+#endif
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -214,6 +224,7 @@ struct vadusa_ctx {
     float* uniforms;             // [max_batch * max_tree_nodes][V+1]: the caller's random numbers of a stochastic step
     float* scores;               // same shape: perturbed scores that replace the logits in such a step
     int sampled;                 // the pending / last verification was a stochastic one
+    int big_min;                 // StepParams::big_min (256 = one unit per compute unit; environment VADUSA_BIG_MIN_UNITS, for tests of small shapes)
     uint32_t epoch;              // grid-barrier epoch reached so far
     std::string err;
 };
@@ -261,6 +272,7 @@ struct StepParams {
     LayerW lw0;
     DraftW dw0;
     size_t lw_stride, dw_stride;
+    int big_min;        // many-row kernel: a map takes 128 x 128 units if it has at least this many of them
 };
 // Phases of the step kernel after the decoder layers, as offsets from H = 1 + 5 * n_layers.
 enum { TP_HEAD = 0, TP_EDGES, TP_SELECT, TP_FINAL, TP_COMMIT, TP_DRAFT2, TP_TOPK, TP_COUNT };

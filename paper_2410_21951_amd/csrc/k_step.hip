@@ -34,6 +34,7 @@
 #include <algorithm>
 #include <cstdlib>
 
+#include <type_traits>
 #include "accept_dev.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -60,6 +61,7 @@ struct GemmD {
     float* stats_out;     // SE_RESID
     int layer;
     int ph;               // phase index (timing points only)
+    int G;                // 64-row-kernel units only: column tiles per unit (4: 64 x 64 unit; 8: 128 x 128 unit)
 };
 
 // The kernel's parameters, copied once per workgroup from the kernel-argument segment (which
@@ -80,13 +82,18 @@ __host__ __device__ inline int pad8(int a) { return (a + 7) & ~7; }
 
 int step_num_phases(int n_layers) { return 1 + 5 * n_layers + TP_COUNT; }
 
+// Maps of the many-row kernel large enough to give every compute unit a 128 x 128 output unit
+// (StepParams::big_min of them) take those (operands staged through LDS and shared by the four waves); smaller ones keep
+// the 64 x 64 units whose waves split the reduction.
+__host__ __device__ inline bool wide_big(int R, int N, int min_units) { return cdiv(R, 128) * cdiv(N, 128) >= min_units; }
 __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     const Dims& D = P.D;
     const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
     if (ph == 0) return R;
     if (P.wide && ph >= 1 && ph <= H && (ph == H || (ph - 1) % 5 != 1)) {
-        // 64 x 64 output tiles: groups of four column tiles
+        // 64 x 64 output tiles: groups of four column tiles; 128 x 128: groups of eight
         const int N = ph == H ? D.V1 : (ph - 1) % 5 == 0 ? 3 * D.d : (ph - 1) % 5 == 3 ? D.F : D.d;
+        if (wide_big(R, N, P.big_min)) return pad8(cdiv(cdiv(N, 16), 8)) * cdiv(R, 128);
         return pad8(cdiv(cdiv(N, 16), 4)) * RG;
     }
     if (ph < H) {
@@ -239,11 +246,14 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
     int rb = 0;
     nt = 0; row0 = 0;
     const bool wide = WIDE && ph <= H;   // the draft maps have only B rows: always narrow
+    g.G = 4;
+    int wrows = 64;   // rows per unit of the many-row kernel
     auto split = [&](int NT) {
-        if (wide) {   // unit = (64-row block) * pad8(tile groups) + group of four column tiles
-            const int NG = cdiv(NT, 4), NGp = pad8(NG), gidx = u % NGp;
+        if (wide) {   // unit = (row block) * pad8(tile groups) + group of G column tiles
+            if (wide_big(R, g.N, P.big_min)) { g.G = 8; wrows = 128; }
+            const int NG = cdiv(NT, g.G), NGp = pad8(NG), gidx = u % NGp;
             rb = u / NGp;
-            nt = gidx * 4;
+            nt = gidx * g.G;
             return gidx < NG;
         }
         const int NTp = pad8(NT);
@@ -274,20 +284,20 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
         case 0:
             g.X = xb0; g.K = D.d; g.N = 3 * D.d; g.Wp = (const uint4*)w.Wqkv; g.bias = w.t_qkv; g.colsum = w.cs_qkv;
             g.stats = st0; g.epi = SE_QKV; g.out = q_l;
-            return split(3 * D.d / 16) ? (row0 = rb * 64, true) : false;
+            return split(3 * D.d / 16) ? (row0 = rb * wrows, true) : false;
         case 1: return false;
         case 2:
             g.X = att_l; g.K = D.d; g.N = D.d; g.Wp = (const uint4*)w.Wo; g.bias = w.bo;
             g.epi = SE_RESID; g.out = xb0 + s.act_stride; g.stats_out = st0 + s.stats_stride;
-            return split(D.d / 16) ? (row0 = rb * (wide ? 64 : 16), true) : false;
+            return split(D.d / 16) ? (row0 = rb * (wide ? wrows : 16), true) : false;
         case 3:
             g.X = xb0 + s.act_stride; g.K = D.d; g.N = D.F; g.Wp = (const uint4*)w.W1; g.bias = w.t_w1; g.colsum = w.cs_w1;
             g.stats = st0 + s.stats_stride; g.epi = SE_GELU; g.out = hid_l;
-            return split(D.F / 16) ? (row0 = rb * 64, true) : false;
+            return split(D.F / 16) ? (row0 = rb * wrows, true) : false;
         default:
             g.X = hid_l; g.K = D.F; g.N = D.d; g.Wp = (const uint4*)w.W2; g.bias = w.b2;
             g.epi = SE_RESID; g.out = xb0 + 2 * s.act_stride; g.stats_out = st0 + 2 * s.stats_stride;
-            return split(D.d / 16) ? (row0 = rb * (wide ? 64 : 16), true) : false;
+            return split(D.d / 16) ? (row0 = rb * (wide ? wrows : 16), true) : false;
         }
     }
     const int RGb = cdiv(D.B, 64);
@@ -296,7 +306,7 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
         g.X = s.xb + (size_t)(2 * D.Ly) * s.act_stride; g.K = D.d; g.N = D.V1; g.Wp = (const uint4*)s.W_out;
         g.bias = s.t_out; g.colsum = s.cs_out;
         g.stats = s.stats + (size_t)(2 * D.Ly) * s.stats_stride; g.epi = SE_LOGITS; g.outf = s.logits;
-        return split(cdiv(D.V1, 16)) ? (row0 = rb * 64, true) : false;
+        return split(cdiv(D.V1, 16)) ? (row0 = rb * wrows, true) : false;
     case TP_COMMIT: {
         const int ncommit = D.Ly * D.nH * P.nseq;
         if (u < ncommit) return false;
@@ -561,6 +571,273 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
 // four column tiles, so a compute unit ingests 256 KB per 64 x 64 outputs instead of 640 KB.
 // All epilogues, including the residual update with the statistics of the new rows.
 // ---------------------------------------------------------------------------
+// Epilogue of the many-row units for one thread's four outputs v[0..3] of row r, columns
+// n0 .. n0 + 3 (inside column tile `tile`): activation / residual / cache scatter as the map
+// asks.  The four threads of a row (tid & 3) hold a tile's 16 columns between them.
+__device__ __forceinline__ void wide_store(const GemmD& g, int r, int n0, int tile, const float (&v)[4], const uint4& xr) {
+    const StepParams& P = sP;
+    const Dims& D = P.D;
+    const DevState& s = P.s;
+    const int tid = threadIdx.x;
+    {
+        const bool full = n0 + 3 < g.N;
+        switch (g.epi) {
+        case SE_GELU:
+            stw64(g.out + toff(r, n0, g.N >> 5),
+                  (uint64_t)pack_bf16(gelu_s(v[0]), gelu_s(v[1])) | ((uint64_t)pack_bf16(gelu_s(v[2]), gelu_s(v[3])) << 32));
+            break;
+        case SE_LOGITS:
+        case SE_F32:
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (full || n0 + j < g.N) stwf(g.outf + (size_t)r * g.N + n0 + j, v[j]);
+            break;
+        case SE_RESID: {
+            // residual update; the statistics of the tile's 16 columns come from the four threads of the row
+            const float x0 = __uint_as_float(xr.x) + v[0], x1 = __uint_as_float(xr.y) + v[1];
+            const float x2 = __uint_as_float(xr.z) + v[2], x3 = __uint_as_float(xr.w) + v[3];
+            stwf2(s.x + (size_t)r * g.N + n0, x0, x1);
+            stwf2(s.x + (size_t)r * g.N + n0 + 2, x2, x3);
+            stw64(g.out + toff(r, n0, g.N >> 5), (uint64_t)pack_bf16(x0, x1) | ((uint64_t)pack_bf16(x2, x3) << 32));
+            float sum = x0 + x1 + x2 + x3;
+            sum += __shfl_xor(sum, 1, 64); sum += __shfl_xor(sum, 2, 64);
+            const float mean = sum * (1.f / 16.f);
+            float m2 = (x0 - mean) * (x0 - mean) + (x1 - mean) * (x1 - mean) + (x2 - mean) * (x2 - mean) + (x3 - mean) * (x3 - mean);
+            m2 += __shfl_xor(m2, 1, 64); m2 += __shfl_xor(m2, 2, 64);
+            if ((tid & 3) == 0) stwf2(g.stats_out + ((size_t)tile * g.R + r) * 2, mean, m2);
+            break;
+        }
+        case SE_QKV: {
+            const uint64_t pk = (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32);
+            if (n0 < D.d) { stw64(g.out + toff(r, n0, D.d >> 5), pk); break; }
+            const int b = r / D.M, node = r - b * D.M;
+            const int which = n0 / D.d - 1, cc = n0 % D.d, head = cc >> 6, dim = cc & 63;
+            const int pos = ldg(s.L + b) + node;
+            if (pos < D.maxpos && ldg(s.n_rows + b) > 0) {
+                const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
+                if (which) {
+                    bf16_t* vp = (bf16_t*)s.Vc + hb + (size_t)dim * D.maxpos + pos;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) stw16(vp + (size_t)j * D.maxpos, f2bf(v[j]));
+                } else {
+                    stw64((bf16_t*)s.Kc + hb + (size_t)pos * 64 + dim, pk);
+                }
+            }
+            break;
+        }
+        default: break;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// 128 x 128 unit of the many-row kernel (maps with at least 128 such units).  The reduction
+// runs in stages of two k-steps: a stage is 16 activation tiles and 16 weight tiles of 1 KiB
+// (tile = one MFMA operand, already in register layout in memory), copied by the four waves
+// into LDS and read from there by all of them: wave (wr, wc) owns rows 64 wr.., columns 64 wc..
+// (4 x 4 MFMA tiles), so every operand byte fetched from memory feeds four times as many MFMAs
+// as in the 64 x 64 unit.  Two stages sit in LDS (2 x 32 KiB) and four more are in flight in
+// registers.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void gemm_big_impl(const GemmD& g, int nt, int row0) {
+    constexpr int NRT = 4, NCT = 4;
+    const StepParams& P = sP;
+    extern __shared__ uint4 smem[];
+    float* s_stat = (float*)((char*)smem + ST_WIDE_TILE_BYTES);   // [2][128]: mean, 1/std of the unit's rows
+    const DevState& s = P.s;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int nks = g.K >> 5, NT = cdiv(g.N, 16), RT = cdiv(g.R, 16);
+    const int nch = nks >> 1;
+    const int wr = wave >> 1, wc = wave & 1;
+    const uint32_t ulane = (uint32_t)lane;
+    // loader: wave w copies tiles T = w + 4 j of a stage; T < 16: activation tile T >> 1 of the
+    // unit's eight row tiles, k-step T & 1 of the stage; T >= 16: weight tile (T - 16) >> 1
+    const uint4* src[8];
+    bool ok[8];
+    const int kk_w = wave & 1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int T = wave + 4 * j;
+        if (j < 4) {
+            const int rt = (row0 >> 4) + (T >> 1);
+            ok[j] = rt < RT;
+            src[j] = uniform_ptr((const uint4*)g.X + ((size_t)(ok[j] ? rt : 0) * nks + kk_w) * 64);
+        } else {
+            const int ct = nt + ((T - 16) >> 1);
+            ok[j] = ct < NT;
+            src[j] = uniform_ptr(g.Wp + ((size_t)(ok[j] ? ct : 0) * nks + kk_w) * 64);
+        }
+    }
+    // Every load is unconditional (a branch per load would serialise them): tiles beyond the map's
+    // last row or column tile re-read tile 0 and stages beyond the last re-read the last one; such
+    // operands only reach accumulators of rows and columns that the epilogue never stores, or
+    // stages that are never multiplied.  K is a multiple of 64 here, so a stage is always whole.
+    auto gload = [&](int c, uint4 (&G)[8]) {
+        const uint32_t off = (uint32_t)(c < nch ? c : nch - 1) * 2048u + ulane * 16u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) G[j] = ldg4((const char*)src[j] + off);
+    };
+    auto lstore = [&](int st, const uint4 (&G)[8]) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) smem[(st * 32 + wave + 4 * j) * 64 + lane] = G[j];
+    };
+    f32x4_t acc[NCT][NRT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) acc[ct][rt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    auto compute = [&](int st) {
+        uint4 a[2][NRT], b[2][NCT];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+            for (int rt = 0; rt < NRT; ++rt) a[kk][rt] = smem[(st * 32 + (wr * 4 + rt) * 2 + kk) * 64 + lane];
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) b[kk][ct] = smem[(st * 32 + 16 + (wc * 4 + ct) * 2 + kk) * 64 + lane];
+        }
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, b[kk][ct]);
+#pragma unroll
+                for (int rt = 0; rt < NRT; ++rt)
+                    acc[ct][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[kk][rt]), bfrag,
+                                                                          acc[ct][rt], 0, 0, 0);
+            }
+    };
+    // four stages are in flight in registers besides the one being multiplied: with ~2 us from a
+    // load's issue to its data under load, a compute unit needs over 100 KB outstanding to keep
+    // its matrix cores fed
+    uint4 G0[8], G1[8], G2[8], G3[8];
+    gload(0, G0);
+    gload(1, G1);
+    gload(2, G2);
+    gload(3, G3);
+    // row statistics of the LayerNorm folded into the map: two threads per row merge the row's
+    // tile statistics (while the first stages are on their way)
+    const bool do_stats = g.stats != nullptr;
+    const int tiles = g.K >> 4;
+    if (do_stats) {
+        const int srow = tid >> 1, sr = row0 + srow;
+        float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        if (sr < g.R) {
+            const float2* sp = (const float2*)g.stats + sr;
+            for (int t0 = tid & 1; t0 < tiles; t0 += 64) {   // 32 loads in flight: one latency up to K = 1024
+                float2 v[32];
+#pragma unroll
+                for (int j = 0; j < 32; ++j) {
+                    const int t = t0 + 2 * j;
+                    v[j] = ldgf2(sp + (size_t)(t < tiles ? t : 0) * g.R);
+                }
+#pragma unroll
+                for (int j = 0; j < 32; ++j)
+                    if (t0 + 2 * j < tiles) { s1 += v[j].x; s2 += v[j].y; s3 += v[j].x * v[j].x; }
+            }
+        }
+        s1 += __shfl_xor(s1, 1, 64);
+        s2 += __shfl_xor(s2, 1, 64);
+        s3 += __shfl_xor(s3, 1, 64);
+        if ((tid & 1) == 0) {
+            const float mean = s1 / tiles;
+            const float m2 = s2 + 16.f * fmaxf(s3 - tiles * mean * mean, 0.f);
+            s_stat[srow] = mean;
+            s_stat[128 + srow] = rsqrtf(m2 / g.K + LN_EPS);
+        }
+    }
+    lstore(0, G0);
+    if (4 < nch) gload(4, G0);
+    __syncthreads();
+    // One round = four stages.  On entry stage c sits in LDS half 0 and G1, G2, G3, G0 hold (or
+    // await) stages c + 1 .. c + 4.  While all of a round's loads exist they are issued without
+    // a branch, so that the waits before the LDS copies count exactly the loads issued since;
+    // the last rounds guard each group of loads and each multiplication.
+    auto round = [&](int c, auto all) {
+        constexpr bool ALL = decltype(all)::value;
+        compute(0);
+        lstore(1, G1);
+        if (ALL || c + 5 < nch) gload(c + 5, G1);
+        __syncthreads();
+        if (ALL || c + 1 < nch) compute(1);
+        lstore(0, G2);
+        if (ALL || c + 6 < nch) gload(c + 6, G2);
+        __syncthreads();
+        if (ALL || c + 2 < nch) compute(0);
+        lstore(1, G3);
+        if (ALL || c + 7 < nch) gload(c + 7, G3);
+        __syncthreads();
+        if (ALL || c + 3 < nch) compute(1);
+        lstore(0, G0);
+        if (ALL || c + 8 < nch) gload(c + 8, G0);
+        __syncthreads();
+    };
+    tp(g.ph, 7);
+    int c = 0;
+    for (; c + 8 < nch; c += 4) round(c, std::true_type{});
+    for (; c < nch; c += 4) round(c, std::false_type{});
+    tp(g.ph, 2);   // reduction done
+    // epilogue inputs of this thread for the four 64 x 64 quarters (row tid / 4 of the quarter,
+    // columns 4 (tid % 4) .. + 3 of each of its column tiles), fetched before the accumulators
+    // travel through LDS
+    const int erow = tid >> 2;
+    const bool resid = g.epi == SE_RESID;
+    uint4 cs4[2][NCT], b4[2][NCT], xr4[4][NCT];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            const int tile = nt + 4 * h + ct, n0 = tile * 16 + (tid & 3) * 4;
+            cs4[h][ct] = b4[h][ct] = make_uint4(0, 0, 0, 0);
+            if (tile < NT) {
+                if (g.colsum) cs4[h][ct] = ldg4(g.colsum + n0);
+                if (g.bias) b4[h][ct] = ldg4(g.bias + n0);
+            }
+        }
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            const int tile = nt + 4 * (q & 1) + ct, n0 = tile * 16 + (tid & 3) * 4;
+            const int er = row0 + 64 * (q >> 1) + erow;
+            xr4[q][ct] = make_uint4(0, 0, 0, 0);
+            if (resid && tile < NT && er < g.R) xr4[q][ct] = ldg4(s.x + (size_t)er * g.N + n0);
+        }
+    float* red = (float*)smem;   // [wave][ct][rt][lane][4]: wave (wr, wc) holds quarter q = 2 wr + wc
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[(((wave * NCT + ct) * NRT + rt) * 64 + lane) * 4 + i] = acc[ct][rt][i];
+    __syncthreads();
+    tp(g.ph, 3);   // accumulators in LDS
+    const int rt = erow >> 4, rr = erow & 15;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int r = row0 + 64 * (q >> 1) + erow;
+        if (r >= g.R) continue;
+        const float mu = do_stats ? s_stat[64 * (q >> 1) + erow] : 0.f;
+        const float rstd = do_stats ? s_stat[128 + 64 * (q >> 1) + erow] : 1.f;
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            const int tile = nt + 4 * (q & 1) + ct, n0 = tile * 16 + (tid & 3) * 4;
+            if (tile >= NT || n0 >= g.N) continue;
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = (tid & 3) * 4 + j;
+                float a = red[q * (NCT * NRT * 256) + ((ct * NRT + rt) * 64 + (rr >> 2) * 16 + col) * 4 + (rr & 3)];
+                const uint4 &csv = cs4[q & 1][ct], &bv = b4[q & 1][ct];
+                const float csj = __uint_as_float(j == 0 ? csv.x : j == 1 ? csv.y : j == 2 ? csv.z : csv.w);
+                const float bj = __uint_as_float(j == 0 ? bv.x : j == 1 ? bv.y : j == 2 ? bv.z : bv.w);
+                if (do_stats) a = rstd * (a - mu * csj);
+                v[j] = a + bj;
+            }
+            wide_store(g, r, n0, tile, v, xr4[q][ct]);
+        }
+    }
+}
+
 __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
     constexpr int NRT = 4, NCT = 4, CH = 2;
     const int ph_u = __builtin_amdgcn_readfirstlane(ph_), u_u = __builtin_amdgcn_readfirstlane(u_);
@@ -568,6 +845,7 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
     GemmD g;
     int nt, row0;
     if (!describe_gemm<true>(ph_u, u_u, g, nt, row0)) return;
+    if (g.G == 8) { gemm_big_impl(g, nt, row0); return; }
     extern __shared__ uint4 smem[];
     float* s_stat = (float*)((char*)smem + ST_WIDE_TILE_BYTES);
     const Dims& D = P.D;
@@ -626,22 +904,24 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
     }
     // two chunks of CH k-steps in flight alternately: the loads of one chunk overlap the MFMAs of
     // the other (chunks beyond the wave's range load nothing and multiply zeros)
+    // Every load is unconditional (a branch per load would serialise them): a tile beyond the
+    // map's last row or column tile re-reads a valid one and only reaches accumulators that the
+    // epilogue never stores; a k-step beyond the wave's range re-reads the map's last k-step and
+    // is not multiplied.
     auto load_chunk = [&](int kb, uint4 (&bw)[NCT][CH], uint4 (&aw)[NRT][CH]) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const bool kok = kb + i < ks_hi;
-            const uint32_t off = (uint32_t)(kok ? kb + i : ks_lo) * 1024u + ulane * 16u;
+            const uint32_t off = (uint32_t)(kb + i < nks ? kb + i : nks - 1) * 1024u + ulane * 16u;
 #pragma unroll
-            for (int ct = 0; ct < NCT; ++ct)
-                bw[ct][i] = (kok && tile_ok[ct]) ? ldg4((const char*)Wp[ct] + off) : make_uint4(0, 0, 0, 0);
+            for (int ct = 0; ct < NCT; ++ct) bw[ct][i] = ldg4((const char*)Wp[ct] + off);
 #pragma unroll
-            for (int rt = 0; rt < NRT; ++rt)
-                aw[rt][i] = (kok && rowok[rt]) ? ldg4((const char*)Ap[rt] + off) : make_uint4(0, 0, 0, 0);
+            for (int rt = 0; rt < NRT; ++rt) aw[rt][i] = ldg4((const char*)Ap[rt] + off);
         }
     };
-    auto mfma_chunk = [&](const uint4 (&bw)[NCT][CH], const uint4 (&aw)[NRT][CH]) {
+    auto mfma_chunk = [&](int kb, const uint4 (&bw)[NCT][CH], const uint4 (&aw)[NRT][CH]) {
 #pragma unroll
         for (int i = 0; i < CH; ++i)
+            if (kb + i < ks_hi)
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct) {
                 const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bw[ct][i]);
@@ -656,9 +936,9 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
         load_chunk(ks_lo, bw0, aw0);
         for (int kb = ks_lo; kb < ks_hi; kb += 2 * CH) {
             load_chunk(kb + CH, bw1, aw1);
-            mfma_chunk(bw0, aw0);
+            mfma_chunk(kb, bw0, aw0);
             load_chunk(kb + 2 * CH, bw0, aw0);
-            mfma_chunk(bw1, aw1);
+            mfma_chunk(kb + CH, bw1, aw1);
         }
     }
     if (do_stats) {
@@ -702,53 +982,7 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
             if (do_stats) a = rstd * (a - mu * csj);
             v[j] = a + bj;
         }
-        const bool full = n0 + 3 < g.N;
-        switch (g.epi) {
-        case SE_GELU:
-            stw64(g.out + toff(r, n0, g.N >> 5),
-                  (uint64_t)pack_bf16(gelu_s(v[0]), gelu_s(v[1])) | ((uint64_t)pack_bf16(gelu_s(v[2]), gelu_s(v[3])) << 32));
-            break;
-        case SE_LOGITS:
-        case SE_F32:
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (full || n0 + j < g.N) stwf(g.outf + (size_t)r * g.N + n0 + j, v[j]);
-            break;
-        case SE_RESID: {
-            // residual update; the statistics of the tile's 16 columns come from the four threads of the row
-            const float x0 = __uint_as_float(xr4[ct].x) + v[0], x1 = __uint_as_float(xr4[ct].y) + v[1];
-            const float x2 = __uint_as_float(xr4[ct].z) + v[2], x3 = __uint_as_float(xr4[ct].w) + v[3];
-            stwf2(s.x + (size_t)r * g.N + n0, x0, x1);
-            stwf2(s.x + (size_t)r * g.N + n0 + 2, x2, x3);
-            stw64(g.out + toff(r, n0, g.N >> 5), (uint64_t)pack_bf16(x0, x1) | ((uint64_t)pack_bf16(x2, x3) << 32));
-            float sum = x0 + x1 + x2 + x3;
-            sum += __shfl_xor(sum, 1, 64); sum += __shfl_xor(sum, 2, 64);
-            const float mean = sum * (1.f / 16.f);
-            float m2 = (x0 - mean) * (x0 - mean) + (x1 - mean) * (x1 - mean) + (x2 - mean) * (x2 - mean) + (x3 - mean) * (x3 - mean);
-            m2 += __shfl_xor(m2, 1, 64); m2 += __shfl_xor(m2, 2, 64);
-            if ((tid & 3) == 0) stwf2(g.stats_out + ((size_t)(nt + ct) * g.R + r) * 2, mean, m2);
-            break;
-        }
-        case SE_QKV: {
-            const uint64_t pk = (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32);
-            if (n0 < D.d) { stw64(g.out + toff(r, n0, D.d >> 5), pk); break; }
-            const int b = r / D.M, node = r - b * D.M;
-            const int which = n0 / D.d - 1, cc = n0 % D.d, head = cc >> 6, dim = cc & 63;
-            const int pos = ldg(s.L + b) + node;
-            if (pos < D.maxpos && ldg(s.n_rows + b) > 0) {
-                const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
-                if (which) {
-                    bf16_t* vp = (bf16_t*)s.Vc + hb + (size_t)dim * D.maxpos + pos;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) stw16(vp + (size_t)j * D.maxpos, f2bf(v[j]));
-                } else {
-                    stw64((bf16_t*)s.Kc + hb + (size_t)pos * 64 + dim, pk);
-                }
-            }
-            break;
-        }
-        default: break;
-        }
+        wide_store(g, r, n0, nt + ct, v, xr4[ct]);
     }
 }
 
