@@ -68,7 +68,18 @@ struct GemmD {
 // may live in host memory) into LDS.  Every device function reads them from here.
 __shared__ StepParams sP;
 
-__device__ __forceinline__ float gelu_s(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752f)); }
+// GELU with the exact (erf) definition; erf by the rational approximation 7.1.26 of Abramowitz &
+// Stegun (absolute error below 1.5e-7, the size of an fp32 rounding of the result, which is then
+// stored as bf16): one exponential, one reciprocal and a fifth-degree polynomial instead of the
+// library routine's two branches.
+__device__ __forceinline__ float gelu_s(float v) {
+    const float x = fabsf(v) * 0.70710678118654752f;
+    const float t = __frcp_rn(1.f + 0.3275911f * x);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    const float erfc_x = poly * __expf(-x * x);            // 1 - erf(|x|)
+    const float one_plus_erf = v < 0.f ? erfc_x : 2.f - erfc_x;
+    return 0.5f * v * one_plus_erf;
+}
 __device__ __forceinline__ float silu_s(float v) { return v / (1.f + __expf(-v)); }
 
 // ---------------------------------------------------------------------------
