@@ -396,10 +396,21 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
     // padded to whole 16-column tiles)
     uint4 cs4 = make_uint4(0, 0, 0, 0), b4 = cs4;
     float xres = 0.f, bres = 0.f;
+    int kv_b = 0, kv_L = 0, kv_rows = 0, kv_which = 0, kv_cc = 0;   // QKV map: where this thread's key / value row goes
     if (NRT == 4) {
         const int n0 = nt * 16 + (tid & 3) * 4;
         if (g.colsum) cs4 = ldg4(g.colsum + n0);
         if (g.bias) b4 = ldg4(g.bias + n0);
+        if (g.epi == SE_QKV && nt * 16 >= D.d) {
+            const int r = row0 + (tid >> 2);
+            kv_which = (nt * 16) / D.d - 1;            // workgroup-uniform: 0 keys, 1 values
+            kv_cc = (nt * 16) % D.d;
+            if (r < g.R) {
+                kv_b = r / D.M;
+                kv_L = ldg(s.L + kv_b);
+                kv_rows = ldg(s.n_rows + kv_b);
+            }
+        }
     } else {
         const int r = row0 + (tid >> 4), n = nt * 16 + (tid & 15);
         if (r < g.R) xres = ldg(s.x + (size_t)r * g.N + n);
@@ -529,10 +540,10 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
             case SE_QKV: {
                 const uint64_t pk = (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32);
                 if (n0 < D.d) { stw64(g.out + toff(r, n0, D.d >> 5), pk); break; }
-                const int b = r / D.M, node = r - b * D.M;
-                const int which = n0 / D.d - 1, cc = n0 % D.d, head = cc >> 6, dim = cc & 63;
-                const int pos = ldg(s.L + b) + node;
-                if (pos < D.maxpos && ldg(s.n_rows + b) > 0) {
+                const int b = kv_b, node = r - b * D.M;
+                const int which = kv_which, cc = kv_cc + (tid & 3) * 4, head = cc >> 6, dim = cc & 63;
+                const int pos = kv_L + node;
+                if (pos < D.maxpos && kv_rows > 0) {
                     const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
                     if (which) {
                         bf16_t* vp = (bf16_t*)s.Vc + hb + (size_t)dim * D.maxpos + pos;   // V is kept [dim][pos]
