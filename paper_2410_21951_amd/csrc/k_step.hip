@@ -439,6 +439,21 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
             }
         }
     };
+    // Up to 64 tiles (K <= 1024) a thread's share of the statistics is at most 16 entries: they are
+    // requested here, ahead of the operands, so that they are back before the operands are (asked
+    // for after them they would return last and the reduction's result would wait for them), and
+    // summed after the MFMAs.  Addresses are clamped instead of guarded: no branch per load.
+    const bool stats_early = do_stats && tiles <= 64;
+    float2 sv[16];
+    if (stats_early) {
+        const int r = row0 + (tid >> 2);
+        const float2* sp = (const float2*)g.stats + (r < g.R ? r : 0);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int t = (tid & 3) + 4 * j;
+            sv[j] = ldgf2(sp + (size_t)(t < tiles ? t : 0) * g.R);
+        }
+    }
     // the first pass always runs: a wave without k-steps (K < 128) loads nothing in it but still
     // merges the statistics of its rows
     for (int kb = ks_lo; kb == ks_lo || kb < ks_hi; kb += CH) {
@@ -466,7 +481,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
                 }
         }
         if (kb == ks_lo) tp(g.ph, 6);
-        if (kb == ks_lo && do_stats) merge_stats();
+        if (kb == ks_lo && do_stats && !stats_early) merge_stats();
         if (kb == ks_lo) tp(g.ph, 7);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
@@ -478,6 +493,11 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
         }
     }
     tp(g.ph, 2);   // operands arrived, MFMAs issued
+    if (stats_early && row0 + (tid >> 2) < g.R) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if ((tid & 3) + 4 * j < tiles) { s1 += sv[j].x; s2 += sv[j].y; s3 += sv[j].x * sv[j].x; }
+    }
     if (g.stats) {
         s1 += __shfl_xor(s1, 1, 64); s1 += __shfl_xor(s1, 2, 64);
         s2 += __shfl_xor(s2, 1, 64); s2 += __shfl_xor(s2, 2, 64);
