@@ -122,7 +122,7 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     case TP_EDGES: return P.prefill_mode ? 0 : cdiv(R, 4);
     case TP_SELECT: return P.prefill_mode ? 0 : P.nseq;
     case TP_FINAL: return P.nseq;
-    case TP_COMMIT: return D.Ly * D.nH * P.nseq + D.Hh * (D.d / 16) * RGb;
+    case TP_COMMIT: return D.Ly * cdiv(D.nH, 4) * P.nseq + D.Hh * (D.d / 16) * RGb;
     case TP_DRAFT2: return D.Hh * cdiv(D.V1, 16) * RGb;
     default: return D.Hh * D.B;
     }
@@ -319,7 +319,7 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
         g.stats = s.stats + (size_t)(2 * D.Ly) * s.stats_stride; g.epi = SE_LOGITS; g.outf = s.logits;
         return split(cdiv(D.V1, 16)) ? (row0 = rb * wrows, true) : false;
     case TP_COMMIT: {
-        const int ncommit = D.Ly * D.nH * P.nseq;
+        const int ncommit = D.Ly * cdiv(D.nH, 4) * P.nseq;
         if (u < ncommit) return false;
         u -= ncommit;
         const int per = (D.d / 16) * RGb, i = u / per, v = u % per;
@@ -1221,11 +1221,11 @@ __device__ __forceinline__ void final_unit(int u_) {
 __device__ __forceinline__ void commit_unit(int u_) {
     const int u = __builtin_amdgcn_readfirstlane(u_);
     const StepParams& P = sP;
-    if (threadIdx.x < 64) {
-        const Dims& D = P.D;
-        const int head = u % D.nH, b = (u / D.nH) % P.nseq, layer = u / (D.nH * P.nseq);
-        dev_commit_kv<bf16_t>(D, P.s, layer, P.seq0 + b, head, threadIdx.x);
-    }
+    // a unit is four heads of one (layer, sequence): one wave (64 head dimensions) per head
+    const Dims& D = P.D;
+    const int HQ = cdiv(D.nH, 4);
+    const int head = (u % HQ) * 4 + (int)(threadIdx.x >> 6), b = (u / HQ) % P.nseq, layer = u / (HQ * P.nseq);
+    if (head < D.nH) dev_commit_kv<bf16_t>(D, P.s, layer, P.seq0 + b, head, threadIdx.x & 63);
 }
 __device__ __forceinline__ void topk_unit(int u_) { const int u = __builtin_amdgcn_readfirstlane(u_); const StepParams& P = sP; dev_topk(P.D, P.s, u / P.D.B, u % P.D.B); }
 
@@ -1253,7 +1253,7 @@ __device__ __forceinline__ void run_unit(int ph, int u) {
         case TP_EDGES: kind = K_EDGE; break;
         case TP_SELECT: kind = K_SELECT; break;
         case TP_FINAL: kind = K_FINAL; break;
-        case TP_COMMIT: kind = u < D.Ly * D.nH * P.nseq ? K_COMMIT : K_GEMM4; break;
+        case TP_COMMIT: kind = u < D.Ly * cdiv(D.nH, 4) * P.nseq ? K_COMMIT : K_GEMM4; break;
         case TP_TOPK: kind = K_TOPK; break;
         default: kind = (WIDE && ph == H) ? K_GEMMW : K_GEMM4; break;   // TP_HEAD, TP_DRAFT2
         }
