@@ -97,6 +97,8 @@ int step_num_phases(int n_layers) { return 1 + 5 * n_layers + TP_COUNT; }
 // (StepParams::big_min of them) take those (operands staged through LDS and shared by the four waves); smaller ones keep
 // the 64 x 64 units whose waves split the reduction.
 __host__ __device__ inline bool wide_big(int R, int N, int min_units) { return cdiv(R, 128) * cdiv(N, 128) >= min_units; }
+// Attention units of the many-row kernel are whole (sequence, head)s once there is one per compute unit.
+__host__ __device__ inline bool attn_allq(const StepParams& P) { return P.wide && P.D.B * P.D.nH >= P.big_min; }
 __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     const Dims& D = P.D;
     const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
@@ -110,7 +112,7 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     if (ph < H) {
         switch ((ph - 1) % 5) {
         case 0: return pad8(3 * D.d / 16) * RG;
-        case 1: return pad8(D.B * D.nH) * cdiv(D.M, 16);
+        case 1: return attn_allq(P) ? pad8(D.B * D.nH) : pad8(D.B * D.nH) * cdiv(D.M, 16);
         case 2: return pad8(D.d / 16) * RB;
         case 3: return pad8(D.F / 16) * RG;
         default: return pad8(D.d / 16) * RB;
@@ -1035,6 +1037,11 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
 // round-robin with a private online softmax (S^T = K Q^T, O^T += V^T P^T on
 // MFMA), then merge through LDS.  K is kept [pos][64], V is kept [64][pos].
 // ---------------------------------------------------------------------------
+// ALLQ (many-row kernel, at least one (sequence, head) per compute unit): a unit is a whole
+// (sequence, head); wave w takes query tile w over all key blocks, so the four waves read the
+// same K / V blocks (once from L2, then from the compute unit's L1), nothing is merged across
+// waves, and the result goes from the accumulators straight to memory.
+template <bool ALLQ>
 __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     const int layer = (__builtin_amdgcn_readfirstlane(ph_) - 1) / 5, u = __builtin_amdgcn_readfirstlane(u_);
     const StepParams& P = sP;
@@ -1046,9 +1053,11 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     // one XCD (workgroup i is on XCD i mod 8) and share its L2 for that head's K / V rows
     const int BH = pad8(D.B * D.nH);
     int bh, qt, h, b;
-    if ((BH & (BH - 1)) == 0) { bh = u & (BH - 1); qt = u >> __builtin_ctz(BH); }   // no division in the usual case
+    if (ALLQ) { bh = u; qt = wave; }
+    else if ((BH & (BH - 1)) == 0) { bh = u & (BH - 1); qt = u >> __builtin_ctz(BH); }   // no division in the usual case
     else { bh = u % BH; qt = u / BH; }
     if (bh >= D.B * D.nH) return;
+    if (ALLQ && qt * 16 >= D.M) return;   // fewer than four query tiles: this wave has none
     if ((D.nH & (D.nH - 1)) == 0) { h = bh & (D.nH - 1); b = bh >> __builtin_ctz(D.nH); }
     else { h = bh % D.nH; b = bh / D.nH; }
     // everything the unit needs before its first key block is requested at once: row count,
@@ -1064,6 +1073,12 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     const uint32_t mword[4] = {mw.x, mw.y, mw.z, mw.w};
     bf16_t* att = (bf16_t*)s.att + (size_t)layer * s.act_stride;
     if (n_rows == 0) {
+        if (ALLQ) {
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+                if (qt * 16 + c < D.M) stw64(att + toff(b * D.M + qt * 16 + c, h * 64 + dt * 16 + 4 * gq, D.d >> 5), 0ull);
+            return;
+        }
         const int q = tid >> 4, d0 = (tid & 15) * 4, nd = qt * 16 + q;
         if (nd < D.M) stw64(att + toff(b * D.M + nd, h * 64 + d0, D.d >> 5), 0ull);
         return;
@@ -1091,10 +1106,11 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
         for (int dt = 0; dt < 4; ++dt) kv[4 + dt] = ldg4(Vh + (size_t)(dt * 16 + c) * D.maxpos + vv);
     };
     uint4 cur[8], nxt[8], nx2[8];   // two blocks in flight behind the one being computed
-    if (wave < nblk) load_block(wave, cur);
-    if (wave + 4 < nblk) load_block(wave + 4, nxt);
-    for (int blk = wave; blk < nblk; blk += 4) {
-        if (blk + 8 < nblk) load_block(blk + 8, nx2);
+    const int blk0 = ALLQ ? 0 : wave, bstep = ALLQ ? 1 : 4;   // the waves split the blocks, or each takes all
+    if (blk0 < nblk) load_block(blk0, cur);
+    if (blk0 + bstep < nblk) load_block(blk0 + bstep, nxt);
+    for (int blk = blk0; blk < nblk; blk += bstep) {
+        if (blk + 2 * bstep < nblk) load_block(blk + 2 * bstep, nx2);
         const int p0 = blk << 5;
         const int v0 = p0 + 8 * gq;
         const uint4 a0 = cur[0], a1 = cur[1], b0 = cur[2], b1 = cur[3];
@@ -1129,7 +1145,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
                 const float p0f = (okm >> j) & 1u ? __expf(sc[j] - m_new) : 0.f;
                 const float p1f = (okm >> (j + 1)) & 1u ? __expf(sc[j + 1] - m_new) : 0.f;
                 psum += p0f + p1f;
-                pk[j >> 1] = (uint32_t)f2bf(p0f) | ((uint32_t)f2bf(p1f) << 16);
+                pk[j >> 1] = pack_bf16(p0f, p1f);
             }
         };
         if (p0 + 32 > L) {   // the block reaches into the tree rows (same for the whole wave)
@@ -1159,9 +1175,20 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) { cur[i] = nxt[i]; nxt[i] = nx2[i]; }
     }
-    // merge the four waves: sm_m / sm_l [wave][query], sm_o [wave][dim][query]
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
+    if (ALLQ) {   // this lane: query c, dimensions dt * 16 + 4 gq .. + 3 of every dt
+        const float inv = 1.f / l_run;
+        const int nd = qt * 16 + c;
+        if (nd < D.M) {
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+                stw64(att + toff(b * D.M + nd, h * 64 + dt * 16 + 4 * gq, D.d >> 5),
+                      (uint64_t)pack_bf16(O[dt][0] * inv, O[dt][1] * inv) | ((uint64_t)pack_bf16(O[dt][2] * inv, O[dt][3] * inv) << 32));
+        }
+        return;
+    }
+    // merge the four waves: sm_m / sm_l [wave][query], sm_o [wave][dim][query]
     float* sm_o = (float*)smem;
     float* sm_m = sm_o + 4 * 64 * 16;
     float* sm_l = sm_m + 64;
@@ -1260,7 +1287,10 @@ __device__ __forceinline__ void run_unit(int ph, int u) {
     }
     switch (kind) {
     case K_EMBED: embed_unit(u); break;
-    case K_ATTN: attn_unit(ph, u); break;
+    case K_ATTN:
+        if constexpr (WIDE) { if (attn_allq(P)) attn_unit<true>(ph, u); else attn_unit<false>(ph, u); }
+        else attn_unit<false>(ph, u);
+        break;
     case K_GEMM4: gemm_unit<4>(ph, u); break;
     case K_GEMM1: if constexpr (!WIDE) gemm_unit<1>(ph, u); break;
     case K_GEMMW: if constexpr (WIDE) gemm_wide_unit(ph, u); break;
