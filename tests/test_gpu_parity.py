@@ -406,3 +406,24 @@ def test_large_vocabulary_16k():
     _say(f"  compared {s.compared}/{s.steps} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} logit err {s.max_logit_err:.2e} "
          f"score err {s.max_score_err:.2e} kept {[round(x) for x in s.nucleus_sizes]}")
     assert s.compared >= 4
+
+
+def test_many_row_unit_kinds_on_ragged_shapes(monkeypatch):
+    """The many-row kernel's 128 x 128 linear-map units and whole-head attention units, which the
+    library only picks for maps and batches that fill the GPU, forced on for a small batch with
+    ragged shapes (280 rows: a partial 128-row block; 56-node tree: a partial query tile;
+    vocabulary 301: a partial column group)."""
+    monkeypatch.setenv("VADUSA_BIG_MIN_UNITS", "1")     # read when the context is created
+    cfg = small_cfg("bf16", layers=2, d=128, heads=3, V=300, maxpos=256)
+    _say("many-row unit kinds, ragged shapes")
+    W = make_weights(cfg, 17, std=STD["bf16"], ln_jitter=0.1)
+    rng = np.random.default_rng(47)
+    text, prompt = rand_tokens(cfg, rng, 5, (3, 9), (40, 75))
+    tree = make_tree(56, (10, 10, 10))
+    ls = _lock(cfg, W, text, prompt, 56)
+    for tau in (1, 3, 8):
+        ls.step(tree, tau)
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    _say(f"  compared {s.compared}/{s.steps} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} logit err {s.max_logit_err:.2e}")
+    assert s.compared >= 2
