@@ -120,6 +120,16 @@ size_t vadusa_blob_floats(const vadusa_config* cfg);
  * stream).  *out receives the context (host object, freed by vadusa_destroy). */
 int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena_bytes,
                   void* hip_stream, vadusa_ctx** out);
+/* Environment variables read by vadusa_create, VADUSA_COOPERATIVE_LAUNCH at the process's first
+ * step launch (debugging and test aids; none changes results):
+ *   VADUSA_PHASE_LAUNCHES       one kernel launch per phase of the bf16 step instead of one
+ *                               persistent launch with grid barriers
+ *   VADUSA_COOPERATIVE_LAUNCH   launch the persistent kernel cooperatively
+ *   VADUSA_PHASE_CLOCK          record the timing points of VADUSA_DBG_PHASE_CLOCK
+ *   VADUSA_BIG_MIN_UNITS=n      many-row kernel (>= 256 rows): a linear map takes 128 x 128 output
+ *                               units, and attention whole (sequence, head) units, from n such
+ *                               units on (default 256 = one per compute unit); lets tests
+ *                               reach those code paths with small shapes */
 
 void vadusa_destroy(vadusa_ctx* ctx);
 
