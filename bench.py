@@ -223,6 +223,23 @@ def main():
     out["ar_step"] = {"us_per_step": ar_us, "steps": n_ar, "tree_step_over_ar_step": ms_step * 1e3 / ar_us,
                       "speedup_at_paper_accepted_len": {"tau1_acc3.00": 3.00 * ar_us / (ms_step * 1e3),
                                                         "tau3_acc3.87": 3.87 * ar_us / (ms_step * 1e3)}}
+    # Prefill (the call synchronises, so host time is the measure): in passes of max_tree_nodes rows
+    # (the default) and in passes of up to 512 rows per sequence (vadusa_config.prefill_chunk), which
+    # run in the many-row kernel from 256 rows on.
+    def prefill_ms(d, reps=5):
+        d.prefill(text, prompt)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            d.prefill(text, prompt)
+        return (time.perf_counter() - t0) / reps * 1e3
+    n_prompt = int(sum(L0))
+    ms_small = prefill_ms(dev)
+    dev512 = Vadusa(m, max_batch=wl.batch, max_tree_nodes=wl.tree_nodes, ignore_eos=True, prefill_chunk=512)
+    dev512.load_weights(W)
+    ms_big = prefill_ms(dev512)
+    dev512.close()
+    out["prefill"] = {"prompt_tokens": n_prompt, "ms_passes_of_tree_size": ms_small, "ms_passes_of_512": ms_big,
+                      "tokens_per_s_passes_of_512": n_prompt / (ms_big * 1e-3)}
     # The stochastic form of Algorithm 1 (temperature 0.9, top_p 0.9 as in Sec. 3.1.2's sampling runs):
     # the same step with the perturbed-score kernel between the base head and the acceptance; the
     # uniforms are drawn on the device beforehand (their generation is not part of the step).

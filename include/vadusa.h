@@ -44,6 +44,7 @@ extern "C" {
 
 #define VADUSA_MAX_TREE_NODES 128   /* M, root included (Sec. 3.1.3 uses 64, 96, 128) */
 #define VADUSA_MAX_TOPK        16   /* largest rank + 1 a tree may use (the paper uses 10) */
+#define VADUSA_MAX_PREFILL_CHUNK 1024 /* most rows of one sequence in one pass of the prefill */
 #define VADUSA_MAX_DRAFT_HEADS  8   /* the paper uses 4 or 6 */
 
 typedef struct vadusa_ctx vadusa_ctx;   /* opaque */
@@ -63,7 +64,10 @@ typedef struct {
     int32_t max_tree_nodes; /* largest M used in any step, <= VADUSA_MAX_TREE_NODES */
     int32_t dtype;          /* 0: fp32 weights/activations, 1: bf16 storage with fp32 accumulation */
     int32_t ignore_eos;     /* 1: EOS is an ordinary token (fixed-length benchmarks) */
-    int32_t reserved;       /* must be 0 */
+    int32_t prefill_chunk;  /* rows of a sequence that one pass of vadusa_prefill runs through the decoder:
+                               0 = max_tree_nodes, else 1..VADUSA_MAX_PREFILL_CHUNK (longer passes turn the
+                               prompt's linear maps into many-row products; the arena grows with
+                               max_batch * prefill_chunk rows of activations) */
 } vadusa_config;
 
 /*

@@ -39,6 +39,9 @@ static int fail(vadusa_ctx* c, int code, const char* fmt, ...) {
     } while (0)
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+// rows of one sequence in one pass of the prefill, and the most rows one sequence ever has in a forward
+static int prefill_rows(const vadusa_config& c) { return c.prefill_chunk > 0 ? c.prefill_chunk : c.max_tree_nodes; }
+static int seq_rows_cap(const vadusa_config& c) { return std::max(c.max_tree_nodes, prefill_rows(c)); }
 static int pad16(int n) { return (n + 15) / 16 * 16; }
 
 extern "C" int vadusa_config_check(const vadusa_config* c, char* msg, size_t n) {
@@ -47,7 +50,8 @@ extern "C" int vadusa_config_check(const vadusa_config* c, char* msg, size_t n) 
     if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->d_ffn < 1 || c->speech_vocab < 1 ||
         c->text_vocab < 1 || c->max_positions < 2 || c->max_batch < 1 || c->max_tree_nodes < 1)
         BAD(VADUSA_EINVAL, "sizes must be positive");
-    if (c->reserved != 0) BAD(VADUSA_EINVAL, "reserved must be 0");
+    if (c->prefill_chunk < 0) BAD(VADUSA_EINVAL, "prefill_chunk must be >= 0");
+    if (c->prefill_chunk > VADUSA_MAX_PREFILL_CHUNK) BAD(VADUSA_ESHAPE, "prefill_chunk must be <= %d", VADUSA_MAX_PREFILL_CHUNK);
     if (c->dtype != 0 && c->dtype != 1) BAD(VADUSA_EINVAL, "dtype must be 0 (fp32) or 1 (bf16)");
     if (c->ignore_eos != 0 && c->ignore_eos != 1) BAD(VADUSA_EINVAL, "ignore_eos must be 0 or 1");
     if (c->head_dim != 64) BAD(VADUSA_ESHAPE, "head_dim must be 64 (got %d)", c->head_dim);
@@ -61,7 +65,8 @@ extern "C" int vadusa_config_check(const vadusa_config* c, char* msg, size_t n) 
         BAD(VADUSA_ESHAPE, "max_positions must exceed max_tree_nodes");
     if (c->max_positions % 8) BAD(VADUSA_ESHAPE, "max_positions must be a multiple of 8");
     if (c->d_model % 64) BAD(VADUSA_ESHAPE, "d_model must be a multiple of 64");
-    if ((int64_t)c->max_batch * c->max_tree_nodes > (1 << 20)) BAD(VADUSA_ESHAPE, "max_batch * max_tree_nodes too large");
+    if ((int64_t)c->max_batch * std::max(c->max_tree_nodes, c->prefill_chunk) > (1 << 20))
+        BAD(VADUSA_ESHAPE, "max_batch * max(max_tree_nodes, prefill_chunk) too large");
 #undef BAD
     return VADUSA_OK;
 }
@@ -180,7 +185,7 @@ static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vecto
     Carver cv{base};
     const size_t e = c.dtype ? 2 : 4;
     const size_t d = c.d_model, F = c.d_ffn, V1 = c.speech_vocab + 1, Hh = c.n_draft_heads;
-    const size_t R = (size_t)c.max_batch * c.max_tree_nodes, B = c.max_batch, P = c.max_positions;
+    const size_t R = (size_t)c.max_batch * seq_rows_cap(c), B = c.max_batch, P = c.max_positions;
     DevState st{};
     std::vector<LayerW> lw(c.n_layers);
     std::vector<DraftW> dw(Hh);
@@ -542,7 +547,12 @@ extern "C" int vadusa_prefill(vadusa_ctx* c, int32_t batch, const int32_t* text_
     if (c->state < 1) return fail(c, VADUSA_ESTATE, "weights not loaded");
     if (batch < 1 || batch > c->cfg.max_batch) return fail(c, VADUSA_EINVAL, "batch %d outside 1..%d", batch, c->cfg.max_batch);
     if (!text_len || !prompt_len) return fail(c, VADUSA_EINVAL, "length arrays are null");
-    const int Mc = c->cfg.max_tree_nodes;
+    int Mc = prefill_rows(c->cfg);
+    {   // no pass needs more rows per sequence than the longest sequence has (whole 16-row tiles)
+        int longest = 1;
+        for (int b = 0; b < batch; ++b) longest = std::max(longest, text_len[b] + prompt_len[b]);
+        Mc = std::min(Mc, std::max((longest + 15) / 16 * 16, std::min(c->cfg.max_tree_nodes, Mc)));
+    }
     std::vector<std::vector<int32_t>> seqs(batch);
     size_t to = 0, po = 0;
     int max_chunks = 0;
@@ -550,8 +560,9 @@ extern "C" int vadusa_prefill(vadusa_ctx* c, int32_t batch, const int32_t* text_
         const int tl = text_len[b], pl = prompt_len[b];
         if (tl < 0 || pl < 0 || tl + pl < 1) return fail(c, VADUSA_EINVAL, "sequence %d is empty or has a negative length", b);
         if ((tl && !text_tok) || (pl && !prompt_tok)) return fail(c, VADUSA_EINVAL, "token array is null");
-        if (tl + pl + Mc > c->cfg.max_positions)
-            return fail(c, VADUSA_EKVFULL, "sequence %d: %d tokens + %d tree rows exceed max_positions %d", b, tl + pl, Mc, c->cfg.max_positions);
+        if (tl + pl + c->cfg.max_tree_nodes > c->cfg.max_positions)
+            return fail(c, VADUSA_EKVFULL, "sequence %d: %d tokens + %d tree rows exceed max_positions %d", b, tl + pl,
+                        c->cfg.max_tree_nodes, c->cfg.max_positions);
         for (int i = 0; i < tl; ++i) {
             const int t = text_tok[to + i];
             if (t < 0 || t >= c->cfg.text_vocab) return fail(c, VADUSA_EINVAL, "text token %d out of range", t);

@@ -168,7 +168,9 @@ __global__ void k_attn_simple(Dims D, DevState s, int layer, int table) {
     float q[64];
 #pragma unroll
     for (int i = 0; i < 64; ++i) q[i] = ldf(qp + i) * 0.125f;
-    const uint32_t* mrow = s.t_mask[table] + (size_t)n * MASK_WORDS;
+    // table 1 is the causal chunk of the prefill (row n sees rows 0..n), which may have more rows
+    // than the mask table has entries: no mask words are read for it
+    const uint32_t* mrow = s.t_mask[0] + (size_t)(table == 1 ? 0 : n) * MASK_WORDS;
     float m = -INFINITY, l = 0.f, o[64];
 #pragma unroll
     for (int i = 0; i < 64; ++i) o[i] = 0.f;
@@ -176,7 +178,7 @@ __global__ void k_attn_simple(Dims D, DevState s, int layer, int table) {
     for (int j = lane; j < T_all; j += 64) {
         if (j >= L) {
             const int mm = j - L;
-            if (!((mrow[mm >> 5] >> (mm & 31)) & 1u)) continue;
+            if (table == 1 ? mm > n : !((mrow[(mm >> 5) & (MASK_WORDS - 1)] >> (mm & 31)) & 1u)) continue;
         }
         const T* kr = Kh + (size_t)j * 64;
         float sc = 0.f;

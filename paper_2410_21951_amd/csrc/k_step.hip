@@ -97,8 +97,9 @@ int step_num_phases(int n_layers) { return 1 + 5 * n_layers + TP_COUNT; }
 // (StepParams::big_min of them) take those (operands staged through LDS and shared by the four waves); smaller ones keep
 // the 64 x 64 units whose waves split the reduction.
 __host__ __device__ inline bool wide_big(int R, int N, int min_units) { return cdiv(R, 128) * cdiv(N, 128) >= min_units; }
-// Attention units of the many-row kernel are whole (sequence, head)s once there is one per compute unit.
-__host__ __device__ inline bool attn_allq(const StepParams& P) { return P.wide && P.D.B * P.D.nH >= P.big_min; }
+// Attention units of the many-row kernel are whole (sequence, head)s once there is one per compute unit
+// (up to four query tiles: one per wave).
+__host__ __device__ inline bool attn_allq(const StepParams& P) { return P.wide && P.D.M <= 64 && P.D.B * P.D.nH >= P.big_min; }
 __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     const Dims& D = P.D;
     const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
@@ -1069,7 +1070,10 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     const int qrow = b * D.M + node;
     const bf16x8_t Q0 = __builtin_bit_cast(bf16x8_t, ldg4(ql + toff(qrow, h * 64 + 8 * gq, D.d >> 5)));
     const bf16x8_t Q1 = __builtin_bit_cast(bf16x8_t, ldg4(ql + toff(qrow, h * 64 + 32 + 8 * gq, D.d >> 5)));
-    const uint4 mw = ldg4(s.t_mask[P.table] + (size_t)node * MASK_WORDS);
+    // table 1 is the causal chunk of the prefill (row n sees rows 0..n): no mask words are read for
+    // it, a chunk may have more rows than the mask table has entries
+    const bool causal = P.table == 1;
+    const uint4 mw = ldg4(s.t_mask[0] + (size_t)(causal ? 0 : node) * MASK_WORDS);
     const uint32_t mword[4] = {mw.x, mw.y, mw.z, mw.w};
     bf16_t* att = (bf16_t*)s.att + (size_t)layer * s.act_stride;
     if (n_rows == 0) {
@@ -1156,7 +1160,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
                 bool okj = key < L;
                 if (!okj && key < T) {
                     const int mm = key - L;
-                    okj = (mword[mm >> 5] >> (mm & 31)) & 1u;
+                    okj = causal ? mm <= node : (mword[(mm >> 5) & 3] >> (mm & 31)) & 1u;
                 }
                 okm |= okj ? (1u << j) : 0u;
             }

@@ -28,7 +28,7 @@ class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "speech_vocab", "text_vocab",
         "n_draft_heads", "max_positions", "max_batch", "max_tree_nodes", "dtype", "ignore_eos",
-        "reserved")]
+        "prefill_chunk")]
 
 
 class _Tree(C.Structure):
@@ -119,12 +119,12 @@ def build_tree(acc, n_nodes):
     return TreeArrays(parent[:n.value], rank[:n.value])
 
 
-def make_config(model, max_batch, max_tree_nodes, ignore_eos=False):
+def make_config(model, max_batch, max_tree_nodes, ignore_eos=False, prefill_chunk=0):
     """model: any object or dict with the fields of the model description."""
     g = (lambda k: model[k]) if isinstance(model, dict) else (lambda k: getattr(model, k))
     return _Config(g("n_layers"), g("d_model"), g("n_heads"), g("head_dim"), g("d_ffn"), g("speech_vocab"),
                    g("text_vocab"), g("n_draft_heads"), g("max_positions"), max_batch, max_tree_nodes,
-                   {"fp32": 0, "bf16": 1}[g("dtype")], int(bool(ignore_eos)), 0)
+                   {"fp32": 0, "bf16": 1}[g("dtype")], int(bool(ignore_eos)), int(prefill_chunk))
 
 
 def blob_order(cfg):
@@ -147,12 +147,12 @@ def pack_blob(cfg, weights):
 class Vadusa:
     """One decoding context on the current CUDA/HIP device."""
 
-    def __init__(self, model, max_batch=1, max_tree_nodes=64, ignore_eos=False, stream=None):
+    def __init__(self, model, max_batch=1, max_tree_nodes=64, ignore_eos=False, stream=None, prefill_chunk=0):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the VADUSA step has no CPU fallback")
         self.lib = load_library()
-        self.cfg = make_config(model, max_batch, max_tree_nodes, ignore_eos)
+        self.cfg = make_config(model, max_batch, max_tree_nodes, ignore_eos, prefill_chunk)
         msg = C.create_string_buffer(256)
         rc = self.lib.vadusa_config_check(C.byref(self.cfg), msg, 256)
         if rc:

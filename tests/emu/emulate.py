@@ -56,9 +56,9 @@ def install(libpath, fill=0xAB):
     lib.emu_alloc.argtypes = [C.c_size_t, C.c_int]
     V._lib = lib
 
-    def init(self, model, max_batch=1, max_tree_nodes=64, ignore_eos=False, stream=None):
+    def init(self, model, max_batch=1, max_tree_nodes=64, ignore_eos=False, stream=None, prefill_chunk=0):
         self.lib = lib
-        self.cfg = V.make_config(model, max_batch, max_tree_nodes, ignore_eos)
+        self.cfg = V.make_config(model, max_batch, max_tree_nodes, ignore_eos, prefill_chunk)
         msg = C.create_string_buffer(256)
         rc = lib.vadusa_config_check(C.byref(self.cfg), msg, 256)
         if rc:

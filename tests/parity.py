@@ -94,14 +94,15 @@ class Stats:
 
 
 class Lockstep:
-    def __init__(self, cfg, weights, text, prompt, max_tree_nodes, ignore_eos=True):
+    def __init__(self, cfg, weights, text, prompt, max_tree_nodes, ignore_eos=True, prefill_chunk=0):
         self.cfg = cfg
         self.model = O.Model(cfg, weights)
         self.text, self.prompt = text, prompt
         self.B = len(text)
         self.ignore_eos = ignore_eos
         self.tol = TOL[cfg.dtype]
-        self.dev = Vadusa(cfg, max_batch=self.B, max_tree_nodes=max_tree_nodes, ignore_eos=ignore_eos)
+        self.dev = Vadusa(cfg, max_batch=self.B, max_tree_nodes=max_tree_nodes, ignore_eos=ignore_eos,
+                          prefill_chunk=prefill_chunk)
         self.dev.load_weights(weights)
         self.stats = Stats()
         self.sts = [O.prefill(self.model, t, p) for t, p in zip(text, prompt)]

@@ -53,7 +53,11 @@ def test_config_check_and_sizes(lib):
     assert lib.vadusa_config_check(C.byref(_cfg(m, dtype=2)), msg, 256) == -1
     assert lib.vadusa_config_check(C.byref(_cfg(m, n_draft_heads=9)), msg, 256) == -2
     assert lib.vadusa_config_check(C.byref(_cfg(m, max_tree_nodes=129)), msg, 256) == -2
-    assert lib.vadusa_config_check(C.byref(_cfg(m, reserved=1)), msg, 256) == -1
+    assert lib.vadusa_config_check(C.byref(_cfg(m, prefill_chunk=-1)), msg, 256) == -1
+    assert lib.vadusa_config_check(C.byref(_cfg(m, prefill_chunk=1025)), msg, 256) == -2
+    assert lib.vadusa_config_check(C.byref(_cfg(m, prefill_chunk=256)), msg, 256) == 0
+    small, big = _cfg(m), _cfg(m, prefill_chunk=256)
+    assert lib.vadusa_arena_bytes(C.byref(big)) > lib.vadusa_arena_bytes(C.byref(small))
     assert lib.vadusa_config_check(None, msg, 256) == -1
     assert lib.vadusa_arena_bytes(C.byref(_cfg(m, head_dim=32))) == 0
 

@@ -427,3 +427,59 @@ def test_many_row_unit_kinds_on_ragged_shapes(monkeypatch):
     s = ls.stats
     _say(f"  compared {s.compared}/{s.steps} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} logit err {s.max_logit_err:.2e}")
     assert s.compared >= 2
+
+
+@pytest.mark.parametrize("dtype,chunk", [("fp32", 160), ("bf16", 160), ("bf16", 512)])
+def test_prefill_in_long_passes(dtype, chunk):
+    """vadusa_config.prefill_chunk: the prompt runs through the decoder in passes of up to that many
+    rows per sequence (more than the 128 rows a tree can have; from 256 rows on in the many-row
+    kernel), ragged batch, then ordinary steps."""
+    cfg = small_cfg(dtype, maxpos=512)
+    _say(f"prefill passes of {chunk} rows, {dtype}")
+    W = make_weights(cfg, 23, std=STD[dtype], ln_jitter=0.1)
+    rng = np.random.default_rng(51)
+    text, prompt = rand_tokens(cfg, rng, 2, (5, 40), (150, 330))
+    tree = make_tree(24, (3, 3, 2))
+    ls = _lock(cfg, W, text, prompt, 24, prefill_chunk=chunk)      # the constructor checks the prefill against the oracle
+    for tau in (1, 3):
+        ls.step(tree, tau)
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    _say(f"  lengths {[len(t) + len(p) for t, p in zip(text, prompt)]} compared {s.compared}/{s.steps} "
+         f"logit err {s.max_logit_err:.2e} kv err {s.max_kv_err:.2e}")
+    assert s.compared >= 1
+
+
+def test_valle_b1_prefill_in_one_pass(valle):
+    """Configuration 2 at full size with prefill_chunk = 512: the 289-token prompt is one pass of the
+    many-row kernel; then steps as usual."""
+    wl, W = valle
+    text, prompt = make_tokens(wl)
+    tree = make_tree(wl.tree_nodes, wl.topk_caps)
+    _say("valle_b1, prefill in one pass")
+    ls = _lock(wl.model, W, text, prompt, wl.tree_nodes, prefill_chunk=512)
+    for tau in (1, 4):
+        ls.step(tree, tau)
+    ls.check_kv(layers=[0, 6, 11])
+    s = ls.stats
+    _say(f"  compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e} kv err {s.max_kv_err:.2e}")
+    assert s.compared >= 1
+
+
+def test_many_row_kernel_with_128_node_tree(monkeypatch):
+    """A 128-node tree has eight query tiles per head: the whole-head attention unit (four waves, one
+    query tile each) must not be picked for it even where every other condition holds."""
+    monkeypatch.setenv("VADUSA_BIG_MIN_UNITS", "1")
+    cfg = small_cfg("bf16", layers=2, d=128, heads=4, V=300, maxpos=384)
+    _say("many-row kernel, 128-node tree")
+    W = make_weights(cfg, 29, std=STD["bf16"])
+    rng = np.random.default_rng(53)
+    text, prompt = rand_tokens(cfg, rng, 2, (3, 9), (40, 75))
+    tree = make_tree(128, (10, 10, 10, 10))
+    ls = _lock(cfg, W, text, prompt, 128)
+    for tau in (1, 4):
+        ls.step(tree, tau)
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    _say(f"  compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e}")
+    assert s.compared >= 1
