@@ -223,6 +223,22 @@ def main():
     out["ar_step"] = {"us_per_step": ar_us, "steps": n_ar, "tree_step_over_ar_step": ms_step * 1e3 / ar_us,
                       "speedup_at_paper_accepted_len": {"tau1_acc3.00": 3.00 * ar_us / (ms_step * 1e3),
                                                         "tau3_acc3.87": 3.87 * ar_us / (ms_step * 1e3)}}
+    # What a plain copy kernel reaches on this GPU (1 GiB read + 1 GiB written per launch): the
+    # measured ceiling next to the nominal 8 TB/s
+    src = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device="cuda").fill_(1.0)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 2 * src.numel() * 4 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del src, dst
+    out["roofline"]["copy_kernel_gbs"] = copy_gbs
+    out["roofline"]["hbm_gbs_over_copy_kernel"] = achieved / copy_gbs
     # Prefill (the call synchronises, so host time is the measure): in passes of max_tree_nodes rows
     # (the default) and in passes of up to 512 rows per sequence (vadusa_config.prefill_chunk), which
     # run in the many-row kernel from 256 rows on.

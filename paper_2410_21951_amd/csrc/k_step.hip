@@ -1042,7 +1042,7 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
 // (sequence, head); wave w takes query tile w over all key blocks, so the four waves read the
 // same K / V blocks (once from L2, then from the compute unit's L1), nothing is merged across
 // waves, and the result goes from the accumulators straight to memory.
-template <bool ALLQ>
+template <bool ALLQ, bool CAUSAL>
 __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     const int layer = (__builtin_amdgcn_readfirstlane(ph_) - 1) / 5, u = __builtin_amdgcn_readfirstlane(u_);
     const StepParams& P = sP;
@@ -1070,10 +1070,11 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     const int qrow = b * D.M + node;
     const bf16x8_t Q0 = __builtin_bit_cast(bf16x8_t, ldg4(ql + toff(qrow, h * 64 + 8 * gq, D.d >> 5)));
     const bf16x8_t Q1 = __builtin_bit_cast(bf16x8_t, ldg4(ql + toff(qrow, h * 64 + 32 + 8 * gq, D.d >> 5)));
-    // table 1 is the causal chunk of the prefill (row n sees rows 0..n): no mask words are read for
-    // it, a chunk may have more rows than the mask table has entries
-    const bool causal = P.table == 1;
-    const uint4 mw = ldg4(s.t_mask[0] + (size_t)(causal ? 0 : node) * MASK_WORDS);
+    // CAUSAL: the rows are a causal pass of the prefill (row n sees rows 0..n): no mask words are
+    // read, a pass may have more rows than the mask table has entries.  It is a separate kernel
+    // so that the step kernel's attention carries no trace of it.
+    uint4 mw = make_uint4(0, 0, 0, 0);
+    if constexpr (!CAUSAL) mw = ldg4(s.t_mask[P.table] + (size_t)node * MASK_WORDS);
     const uint32_t mword[4] = {mw.x, mw.y, mw.z, mw.w};
     bf16_t* att = (bf16_t*)s.att + (size_t)layer * s.act_stride;
     if (n_rows == 0) {
@@ -1160,7 +1161,8 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
                 bool okj = key < L;
                 if (!okj && key < T) {
                     const int mm = key - L;
-                    okj = causal ? mm <= node : (mword[(mm >> 5) & 3] >> (mm & 31)) & 1u;
+                    if constexpr (CAUSAL) okj = mm <= node;
+                    else okj = (mword[mm >> 5] >> (mm & 31)) & 1u;
                 }
                 okm |= okj ? (1u << j) : 0u;
             }
@@ -1266,7 +1268,7 @@ __device__ __forceinline__ void topk_unit(int u_) { const int u = __builtin_amdg
 // ---------------------------------------------------------------------------
 // one unit of one phase: dispatch to the unit's own function
 // ---------------------------------------------------------------------------
-template <bool WIDE>
+template <bool WIDE, bool CAUSAL>
 __device__ __forceinline__ void run_unit(int ph, int u) {
     const StepParams& P = sP;
     const Dims& D = P.D;
@@ -1292,8 +1294,8 @@ __device__ __forceinline__ void run_unit(int ph, int u) {
     switch (kind) {
     case K_EMBED: embed_unit(u); break;
     case K_ATTN:
-        if constexpr (WIDE) { if (attn_allq(P)) attn_unit<true>(ph, u); else attn_unit<false>(ph, u); }
-        else attn_unit<false>(ph, u);
+        if constexpr (WIDE) { if (attn_allq(P)) attn_unit<true, CAUSAL>(ph, u); else attn_unit<false, CAUSAL>(ph, u); }
+        else attn_unit<false, CAUSAL>(ph, u);
         break;
     case K_GEMM4: gemm_unit<4>(ph, u); break;
     case K_GEMM1: if constexpr (!WIDE) gemm_unit<1>(ph, u); break;
@@ -1306,9 +1308,10 @@ __device__ __forceinline__ void run_unit(int ph, int u) {
     }
 }
 
-// Two kernels from one body: the ordinary one (up to 255 rows) and the one whose layer maps and
-// base head run as 64 x 64 units (StepParams::wide); each carries only the unit code it uses.
-template <bool WIDE>
+// Four kernels from one body: the ordinary one (up to 255 rows) and the one whose layer maps and
+// base head run as 64 x 64 or 128 x 128 units (StepParams::wide), each for tree rows and for the
+// causal passes of the prefill; each carries only the unit code it uses.
+template <bool WIDE, bool CAUSAL>
 __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
     {
         const uint32_t* src = (const uint32_t*)&Parg;
@@ -1327,7 +1330,7 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
         tp(ph, 0);
         const int nu = ph == 0 ? P.D.B * P.D.M : ph < H ? s_nu[(ph - 1) % 5] : s_nu[5 + ph - H];
         for (int u = blockIdx.x; u < nu; u += gridDim.x) {
-            run_unit<WIDE>(ph, u);
+            run_unit<WIDE, CAUSAL>(ph, u);
             __syncthreads();
         }
         tp(ph, 1);
@@ -1342,21 +1345,25 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
 void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err) {
     static bool once = false;
     if (!once) {
-        (void)hipFuncSetAttribute((const void*)k_step<true>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_WIDE_LDS_BYTES);
-        (void)hipFuncSetAttribute((const void*)k_step<false>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_WIDE_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_WIDE_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS_BYTES);
         once = true;
     }
     *err = hipSuccess;
     const size_t lds = p.wide ? ST_WIDE_LDS_BYTES : ST_LDS_BYTES;
-    void (*kfn)(StepParams) = p.wide ? k_step<true> : k_step<false>;
+    // four kernels from one body: few or many rows, tree (table 0) or causal pass of the prefill (table 1)
+    void (*kfn)(StepParams) = p.wide ? (p.table == 1 ? k_step<true, true> : k_step<true, false>)
+                                     : (p.table == 1 ? k_step<false, true> : k_step<false, false>);
     if (p.persistent) {
         // every workgroup of the grid must fit on the GPU at once
         static int resident = -1;
         if (resident < 0) {
             int nb = 0;
             int nw = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_step<false>, 256, ST_LDS_BYTES) != hipSuccess) nb = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nw, k_step<true>, 256, ST_WIDE_LDS_BYTES) != hipSuccess) nw = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_step<false, false>, 256, ST_LDS_BYTES) != hipSuccess) nb = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nw, k_step<true, true>, 256, ST_WIDE_LDS_BYTES) != hipSuccess) nw = 0;
             nb = std::min(nb, nw);
             resident = nb;
         }
