@@ -74,7 +74,7 @@ def load_library(path=None):
     global _lib
     if _lib is not None and path is None:
         return _lib
-    p = path or _LIB_PATH
+    p = path or os.environ.get("VADUSA_LIB") or _LIB_PATH   # VADUSA_LIB: another build of the same library
     if not os.path.exists(p):
         raise FileNotFoundError(f"{p} not found: build it with `python -m paper_2410_21951_amd.build`")
     lib = C.CDLL(p)
