@@ -1054,11 +1054,15 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     // one XCD (workgroup i is on XCD i mod 8) and share its L2 for that head's K / V rows
     const int BH = pad8(D.B * D.nH);
     int bh, qt, h, b;
-    if (ALLQ) { bh = u; qt = wave; }
+    // ALLQ: with three or four query tiles a wave takes one; with two, two waves share a tile's key
+    // blocks; with one, all four do (wpq = waves per query tile)
+    const int n_qt = (D.M + 15) >> 4;
+    const int wpq = !ALLQ ? 4 : n_qt >= 3 ? 1 : n_qt == 2 ? 2 : 4;
+    if (ALLQ) { bh = u; qt = wave / wpq; }
     else if ((BH & (BH - 1)) == 0) { bh = u & (BH - 1); qt = u >> __builtin_ctz(BH); }   // no division in the usual case
     else { bh = u % BH; qt = u / BH; }
     if (bh >= D.B * D.nH) return;
-    if (ALLQ && qt * 16 >= D.M) return;   // fewer than four query tiles: this wave has none
+    if (ALLQ && qt * 16 >= D.M) return;   // three query tiles: the fourth wave has none (wpq = 1: no workgroup barrier follows)
     if ((D.nH & (D.nH - 1)) == 0) { h = bh & (D.nH - 1); b = bh >> __builtin_ctz(D.nH); }
     else { h = bh % D.nH; b = bh / D.nH; }
     // everything the unit needs before its first key block is requested at once: row count,
@@ -1111,7 +1115,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
         for (int dt = 0; dt < 4; ++dt) kv[4 + dt] = ldg4(Vh + (size_t)(dt * 16 + c) * D.maxpos + vv);
     };
     uint4 cur[8], nxt[8], nx2[8];   // two blocks in flight behind the one being computed
-    const int blk0 = ALLQ ? 0 : wave, bstep = ALLQ ? 1 : 4;   // the waves split the blocks, or each takes all
+    const int blk0 = ALLQ ? wave % wpq : wave, bstep = ALLQ ? wpq : 4;   // the waves of a query tile split its key blocks
     if (blk0 < nblk) load_block(blk0, cur);
     if (blk0 + bstep < nblk) load_block(blk0 + bstep, nxt);
     for (int blk = blk0; blk < nblk; blk += bstep) {
@@ -1183,7 +1187,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     }
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
-    if (ALLQ) {   // this lane: query c, dimensions dt * 16 + 4 gq .. + 3 of every dt
+    if (ALLQ && wpq == 1) {   // this lane: query c, dimensions dt * 16 + 4 gq .. + 3 of every dt
         const float inv = 1.f / l_run;
         const int nd = qt * 16 + c;
         if (nd < D.M) {
@@ -1205,6 +1209,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) sm_o[(wave * 64 + dt * 16 + 4 * gq + i) * 16 + c] = O[dt][i];
     __syncthreads();
+    if constexpr (!ALLQ)
     {
         const int q = tid >> 4, d0 = (tid & 15) * 4, nd = qt * 16 + q;
         float mstar = sm_m[q];
@@ -1225,6 +1230,37 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
         if (nd < D.M)
             stw64(att + toff(b * D.M + nd, h * 64 + d0, D.d >> 5),
                   (uint64_t)pack_bf16(o[0], o[1]) | ((uint64_t)pack_bf16(o[2], o[3]) << 32));
+    }
+    else {
+        // merge the waves of each query tile (one tile with four waves, or ALLQ: 4 / wpq tiles)
+        const int tiles_here = 4 / wpq;
+        for (int t = 0; t < tiles_here; ++t) {
+            const int q = tid >> 4, d0 = (tid & 15) * 4, w0 = t * wpq;
+            const int nd = t * 16 + q;
+            float mstar = sm_m[w0 * 16 + q];
+#pragma unroll
+            for (int w = 1; w < 4; ++w)
+                if (w < wpq) mstar = fmaxf(mstar, sm_m[(w0 + w) * 16 + q]);
+            float f[4], lsum = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                f[w] = w < wpq ? __expf(sm_m[(w0 + w) * 16 + q] - mstar) : 0.f;
+                if (w < wpq) lsum += f[w] * sm_l[(w0 + w) * 16 + q];
+            }
+            const float inv = 1.f / lsum;
+            float o[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float a = 0.f;
+#pragma unroll
+                for (int w = 0; w < 4; ++w)
+                    if (w < wpq) a += f[w] * sm_o[((w0 + w) * 64 + d0 + j) * 16 + q];
+                o[j] = a * inv;
+            }
+            if (nd < D.M)
+                stw64(att + toff(b * D.M + nd, h * 64 + d0, D.d >> 5),
+                      (uint64_t)pack_bf16(o[0], o[1]) | ((uint64_t)pack_bf16(o[2], o[3]) << 32));
+        }
     }
 }
 
