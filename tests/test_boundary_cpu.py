@@ -140,3 +140,27 @@ def test_build_tree_matches_bruteforce_and_reference_generator():
         build_tree(np.full((2, 3), 1.5, np.float32), 4)
     with pytest.raises(VadusaError):
         build_tree(acc, 500)
+
+
+def test_bench_prices_the_step_as_the_paper_sized_model_implies():
+    """bench.py's algorithmic bytes and flops per step, against the figures that follow from the
+    model sizes of Sec. 3.1.1 (12 layers, d = 1024, FFN 4096, 1025 logits, four draft heads, bf16):
+    302.0 MB of layer weights, 2.1 MB vocabulary map, 16.8 MB draft heads, 48 KiB of K/V per position."""
+    import importlib.util
+    import os
+    spec = importlib.util.spec_from_file_location("bench", os.path.join(os.path.dirname(os.path.dirname(__file__)), "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    m = PRESETS["valle_b1"].model
+    weights = (12 * (4 * 1024 * 1024 + 2 * 1024 * 4096) + 1025 * 1024 + 4 * (1024 * 1024 + 1025 * 1024)) * 2
+    kv = 12 * 2 * 1024 * 2
+    assert kv == 48 * 1024
+    for L in (289, 664, 1039):
+        assert bench.algorithmic_bytes(m, 1, 64, L) == weights + (L + 64) * kv
+    assert abs(bench.algorithmic_bytes(m, 1, 64, 664) / 1e6 - 356.7) < 0.5
+    # 64 rows through the layers and the base head, one row through the draft heads, attention over
+    # L + M/2 keys: 19.5 GFLOP of maps + attention
+    f = bench.algorithmic_flops(m, 1, 64, 664)
+    maps = 2 * 64 * (12 * (4 * 1024 * 1024 + 2 * 1024 * 4096) + 1025 * 1024) + 2 * 4 * (1024 * 1024 + 1025 * 1024)
+    assert abs(f - (maps + 4 * 64 * (664 + 32) * 1024 * 12)) < 1e-6 * f
+    assert 19.4e9 < maps < 19.6e9
