@@ -172,3 +172,24 @@ def test_stochastic_entry_points():
         dev.close()
     assert outs[0] == outs[1] == outs[2]
     assert all(len(o) >= 8 for o in outs[0])
+
+
+def test_stochastic_rule_refuses_vocabularies_beyond_its_lds_row():
+    """The perturbation kernel keeps a row of V + 1 floats in 64 KiB of LDS: a larger vocabulary is
+    refused with VADUSA_ESHAPE before anything runs; the deterministic step still works."""
+    from paper_2410_21951_amd import VadusaError
+    from synth import make_uniforms
+    print("stochastic rule, vocabulary too large", flush=True)
+    cfg = ModelConfig(n_layers=1, d_model=64, n_heads=1, head_dim=64, d_ffn=128, speech_vocab=16400,
+                      text_vocab=20, n_draft_heads=2, max_positions=64, dtype="bf16")
+    W = make_weights(cfg, 5, std=0.05)
+    rng = np.random.default_rng(3)
+    dev = _dev(cfg, max_batch=1, max_tree_nodes=8, ignore_eos=True)
+    dev.load_weights(W)
+    dev.prefill([rng.integers(0, 20, 3).astype(np.int32)], [rng.integers(0, 16400, 9).astype(np.int32)])
+    tree = _tree(make_tree(8, (3, 2)))
+    with pytest.raises(VadusaError) as e:
+        dev.step(tree, 2, sample=(1.0, 0.9, make_uniforms(1, 0, 1, 8, cfg.n_logits)))
+    assert e.value.code == -2
+    assert len(dev.step(tree, 2)[0]) >= 1
+    dev.close()
