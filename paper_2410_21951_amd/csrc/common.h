@@ -122,6 +122,20 @@ __device__ __forceinline__ float wave_max(float v) {
 // read from lanes 0, 16, 32 and 48.  Every lane returns the total; all 64 lanes must be active.
 template <int CTRL>
 __device__ __forceinline__ int dpp_perm(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false); }
+// sums over the 4 lanes of a quad and over the 16 lanes of a row; every lane gets the total.  The
+// additions pair the same values as an xor-butterfly of __shfl_xor would, so the results are the same bits.
+__device__ __forceinline__ float quad_sum(float v) {
+    v += __int_as_float(dpp_perm<0xB1>(__float_as_int(v)));
+    v += __int_as_float(dpp_perm<0x4E>(__float_as_int(v)));
+    return v;
+}
+__device__ __forceinline__ float pair_sum(float v) { return v + __int_as_float(dpp_perm<0xB1>(__float_as_int(v))); }
+__device__ __forceinline__ float row16_sum(float v) {
+    v = quad_sum(v);
+    v += __int_as_float(dpp_perm<0x141>(__float_as_int(v)));
+    v += __int_as_float(dpp_perm<0x140>(__float_as_int(v)));
+    return v;
+}
 __device__ __forceinline__ int wave_sum_i_dpp(int v) {
     v += dpp_perm<0xB1>(v);    // quad_perm [1,0,3,2]
     v += dpp_perm<0x4E>(v);    // quad_perm [2,3,0,1]

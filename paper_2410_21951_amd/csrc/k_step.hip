@@ -230,14 +230,12 @@ __device__ __forceinline__ void embed_unit(int r_) {
         v[3] = bf2f((bf16_t)(ev.y >> 16)) + bf2f((bf16_t)(pv.y >> 16));
         if (!valid) v[0] = v[1] = v[2] = v[3] = 0.f;
         float sum = v[0] + v[1] + v[2] + v[3];
-        sum += __shfl_xor(sum, 1, 64);
-        sum += __shfl_xor(sum, 2, 64);
+        sum = quad_sum(sum);
         const float mean = sum * (1.f / 16.f);
         float m2 = 0.f;
 #pragma unroll
         for (int j = 0; j < 4; ++j) { const float t = v[j] - mean; m2 += t * t; }
-        m2 += __shfl_xor(m2, 1, 64);
-        m2 += __shfl_xor(m2, 2, 64);
+        m2 = quad_sum(m2);
         stwf2(x + c0, v[0], v[1]);
         stwf2(x + c0 + 2, v[2], v[3]);
         stw64(xb + toff(r, c0, D.d >> 5), (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32));
@@ -502,9 +500,9 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
             if ((tid & 3) + 4 * j < tiles) { s1 += sv[j].x; s2 += sv[j].y; s3 += sv[j].x * sv[j].x; }
     }
     if (g.stats) {
-        s1 += __shfl_xor(s1, 1, 64); s1 += __shfl_xor(s1, 2, 64);
-        s2 += __shfl_xor(s2, 1, 64); s2 += __shfl_xor(s2, 2, 64);
-        s3 += __shfl_xor(s3, 1, 64); s3 += __shfl_xor(s3, 2, 64);
+        s1 = quad_sum(s1);
+        s2 = quad_sum(s2);
+        s3 = quad_sum(s3);
         if (do_stats && (tid & 3) == 0) {
             // mean of tile means; M2 = sum M2_t + 16 sum (mean_t - mean)^2
             const float mean = s1 / tiles;
@@ -599,12 +597,10 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
             if (ok && !(col & 1)) stw32(g.out + toff(r, n, g.N >> 5), pack_bf16(xn, nb));
         }
         float sum = xn;
-#pragma unroll
-        for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 64);
+        sum = row16_sum(sum);
         const float mean = sum * (1.f / 16.f);
         float m2 = (xn - mean) * (xn - mean);
-#pragma unroll
-        for (int o = 1; o < 16; o <<= 1) m2 += __shfl_xor(m2, o, 64);
+        m2 = row16_sum(m2);
         if (ok && col == 0) stwf2(g.stats_out + ((size_t)nt * g.R + r) * 2, mean, m2);
     }
 }
@@ -645,10 +641,10 @@ __device__ __forceinline__ void wide_store(const GemmD& g, int r, int n0, int ti
             stwf2(s.x + (size_t)r * g.N + n0 + 2, x2, x3);
             stw64(g.out + toff(r, n0, g.N >> 5), (uint64_t)pack_bf16(x0, x1) | ((uint64_t)pack_bf16(x2, x3) << 32));
             float sum = x0 + x1 + x2 + x3;
-            sum += __shfl_xor(sum, 1, 64); sum += __shfl_xor(sum, 2, 64);
+            sum = quad_sum(sum);
             const float mean = sum * (1.f / 16.f);
             float m2 = (x0 - mean) * (x0 - mean) + (x1 - mean) * (x1 - mean) + (x2 - mean) * (x2 - mean) + (x3 - mean) * (x3 - mean);
-            m2 += __shfl_xor(m2, 1, 64); m2 += __shfl_xor(m2, 2, 64);
+            m2 = quad_sum(m2);
             if ((tid & 3) == 0) stwf2(g.stats_out + ((size_t)tile * g.R + r) * 2, mean, m2);
             break;
         }
@@ -780,9 +776,9 @@ __device__ __forceinline__ void gemm_big_impl(const GemmD& g, int nt, int row0) 
                     if (t0 + 2 * j < tiles) { s1 += v[j].x; s2 += v[j].y; s3 += v[j].x * v[j].x; }
             }
         }
-        s1 += __shfl_xor(s1, 1, 64);
-        s2 += __shfl_xor(s2, 1, 64);
-        s3 += __shfl_xor(s3, 1, 64);
+        s1 = pair_sum(s1);
+        s2 = pair_sum(s2);
+        s3 = pair_sum(s3);
         if ((tid & 1) == 0) {
             const float mean = s1 / tiles;
             const float m2 = s2 + 16.f * fmaxf(s3 - tiles * mean * mean, 0.f);
@@ -987,9 +983,9 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
         }
     }
     if (do_stats) {
-        s1 += __shfl_xor(s1, 1, 64); s1 += __shfl_xor(s1, 2, 64);
-        s2 += __shfl_xor(s2, 1, 64); s2 += __shfl_xor(s2, 2, 64);
-        s3 += __shfl_xor(s3, 1, 64); s3 += __shfl_xor(s3, 2, 64);
+        s1 = quad_sum(s1);
+        s2 = quad_sum(s2);
+        s3 = quad_sum(s3);
         if ((tid & 3) == 0) {
             const float mean = s1 / tiles;
             const float m2 = s2 + 16.f * fmaxf(s3 - tiles * mean * mean, 0.f);

@@ -142,15 +142,18 @@ long long emu_clock() { return ++g_clock; }
 
 // ---- pairwise exchange for __shfl_xor ----
 struct Slot {
-    std::atomic<uint64_t> seq[6];
-    uint64_t cnt[6];
-    uint32_t val[6][4];
+    std::atomic<uint64_t> seq[8];
+    uint64_t cnt[8];
+    uint32_t val[8][4];
 };
 static Slot g_slot[MAXT];
 
 uint32_t emu_shfl_xor32(uint32_t v, int mask) {
-    if (mask <= 0 || mask >= 64 || (mask & (mask - 1))) { fprintf(stderr, "[emu] shfl_xor mask %d\n", mask); abort(); }
-    const int bit = __builtin_ctz(mask), me = t_id, other = me ^ mask;
+    // one exchange channel per mask: the powers of two, and 7 / 15 (the mirrored half row / row of the
+    // DPP permutations, which are the exchanges i <-> i ^ 7 and i <-> i ^ 15)
+    const bool pow2 = mask > 0 && mask < 64 && !(mask & (mask - 1));
+    if (!pow2 && mask != 7 && mask != 15) { fprintf(stderr, "[emu] shfl_xor mask %d\n", mask); abort(); }
+    const int bit = pow2 ? __builtin_ctz(mask) : mask == 7 ? 6 : 7, me = t_id, other = me ^ mask;
     Slot& a = g_slot[me];
     Slot& b = g_slot[other];
     const uint64_t k = a.cnt[bit]++;

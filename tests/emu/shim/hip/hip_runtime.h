@@ -129,19 +129,19 @@ static inline int atomicAdd(int* p, int v) { return __atomic_fetch_add(p, v, __A
 #define __builtin_amdgcn_readfirstlane(x) (x)
 // every lane reads lane l of its wave
 #define __builtin_amdgcn_readlane(v, l) (EMU_MARK, (int)emu_shfl_idx32((uint32_t)(v), (l)))
-// DPP lane permutations used by the kernels (all lanes active, full row and bank masks):
-// quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror
-static inline int emu_dpp_src(int lane, int ctrl) {
+// DPP lane permutations used by the kernels (full row and bank masks): quad_perm [1,0,3,2],
+// quad_perm [2,3,0,1], row_half_mirror, row_mirror are the pairwise exchanges lane ^ 1, ^ 2, ^ 7, ^ 15
+static inline int emu_dpp_mask(int ctrl) {
     switch (ctrl) {
-    case 0xB1: return lane ^ 1;
-    case 0x4E: return lane ^ 2;
-    case 0x141: return (lane & ~7) | (7 - (lane & 7));
-    case 0x140: return (lane & ~15) | (15 - (lane & 15));
+    case 0xB1: return 1;
+    case 0x4E: return 2;
+    case 0x141: return 7;
+    case 0x140: return 15;
     default: __builtin_trap();
     }
 }
 #define __builtin_amdgcn_update_dpp(old, v, ctrl, rm, bm, bc) \
-    (EMU_MARK, (int)emu_shfl_idx32((uint32_t)(v), emu_dpp_src((int)(threadIdx.x & 63), (ctrl))))
+    (EMU_MARK, (int)emu_shfl_xor32((uint32_t)(v), emu_dpp_mask(ctrl)))
 
 // ---- math / bits ----
 static inline float __uint_as_float(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
