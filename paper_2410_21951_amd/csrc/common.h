@@ -136,6 +136,35 @@ __device__ __forceinline__ float row16_sum(float v) {
     v += __int_as_float(dpp_perm<0x140>(__float_as_int(v)));
     return v;
 }
+// Combining a value with the ones 16 and 32 lanes away (the four rows of a wave), every lane gets
+// the result.  gfx950 swaps rows between two registers in the vector ALU: with both operands the
+// same value, one register then holds rows {0, 0, 2, 2} and the other rows {1, 1, 3, 3} (16-lane
+// swap), or halves {lo, lo} and {hi, hi} (32-lane swap), and combining the two registers lane by
+// lane is the exchange, without a trip through the LDS permute unit.
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef unsigned int vadusa_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float rows_max(float v) {
+    vadusa_u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+__device__ __forceinline__ float rows_sum(float v) {
+    vadusa_u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(r.x) + __uint_as_float(r.y);
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+#else
+__device__ __forceinline__ float rows_max(float v) {
+    v = fmaxf(v, __shfl_xor(v, 16, 64));
+    return fmaxf(v, __shfl_xor(v, 32, 64));
+}
+__device__ __forceinline__ float rows_sum(float v) {
+    v += __shfl_xor(v, 16, 64);
+    return v + __shfl_xor(v, 32, 64);
+}
+#endif
 __device__ __forceinline__ int wave_sum_i_dpp(int v) {
     v += dpp_perm<0xB1>(v);    // quad_perm [1,0,3,2]
     v += dpp_perm<0x4E>(v);    // quad_perm [2,3,0,1]

@@ -1141,8 +1141,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
                 sc[j] = (okm >> j) & 1u ? sv : -1e30f;
                 mx = fmaxf(mx, sc[j]);
             }
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            mx = rows_max(mx);
             m_new = fmaxf(m_run, mx);
             corr = __expf(m_run - m_new);
 #pragma unroll
@@ -1181,8 +1180,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) { cur[i] = nxt[i]; nxt[i] = nx2[i]; }
     }
-    l_run += __shfl_xor(l_run, 16, 64);
-    l_run += __shfl_xor(l_run, 32, 64);
+    l_run = rows_sum(l_run);
     if (ALLQ && wpq == 1) {   // this lane: query c, dimensions dt * 16 + 4 gq .. + 3 of every dt
         const float inv = 1.f / l_run;
         const int nd = qt * 16 + c;
