@@ -12,6 +12,46 @@ __device__ __forceinline__ bool before(float va, int ia, float vb, int ib) {
     return va > vb || (va == vb && ia < ib);
 }
 
+// Best (value, id) pair of a wave under the order above; every lane gets it.  Inside a row of 16
+// lanes by DPP permutations (after each step twice as many lanes agree, so the mirrored partners
+// serve as well as the xor partners), across the four rows by the row-swap instructions.
+template <int CTRL>
+__device__ __forceinline__ void argbest_step(float& bv, int& bi) {
+    const float ov = __int_as_float(dpp_perm<CTRL>(__float_as_int(bv)));
+    const int oi = dpp_perm<CTRL>(bi);
+    if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+}
+__device__ __forceinline__ void row16_argbest(float& bv, int& bi) {
+    argbest_step<0xB1>(bv, bi);
+    argbest_step<0x4E>(bv, bi);
+    argbest_step<0x141>(bv, bi);
+    argbest_step<0x140>(bv, bi);
+}
+__device__ __forceinline__ void wave_argbest(float& bv, int& bi) {
+    row16_argbest(bv, bi);
+#if defined(__HIP_DEVICE_COMPILE__)
+    {
+        const vadusa_u32x2 rv = __builtin_amdgcn_permlane16_swap(__float_as_uint(bv), __float_as_uint(bv), false, false);
+        const vadusa_u32x2 ri = __builtin_amdgcn_permlane16_swap((unsigned)bi, (unsigned)bi, false, false);
+        const bool x = before(__uint_as_float(rv.x), (int)ri.x, __uint_as_float(rv.y), (int)ri.y);
+        bv = __uint_as_float(x ? rv.x : rv.y); bi = (int)(x ? ri.x : ri.y);
+    }
+    {
+        const vadusa_u32x2 rv = __builtin_amdgcn_permlane32_swap(__float_as_uint(bv), __float_as_uint(bv), false, false);
+        const vadusa_u32x2 ri = __builtin_amdgcn_permlane32_swap((unsigned)bi, (unsigned)bi, false, false);
+        const bool x = before(__uint_as_float(rv.x), (int)ri.x, __uint_as_float(rv.y), (int)ri.y);
+        bv = __uint_as_float(x ? rv.x : rv.y); bi = (int)(x ? ri.x : ri.y);
+    }
+#else
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+#endif
+}
+
 // Block-wide arg-best under the order above, restricted to entries that come
 // strictly after (pv, pi).  Every thread returns the winner.  256 threads.
 __device__ inline int block_argbest(const float* __restrict__ z, int n, float pv, int pi, float* best_val) {
@@ -29,12 +69,7 @@ __device__ inline int block_argbest(const float* __restrict__ z, int n, float pv
             if (v < n && before(pv, pi, zv[j], v) && before(zv[j], v, bv, bi)) { bv = zv[j]; bi = v; }
         }
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const float ov = __shfl_xor(bv, o, 64);
-        const int oi = __shfl_xor(bi, o, 64);
-        if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-    }
+    wave_argbest(bv, bi);
     __syncthreads();   // protects sv/si against the previous call's readers
     if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
     __syncthreads();
@@ -60,7 +95,7 @@ __device__ inline int dev_edge(const Dims& D, const DevState& s, int b, int n, i
 #pragma unroll
         for (int q = 0; q < 17; ++q) cnt += (v0 + 64 * q < D.V1 && before(zv[q], v0 + 64 * q, zt, t)) ? 1 : 0;
     }
-    return wave_sum_i(cnt) < tau;
+    return wave_sum_i_dpp(cnt) < tau;
 }
 
 // Sec. 2.3's choice from the edge decisions in s_edge (LDS, complete and visible on entry):
@@ -166,7 +201,7 @@ __device__ inline void dev_accept(const Dims& D, const DevState& s, int b, int t
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
             const int n = wave + 4 * (j0 + e);
-            const int total = wave_sum_i(cnt[e]);
+            const int total = wave_sum_i_dpp(cnt[e]);
             if (j0 + e < nj && lane == 0) {
                 const int edge = n == 0 ? 1 : (total < tau);
                 s_edge[n] = edge;   // stored to memory after the loop: a store inside it would
@@ -232,7 +267,7 @@ __device__ inline void dev_finalize(const Dims& D, const DevState& s, int b, int
                 xv[2 * j + 1] = i < D.d ? ldcf(xr + i + 1) : 0.f;
                 sum += xv[2 * j] + xv[2 * j + 1];
             }
-            sum = wave_sum(sum);
+            sum = wave_sum_dpp(sum);
             if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = sum;
             __syncthreads();
             const float mu = (s_red[0] + s_red[1] + s_red[2] + s_red[3]) / D.d;
@@ -242,7 +277,7 @@ __device__ inline void dev_finalize(const Dims& D, const DevState& s, int b, int
                 const int i = threadIdx.x * 2 + 512 * j;
                 if (i < D.d) { const float t0 = xv[2 * j] - mu, t1 = xv[2 * j + 1] - mu; sq += t0 * t0 + t1 * t1; }
             }
-            sq = wave_sum(sq);
+            sq = wave_sum_dpp(sq);
             if ((threadIdx.x & 63) == 0) s_red[4 + (threadIdx.x >> 6)] = sq;
             __syncthreads();
             const float rstd = rsqrtf((s_red[4] + s_red[5] + s_red[6] + s_red[7]) / D.d + LN_EPS);
@@ -258,13 +293,13 @@ __device__ inline void dev_finalize(const Dims& D, const DevState& s, int b, int
         } else {
         float sum = 0.f;
         for (int i = threadIdx.x; i < D.d; i += 256) sum += ldcf(xr + i);
-        sum = wave_sum(sum);
+        sum = wave_sum_dpp(sum);
         if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = sum;
         __syncthreads();
         const float mu = (s_red[0] + s_red[1] + s_red[2] + s_red[3]) / D.d;
         float sq = 0.f;
         for (int i = threadIdx.x; i < D.d; i += 256) { const float t = ldcf(xr + i) - mu; sq += t * t; }
-        sq = wave_sum(sq);
+        sq = wave_sum_dpp(sq);
         if ((threadIdx.x & 63) == 0) s_red[4 + (threadIdx.x >> 6)] = sq;
         __syncthreads();
         const float rstd = rsqrtf((s_red[4] + s_red[5] + s_red[6] + s_red[7]) / D.d + LN_EPS);
@@ -430,12 +465,7 @@ __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) 
             const int v = threadIdx.x + 256 * j;
             if (v < D.V1 && before(zr[j], v, lv, li)) { lv = zr[j]; li = v; }
         }
-#pragma unroll
-        for (int o = 1; o < 16; o <<= 1) {   // best of each group of 16 lanes
-            const float ov = __shfl_xor(lv, o, 64);
-            const int oi = __shfl_xor(li, o, 64);
-            if (before(ov, oi, lv, li)) { lv = ov; li = oi; }
-        }
+        row16_argbest(lv, li);   // best of each group of 16 lanes
         if ((threadIdx.x & 15) == 0) { g_v[threadIdx.x >> 4] = lv; g_i[threadIdx.x >> 4] = li; }
         if (threadIdx.x == 0) c_n = 0;
         __syncthreads();
