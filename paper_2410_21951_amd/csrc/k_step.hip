@@ -593,7 +593,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_) {
             stwf(s.x + (size_t)r * g.N + n, xn);
         }
         {
-            const float nb = __shfl_down(xn, 1, 64);   // pair of columns -> one 32-bit store
+            const float nb = __int_as_float(dpp_perm<0xB1>(__float_as_int(xn)));   // the neighbouring column (used by even columns): a pair -> one 32-bit store
             if (ok && !(col & 1)) stw32(g.out + toff(r, n, g.N >> 5), pack_bf16(xn, nb));
         }
         float sum = xn;
