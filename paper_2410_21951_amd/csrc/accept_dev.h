@@ -364,10 +364,10 @@ __device__ inline void dev_commit_kv(const Dims& D, const DevState& s, int layer
 
 // Draft list of head i, sequence b: the VADUSA_MAX_TOPK best ids of its logits,
 // descending, equal logits: lower id first (Sec. 2.1).
-// Up to 4096 logits sit in registers (16 per thread).  The 256 threads form 16 groups of 16
-// lanes; the 16 group maxima are 16 distinct entries, so the 16th best entry overall is not
-// after the last of them, T.  Every entry not after T is a candidate (a few dozen for random
-// logits); each candidate counts the candidates before it, which is its place in the list.
+// Up to 4096 logits sit in registers (16 per thread).  The 256 threads form 64 quads; the 64
+// quad maxima are distinct entries of the row, so the row's 16th best entry is not after the
+// 16th best of them, T.  Every entry not after T is a candidate (two dozen for random logits);
+// each candidate counts the candidates before it, which is its place in the list.
 // More than 256 candidates (many equal or missing values), or more than 4096 logits: the
 // list is built one entry per round by re-scanning (block_argbest); with SLICED, rows of up to
 // 65536 logits first try the candidate scheme slice by slice (used by the stand-alone top-k
@@ -376,9 +376,11 @@ template <bool SLICED = false>
 __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) {
     __shared__ float c_v[256];
     __shared__ int c_i[256];
-    __shared__ float g_v[16];
-    __shared__ int g_i[16];
+    __shared__ float g_v[64];
+    __shared__ int g_i[64];
     __shared__ int c_n;
+    __shared__ float t_v;
+    __shared__ int t_i;
     const float* z = s.zdraft + ((size_t)i * D.Bmax + b) * D.V1;
     int32_t* out = s.draft_topk + ((size_t)b * D.Hh + i) * VADUSA_MAX_TOPK;
     const int kmax = D.V1 < VADUSA_MAX_TOPK ? D.V1 : VADUSA_MAX_TOPK;
@@ -465,19 +467,31 @@ __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) 
             const int v = threadIdx.x + 256 * j;
             if (v < D.V1 && before(zr[j], v, lv, li)) { lv = zr[j]; li = v; }
         }
-        row16_argbest(lv, li);   // best of each group of 16 lanes
-        if ((threadIdx.x & 15) == 0) { g_v[threadIdx.x >> 4] = lv; g_i[threadIdx.x >> 4] = li; }
-        if (threadIdx.x == 0) c_n = 0;
+        // best of each quad: 64 group maxima (fewer for fewer than 253 logits; empty groups leave
+        // (-inf, 0x7fffffff), which ranks after every real entry)
+        argbest_step<0xB1>(lv, li);
+        argbest_step<0x4E>(lv, li);
+        if ((threadIdx.x & 3) == 0) { g_v[threadIdx.x >> 2] = lv; g_i[threadIdx.x >> 2] = li; }
+        if (threadIdx.x == 0) { c_n = 0; t_v = -INFINITY; t_i = 0x7fffffff; }   // default T: keep everything
         __syncthreads();
-        float gv[16];
-        int gi[16];
-#pragma unroll
-        for (int g = 0; g < 16; ++g) { gv[g] = g_v[g]; gi[g] = g_i[g]; }   // all LDS reads in flight at once
-        float tv = gv[0];
-        int ti = gi[0];
-#pragma unroll
-        for (int g = 1; g < 16; ++g)
-            if (before(tv, ti, gv[g], gi[g])) { tv = gv[g]; ti = gi[g]; }   // T = the last of the group maxima
+        // T = the 16th best of the group maxima: an entry of the row with at least 15 others before
+        // it, so the row's 16th best is not after T.  Wave 0 ranks the 64 maxima against each other
+        // with lane broadcasts (no LDS traffic in the loop).  With fewer than 16 real maxima T stays
+        // at its default.
+        if (threadIdx.x < 64 && D.V1 >= 64) {
+            const float gv = g_v[threadIdx.x];
+            const int gi = g_i[threadIdx.x];
+            int r = 0;
+            for (int j = 0; j < 64; ++j) {
+                const float bv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), j));
+                const int bi = __builtin_amdgcn_readlane(gi, j);
+                r += before(bv, bi, gv, gi) ? 1 : 0;
+            }
+            if (r == 15) { t_v = gv; t_i = gi; }
+        }
+        __syncthreads();
+        const float tv = t_v;
+        const int ti = t_i;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int v = threadIdx.x + 256 * j;
@@ -488,7 +502,22 @@ __device__ inline void dev_topk(const Dims& D, const DevState& s, int i, int b) 
         }
         __syncthreads();
         const int n = c_n;
-        if (n <= 256) {
+        if (n <= 64) {
+            // the usual case (a few dozen candidates): wave 0 holds one candidate per lane and ranks
+            // them against each other with lane broadcasts; a candidate's rank is its place in the list
+            if (threadIdx.x < 64) {
+                const bool have = (int)threadIdx.x < n;
+                const float mv = have ? c_v[threadIdx.x] : -INFINITY;
+                const int mi = have ? c_i[threadIdx.x] : 0x7fffffff;
+                int r = 0;
+                for (int j = 0; j < n; ++j) {
+                    const float bv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mv), j));
+                    const int bi = __builtin_amdgcn_readlane(mi, j);
+                    r += before(bv, bi, mv, mi) ? 1 : 0;
+                }
+                if (have && r < kmax) stwi(out + r, mi);
+            }
+        } else if (n <= 256) {
             if ((int)threadIdx.x < n) {
                 const float mv = c_v[threadIdx.x];
                 const int mi = c_i[threadIdx.x];
