@@ -245,6 +245,7 @@ static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vecto
     st.bar = (uint32_t*)cv.take(4096 * 4);
     st.kerr = (int32_t*)cv.take(4 * 4);
     st.tprof = (long long*)cv.take(1024 * 8);
+    st.gtab = (const uint32_t*)cv.take((size_t)5 * VADUSA_GREC_WORDS * 4);
     st.layers_dev = (const LayerW*)cv.take(sizeof(LayerW) * c.n_layers);
     st.draft_dev = (const DraftW*)cv.take(sizeof(DraftW) * Hh);
     st.xn = cv.take(R * d * e);
@@ -308,6 +309,17 @@ static Dims make_dims(const vadusa_ctx* c, int B, int M) {
     D.Bmax = c->cfg.max_batch; D.Mmax = c->cfg.max_tree_nodes; D.B = B; D.M = M;
     return D;
 }
+
+// The launch-independent part of the step kernel's parameters.
+static StepParams base_params(const vadusa_ctx* c, const Dims& D) {
+    StepParams P{};
+    P.D = D; P.s = c->s; P.big_min = c->big_min;
+    P.lw0 = c->layers[0]; P.dw0 = c->draft[0];
+    P.lw_stride = c->layers.size() > 1 ? (size_t)((const char*)c->layers[1].Wqkv - (const char*)c->layers[0].Wqkv) : 0;
+    P.dw_stride = c->draft.size() > 1 ? (size_t)((const char*)c->draft[1].W1 - (const char*)c->draft[0].W1) : 0;
+    return P;
+}
+
 
 extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena_bytes, void* hip_stream,
                              vadusa_ctx** out) {
@@ -439,8 +451,13 @@ extern "C" int vadusa_load_weights(vadusa_ctx* c, const float* blob, size_t n_fl
         HIP_TRY(c, hipMemcpyAsync((void*)c->s.draft_dev, c->draft.data(), sizeof(DraftW) * c->draft.size(),
                                   hipMemcpyHostToDevice, c->stream));
     }
+    if (c->cfg.dtype) {
+        const StepParams P = base_params(c, make_dims(c, 1, 1));
+        launch_build_gtab(P, (uint32_t*)c->s.gtab, c->stream);
+    }
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     HIP_TRY(c, hipGetLastError());
+    c->gtab_ready = c->cfg.dtype != 0;
     c->state = 1;
     return VADUSA_OK;
 }
@@ -459,15 +476,12 @@ static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode,
     // once per list entry)
     const bool topk_apart = D.V1 > 4096 && hi == 1 + 5 * D.Ly + TP_COUNT;
     if (topk_apart) --hi;
-    StepParams P;
-    P.D = D; P.s = c->s;
+    StepParams P = base_params(c, D);
     if (rank_rows) P.s.logits = rank_rows;   // acceptance and continuation rank these rows instead of the logits
     P.table = table; P.prefill_mode = prefill_mode; P.tau = tau;
     P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent; P.profile = c->profile; P.wide = D.B * D.M >= 256;
-    P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq; P.big_min = c->big_min;
-    P.lw0 = c->layers[0]; P.dw0 = c->draft[0];
-    P.lw_stride = c->layers.size() > 1 ? (size_t)((const char*)c->layers[1].Wqkv - (const char*)c->layers[0].Wqkv) : 0;
-    P.dw_stride = c->draft.size() > 1 ? (size_t)((const char*)c->draft[1].W1 - (const char*)c->draft[0].W1) : 0;
+    P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq;
+    if (!c->gtab_ready) P.s.gtab = nullptr;
     hipError_t e;
     launch_step(P, c->n_cus, c->stream, &e);
     if (e != hipSuccess) return fail(c, VADUSA_EHIP, "step kernel launch failed: %s", hipGetErrorString(e));

@@ -223,6 +223,7 @@ struct DevState {
     size_t act_stride, stats_stride, hid_stride, draft_stride;   // rows padded to a multiple of 16
     uint32_t* bar;   // grid barrier: [0..16*64) group counters, [1024] top counter, [2048 + 16*64) release flags
     int32_t* kerr;   // [4] error flag raised by a kernel (barrier time-out)
+    const uint32_t* gtab;   // bf16 model: [5][VADUSA_GREC_WORDS] descriptors of the layers' linear maps (null: none)
     long long* tprof; // [128][8] timing points of workgroup 0 in the last launch (device clock, 100 MHz)
     void* xn;        // [R][d]  LayerNorm output
     void* q;         // [R][d]   (bf16 model: one slot per layer)
@@ -267,6 +268,7 @@ struct vadusa_ctx {
     float* uniforms;             // [max_batch * max_tree_nodes][V+1]: the caller's random numbers of a stochastic step
     float* scores;               // same shape: perturbed scores that replace the logits in such a step
     int sampled;                 // the pending / last verification was a stochastic one
+    int gtab_ready;              // the descriptor table of the layer maps has been written (after the weights are placed)
     int big_min;                 // StepParams::big_min (256 = one unit per compute unit; environment VADUSA_BIG_MIN_UNITS, for tests of small shapes)
     uint32_t epoch;              // grid-barrier epoch reached so far
     std::string err;
@@ -320,6 +322,11 @@ struct StepParams {
 // Phases of the step kernel after the decoder layers, as offsets from H = 1 + 5 * n_layers.
 enum { TP_HEAD = 0, TP_EDGES, TP_SELECT, TP_FINAL, TP_COMMIT, TP_DRAFT2, TP_TOPK, TP_COUNT };
 int step_num_phases(int n_layers);
+// One record per kind of layer phase: everything about a linear map that does not depend on the
+// launch (operand and result pointers of layer 0 with their advance per layer, K, N, epilogue),
+// written once per context by launch_build_gtab from the same code that otherwise derives it per unit.
+#define VADUSA_GREC_WORDS 32
+void launch_build_gtab(const StepParams& p, uint32_t* tab, hipStream_t st);
 // phase index: 0 embed; 1+5l.. layer l (qkv, attn, wo, ffn1, ffn2); then H + TP_*
 void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err);
 void launch_pack_w_ln(const float* src, const float* gamma, const float* beta, void* dst, float* colsum,

@@ -243,15 +243,51 @@ __device__ __forceinline__ void embed_unit(int r_) {
     }
 }
 
+// The context's descriptor table: one record of 32 words for each kind of layer phase (QKV 0,
+// out-projection 2, FFN1 3, FFN2 4; slot 1 is unused), holding what does not depend on the launch:
+//   words 4i .. 4i+3, i = 0..6: pointer for layer 0 and its advance per layer in bytes, for
+//       X, Wp, bias, colsum, stats, out, stats_out (a null pointer has advance 0)
+//   words 28..31: K, N, epilogue, -
+#if defined(__HIP_DEVICE_COMPILE__)
+#define VADUSA_CONSTANT __attribute__((address_space(4)))
+#else
+#define VADUSA_CONSTANT
+#endif
+
 // Descriptor of linear-map unit u of phase ph (all values are workgroup-uniform).  Returns false
 // for an empty unit (padding of the XCD-aware numbering) and for phases that are not linear maps.
 template <bool WIDE>
-__device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, int& row0) {
+__device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, int& row0, const uint32_t* gtab = nullptr) {
     const StepParams& P = sP;
     const Dims& D = P.D;
     const DevState& s = P.s;
     const int R = D.B * D.M, H = 1 + 5 * D.Ly;
     if (ph == 0) return false;
+    if (!WIDE && gtab != nullptr && ph < H) {
+        // The table never changes while kernels run and its address is workgroup-uniform: read
+        // through the constant address space, i.e. by scalar loads into scalar registers; the
+        // same four records serve every layer, so they stay in the scalar cache.
+        const int l = (ph - 1) / 5, k = (ph - 1) % 5;
+        const VADUSA_CONSTANT vadusa_u32x4* t = (const VADUSA_CONSTANT vadusa_u32x4*)(gtab + k * VADUSA_GREC_WORDS);
+        vadusa_u32x4 w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = t[i];
+        auto at = [&](int i) {
+            const uint64_t base = (uint64_t)w[i].x | ((uint64_t)w[i].y << 32), adv = (uint64_t)w[i].z | ((uint64_t)w[i].w << 32);
+            return base + (uint64_t)l * adv;
+        };
+        g.R = R; g.outf = nullptr; g.ph = ph; g.G = 4; g.layer = l;
+        g.X = (const bf16_t*)at(0); g.Wp = (const uint4*)at(1); g.bias = (const float*)at(2); g.colsum = (const float*)at(3);
+        g.stats = (const float*)at(4); g.out = (bf16_t*)at(5); g.stats_out = (float*)at(6);
+        g.K = (int)w[7].x; g.N = (int)w[7].y; g.epi = (int)w[7].z;
+        const int NT = g.N >> 4, NTp = pad8(NT);
+        int rb;
+        if (u < NTp) { nt = u; rb = 0; }
+        else if ((NTp & (NTp - 1)) == 0) { nt = u & (NTp - 1); rb = u >> __builtin_ctz(NTp); }
+        else { nt = u % NTp; rb = u / NTp; }
+        row0 = rb * (g.epi == SE_RESID ? 16 : 64);
+        return nt < NT;
+    }
     g.R = R; g.stats = nullptr; g.colsum = nullptr; g.bias = nullptr; g.out = nullptr; g.outf = nullptr;
     g.stats_out = nullptr; g.layer = 0; g.ph = ph;
     // (column tile, row block) of unit u of a map with NT column tiles; false: empty unit
@@ -359,13 +395,13 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
 // sums are combined in wave order through LDS.
 // ---------------------------------------------------------------------------
 template <int NRT>
-__device__ __forceinline__ void gemm_unit(int ph_, int u_) {
+__device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab) {
     // arguments arrive in vector registers: make them (and all that follows from them) scalar
     const int ph_u = __builtin_amdgcn_readfirstlane(ph_), u_u = __builtin_amdgcn_readfirstlane(u_);
     const StepParams& P = sP;
     GemmD g;
     int nt, row0;
-    if (!describe_gemm<false>(ph_u, u_u, g, nt, row0)) return;
+    if (!describe_gemm<false>(ph_u, u_u, g, nt, row0, gtab)) return;
     extern __shared__ uint4 smem[];
     float* s_stat = (float*)((char*)smem + ST_TILE_BYTES);
     constexpr int CH = NRT == 4 ? 8 : 16;     // k-steps per chunk
@@ -1299,7 +1335,7 @@ __device__ __forceinline__ void topk_unit(int u_) { const int u = __builtin_amdg
 // one unit of one phase: dispatch to the unit's own function
 // ---------------------------------------------------------------------------
 template <bool WIDE, bool CAUSAL>
-__device__ __forceinline__ void run_unit(int ph, int u) {
+__device__ __forceinline__ void run_unit(int ph, int u, const uint32_t* gtab) {
     const StepParams& P = sP;
     const Dims& D = P.D;
     const int H = 1 + 5 * D.Ly;
@@ -1327,8 +1363,8 @@ __device__ __forceinline__ void run_unit(int ph, int u) {
         if constexpr (WIDE) { if (attn_allq(P)) attn_unit<true, CAUSAL>(ph, u); else attn_unit<false, CAUSAL>(ph, u); }
         else attn_unit<false, CAUSAL>(ph, u);
         break;
-    case K_GEMM4: gemm_unit<4>(ph, u); break;
-    case K_GEMM1: if constexpr (!WIDE) gemm_unit<1>(ph, u); break;
+    case K_GEMM4: gemm_unit<4>(ph, u, gtab); break;
+    case K_GEMM1: if constexpr (!WIDE) gemm_unit<1>(ph, u, gtab); break;
     case K_GEMMW: if constexpr (WIDE) gemm_wide_unit(ph, u); break;
     case K_EDGE: edge_unit(u); break;
     case K_SELECT: select_unit(u); break;
@@ -1356,11 +1392,14 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
     const int H = 1 + 5 * P.D.Ly;
     if (threadIdx.x < 5 + TP_COUNT) s_nu[threadIdx.x] = phase_units(P, threadIdx.x < 5 ? 1 + (int)threadIdx.x : H + (int)threadIdx.x - 5);
     __syncthreads();
+    // the few-row kernel takes the launch-independent part of a layer map's descriptor from the
+    // context's table (null: derived per unit)
+    const uint32_t* gtab = WIDE ? nullptr : uniform_ptr(P.s.gtab);
     for (int ph = P.ph_lo; ph < P.ph_hi; ++ph) {
         tp(ph, 0);
         const int nu = ph == 0 ? P.D.B * P.D.M : ph < H ? s_nu[(ph - 1) % 5] : s_nu[5 + ph - H];
         for (int u = blockIdx.x; u < nu; u += gridDim.x) {
-            run_unit<WIDE, CAUSAL>(ph, u);
+            run_unit<WIDE, CAUSAL>(ph, u, gtab);
             __syncthreads();
         }
         tp(ph, 1);
@@ -1370,6 +1409,46 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
         }
     }
     tp(127, 0);
+}
+
+// Writes the descriptor table of a context: one thread runs the per-unit derivation for unit 0 of
+// the phases of layers 0 and 1 and stores layer 0's pointers and their advance per layer.
+__global__ __launch_bounds__(64) void k_build_gtab(StepParams Parg, uint32_t* tab) {
+    {
+        const uint32_t* src = (const uint32_t*)&Parg;
+        uint32_t* dst = (uint32_t*)&sP;
+        for (int i = threadIdx.x; i < (int)(sizeof(StepParams) / 4); i += 64) dst[i] = src[i];
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    for (int k = 0; k < 5; ++k) {
+        uint64_t q[16];
+        for (int i = 0; i < 16; ++i) q[i] = 0;
+        GemmD g0, g1;
+        int nt, row0;
+        if (describe_gemm<false>(1 + k, 0, g0, nt, row0)) {
+            const uint64_t p0[7] = {(uint64_t)g0.X, (uint64_t)g0.Wp, (uint64_t)g0.bias, (uint64_t)g0.colsum,
+                                    (uint64_t)g0.stats, (uint64_t)g0.out, (uint64_t)g0.stats_out};
+            uint64_t p1[7] = {p0[0], p0[1], p0[2], p0[3], p0[4], p0[5], p0[6]};
+            if (sP.D.Ly > 1 && describe_gemm<false>(6 + k, 0, g1, nt, row0)) {
+                p1[0] = (uint64_t)g1.X; p1[1] = (uint64_t)g1.Wp; p1[2] = (uint64_t)g1.bias; p1[3] = (uint64_t)g1.colsum;
+                p1[4] = (uint64_t)g1.stats; p1[5] = (uint64_t)g1.out; p1[6] = (uint64_t)g1.stats_out;
+            }
+            for (int i = 0; i < 7; ++i) { q[2 * i] = p0[i]; q[2 * i + 1] = p0[i] ? p1[i] - p0[i] : 0; }
+            q[14] = (uint64_t)(uint32_t)g0.K | ((uint64_t)(uint32_t)g0.N << 32);
+            q[15] = (uint64_t)(uint32_t)g0.epi;
+        }
+        for (int i = 0; i < 16; ++i) {
+            tab[k * VADUSA_GREC_WORDS + 2 * i] = (uint32_t)q[i];
+            tab[k * VADUSA_GREC_WORDS + 2 * i + 1] = (uint32_t)(q[i] >> 32);
+        }
+    }
+}
+void launch_build_gtab(const StepParams& p, uint32_t* tab, hipStream_t st) {
+    StepParams q = p;
+    q.s.gtab = nullptr;   // the derivation itself, not a table
+    q.wide = 0;
+    hipLaunchKernelGGL(k_build_gtab, dim3(1), dim3(64), 0, st, q, tab);
 }
 
 void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err) {
