@@ -100,6 +100,11 @@ __host__ __device__ inline bool wide_big(int R, int N, int min_units) { return c
 // Attention units of the many-row kernel are whole (sequence, head)s once there is one per compute unit
 // (up to four query tiles: one per wave).
 __host__ __device__ inline bool attn_allq(const StepParams& P) { return P.wide && P.D.M <= 64 && P.D.B * P.D.nH >= P.big_min; }
+// Few-row kernel, maps with more than 32 rows whose width is a multiple of 32 (QKV, FFN1): units
+// of 32 rows x 32 columns instead of 64 x 16.  What bounds such a phase is the bytes the compute
+// units pull through L2 (every unit reads its rows of X and its columns of W over the whole K):
+// a square unit needs (32 + 32) K values for the same 1024 outputs, not (64 + 16) K.
+__host__ __device__ inline bool sq_units(const StepParams& P, int N) { return !P.wide && P.D.B * P.D.M > 32 && N % 32 == 0; }
 __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     const Dims& D = P.D;
     const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
@@ -112,10 +117,10 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     }
     if (ph < H) {
         switch ((ph - 1) % 5) {
-        case 0: return pad8(3 * D.d / 16) * RG;
+        case 0: return sq_units(P, 3 * D.d) ? pad8(3 * D.d / 32) * cdiv(R, 32) : pad8(3 * D.d / 16) * RG;
         case 1: return attn_allq(P) ? pad8(D.B * D.nH) : pad8(D.B * D.nH) * cdiv(D.M, 16);
         case 2: return pad8(D.d / 16) * RB;
-        case 3: return pad8(D.F / 16) * RG;
+        case 3: return sq_units(P, D.F) ? pad8(D.F / 32) * cdiv(R, 32) : pad8(D.F / 16) * RG;
         default: return pad8(D.d / 16) * RB;
         }
     }
@@ -638,6 +643,197 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
         float m2 = (xn - mean) * (xn - mean);
         m2 = row16_sum(m2);
         if (ok && col == 0) stwf2(g.stats_out + ((size_t)nt * g.R + r) * 2, mean, m2);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// 32 x 32 unit of the few-row kernel (two row tiles x two column tiles; QKV and FFN1 when
+// sq_units): the same scheme as gemm_unit (wave w owns a quarter of the k-steps, operands
+// straight into MFMA registers, partial sums added in wave order through LDS), with every A
+// fragment used for two column tiles and every B fragment for two row tiles.  Units are
+// numbered (row block) * pad8(column pairs) + column pair.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void gemm_unit22(int ph_, int u_, const uint32_t* gtab) {
+    const int ph_u = __builtin_amdgcn_readfirstlane(ph_), u_u = __builtin_amdgcn_readfirstlane(u_);
+    const StepParams& P = sP;
+    GemmD g;
+    int nt, row0;
+    if (!describe_gemm<false>(ph_u, 0, g, nt, row0, gtab)) return;   // unit 0 always exists: the map itself
+    {
+        const int NG = g.N >> 5, NGp = pad8(NG);
+        int gi, rb;
+        if (u_u < NGp) { gi = u_u; rb = 0; }
+        else if ((NGp & (NGp - 1)) == 0) { gi = u_u & (NGp - 1); rb = u_u >> __builtin_ctz(NGp); }
+        else { gi = u_u % NGp; rb = u_u / NGp; }
+        if (gi >= NG) return;
+        nt = gi * 2; row0 = rb * 32;
+    }
+    extern __shared__ uint4 smem[];
+    float* s_stat = (float*)((char*)smem + ST_TILE_BYTES);
+    constexpr int CH = 8;
+    const Dims& D = P.D;
+    const DevState& s = P.s;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int nks = g.K >> 5;
+    const int ks_lo = (nks * wave) >> 2, ks_hi = (nks * (wave + 1)) >> 2;
+    const uint4* Wp[2];
+    const uint4* Ap[2];
+    bool rowok[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        Wp[t] = uniform_ptr(g.Wp + (size_t)(nt + t) * nks * 64);
+        rowok[t] = row0 + t * 16 < g.R;
+        Ap[t] = uniform_ptr((const uint4*)g.X + (size_t)(rowok[t] ? (row0 >> 4) + t : 0) * nks * 64);
+    }
+    const uint32_t ulane = (uint32_t)lane;
+    f32x4_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    tp(g.ph, 5);
+    // epilogue inputs of this thread's four columns, requested with the operands
+    const int erow = tid >> 3, ecg = tid & 7;                 // row of the unit, group of four columns (of 32)
+    const int n0 = nt * 16 + ecg * 4;
+    uint4 cs4 = make_uint4(0, 0, 0, 0), b4 = cs4;
+    if (g.colsum) cs4 = ldg4(g.colsum + n0);
+    if (g.bias) b4 = ldg4(g.bias + n0);
+    int kv_b = 0, kv_L = 0, kv_rows = 0, kv_which = 0, kv_cc = 0;
+    if (g.epi == SE_QKV && nt * 16 >= D.d) {
+        const int r = row0 + erow;
+        kv_which = (nt * 16) / D.d - 1;
+        kv_cc = (nt * 16) % D.d;
+        if (r < g.R) {
+            kv_b = r / D.M;
+            kv_L = ldg(s.L + kv_b);
+            kv_rows = ldg(s.n_rows + kv_b);
+        }
+    }
+    // LayerNorm statistics of the unit's 32 rows: four threads per row (threads 0..127)
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    const int tiles = g.K >> 4;
+    const bool do_stats = g.stats != nullptr && tid < 128;
+    const bool stats_early = do_stats && tiles <= 64;
+    float2 sv[16];
+    if (stats_early) {
+        const int r = row0 + (tid >> 2);
+        const float2* sp = (const float2*)g.stats + (r < g.R ? r : 0);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int t = (tid & 3) + 4 * j;
+            sv[j] = ldgf2(sp + (size_t)(t < tiles ? t : 0) * g.R);
+        }
+    }
+    for (int kb = ks_lo; kb == ks_lo || kb < ks_hi; kb += CH) {
+        uint4 bw[2][CH], aw[2][CH];
+        if (kb + CH <= ks_hi) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < CH; ++i) bw[t][i] = ldg4((const char*)Wp[t] + ((uint32_t)(kb + i) * 1024u + ulane * 16u));
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < CH; ++i)
+                    aw[t][i] = rowok[t] ? ldg4((const char*)Ap[t] + ((uint32_t)(kb + i) * 1024u + ulane * 16u)) : make_uint4(0, 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < CH; ++i) {
+                    const int ks = kb + i;
+                    bw[t][i] = ks < ks_hi ? ldg4((const char*)Wp[t] + ((uint32_t)ks * 1024u + ulane * 16u)) : make_uint4(0, 0, 0, 0);
+                    aw[t][i] = (ks < ks_hi && rowok[t]) ? ldg4((const char*)Ap[t] + ((uint32_t)ks * 1024u + ulane * 16u)) : make_uint4(0, 0, 0, 0);
+                }
+        }
+        if (kb == ks_lo) tp(g.ph, 6);
+        if (kb == ks_lo && do_stats && !stats_early) {
+            const int r = row0 + (tid >> 2);
+            if (r < g.R) {
+                const float2* sp = (const float2*)g.stats + r;
+                for (int t = tid & 3; t < tiles; t += 4) {
+                    const float2 v = ldgf2(sp + (size_t)t * g.R);
+                    s1 += v.x; s2 += v.y; s3 += v.x * v.x;
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < 2; ++ct)
+                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aw[rt][i]),
+                                                                          __builtin_bit_cast(bf16x8_t, bw[ct][i]), acc[rt][ct], 0, 0, 0);
+    }
+    tp(g.ph, 2);
+    if (stats_early && row0 + (tid >> 2) < g.R) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if ((tid & 3) + 4 * j < tiles) { s1 += sv[j].x; s2 += sv[j].y; s3 += sv[j].x * sv[j].x; }
+    }
+    if (g.stats) {
+        s1 = quad_sum(s1);
+        s2 = quad_sum(s2);
+        s3 = quad_sum(s3);
+        if (do_stats && (tid & 3) == 0) {
+            const float mean = s1 / tiles;
+            const float m2 = s2 + 16.f * fmaxf(s3 - tiles * mean * mean, 0.f);
+            s_stat[tid >> 2] = mean;
+            s_stat[64 + (tid >> 2)] = rsqrtf(m2 / g.K + LN_EPS);
+        }
+    }
+    __syncthreads();
+    float* red = (float*)smem;   // [wave][row tile][column tile][lane][4]
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[((wave * 4 + rt * 2 + ct) * 64 + lane) * 4 + i] = acc[rt][ct][i];
+    __syncthreads();
+    tp(g.ph, 3);
+    {
+        const int rt = erow >> 4, rr = erow & 15, ct = ecg >> 2, r = row0 + erow;
+        if (r < g.R) {
+            const float mu = g.stats ? s_stat[erow] : 0.f, rstd = g.stats ? s_stat[64 + erow] : 1.f;
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = (ecg & 3) * 4 + j;
+                const int src = (((rt * 2 + ct) * 64) + (rr >> 2) * 16 + col) * 4 + (rr & 3);
+                float a = red[src];
+#pragma unroll
+                for (int w = 1; w < 4; ++w) a += red[w * 1024 + src];
+                const float csj = __uint_as_float(j == 0 ? cs4.x : j == 1 ? cs4.y : j == 2 ? cs4.z : cs4.w);
+                const float bj = __uint_as_float(j == 0 ? b4.x : j == 1 ? b4.y : j == 2 ? b4.z : b4.w);
+                if (g.stats) a = rstd * (a - mu * csj);
+                v[j] = a + bj;
+            }
+            if (g.epi == SE_GELU) {
+                stw64(g.out + toff(r, n0, g.N >> 5),
+                      (uint64_t)pack_bf16(gelu_s(v[0]), gelu_s(v[1])) | ((uint64_t)pack_bf16(gelu_s(v[2]), gelu_s(v[3])) << 32));
+            } else if (g.epi == SE_QKV) {
+                const uint64_t pk = (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32);
+                if (n0 < D.d) {
+                    stw64(g.out + toff(r, n0, D.d >> 5), pk);
+                } else {
+                    const int b = kv_b, node = r - b * D.M;
+                    const int cc = kv_cc + ecg * 4, head = cc >> 6, dim = cc & 63;
+                    const int pos = kv_L + node;
+                    if (pos < D.maxpos && kv_rows > 0) {
+                        const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
+                        if (kv_which) {
+                            bf16_t* vp = (bf16_t*)s.Vc + hb + (size_t)dim * D.maxpos + pos;   // V is kept [dim][pos]
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) stw16(vp + (size_t)j * D.maxpos, f2bf(v[j]));
+                        } else {
+                            stw64((bf16_t*)s.Kc + hb + (size_t)pos * 64 + dim, pk);         // K is kept [pos][dim]
+                        }
+                    }
+                }
+            }
+        }
     }
 }
 
@@ -1341,12 +1537,12 @@ __device__ __forceinline__ void run_unit(int ph, int u, const uint32_t* gtab) {
     const int H = 1 + 5 * D.Ly;
     // each kind of unit is instantiated once (the kernel's code has to stay small enough for the
     // instruction cache): first decide the kind, then one call site per kind
-    enum { K_EMBED, K_ATTN, K_GEMM4, K_GEMM1, K_GEMMW, K_EDGE, K_SELECT, K_FINAL, K_COMMIT, K_TOPK };
+    enum { K_EMBED, K_ATTN, K_GEMM4, K_GEMM1, K_GEMM22, K_GEMMW, K_EDGE, K_SELECT, K_FINAL, K_COMMIT, K_TOPK };
     int kind;
     if (ph == 0) kind = K_EMBED;
     else if (ph < H) {
         const int k = (ph - 1) % 5;
-        kind = k == 1 ? K_ATTN : WIDE ? K_GEMMW : (k == 0 || k == 3) ? K_GEMM4 : K_GEMM1;
+        kind = k == 1 ? K_ATTN : WIDE ? K_GEMMW : (k == 0 || k == 3) ? (sq_units(P, k == 0 ? 3 * D.d : D.F) ? K_GEMM22 : K_GEMM4) : K_GEMM1;
     } else {
         switch (ph - H) {
         case TP_EDGES: kind = K_EDGE; break;
@@ -1365,6 +1561,7 @@ __device__ __forceinline__ void run_unit(int ph, int u, const uint32_t* gtab) {
         break;
     case K_GEMM4: gemm_unit<4>(ph, u, gtab); break;
     case K_GEMM1: if constexpr (!WIDE) gemm_unit<1>(ph, u, gtab); break;
+    case K_GEMM22: if constexpr (!WIDE) gemm_unit22(ph, u, gtab); break;
     case K_GEMMW: if constexpr (WIDE) gemm_wide_unit(ph, u); break;
     case K_EDGE: edge_unit(u); break;
     case K_SELECT: select_unit(u); break;
