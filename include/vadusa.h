@@ -129,7 +129,7 @@ int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena_bytes,
  *   VADUSA_PHASE_LAUNCHES       one kernel launch per phase of the bf16 step instead of one
  *                               persistent launch with grid barriers
  *   VADUSA_COOPERATIVE_LAUNCH   launch the persistent kernel cooperatively
- *   VADUSA_PHASE_CLOCK          record the timing points of VADUSA_DBG_PHASE_CLOCK
+ *   VADUSA_PHASE_CLOCK=n        record the timing points of VADUSA_DBG_PHASE_CLOCK in workgroup n - 1
  *   VADUSA_BIG_MIN_UNITS=n      many-row kernel (>= 256 rows): a linear map takes 128 x 128 output
  *                               units, and attention whole (sequence, head) units, from n such
  *                               units on (default 256 = one per compute unit); lets tests

@@ -364,7 +364,7 @@ extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena
     c->pending.assign(cfg->max_batch, 0);
     c->epoch = 0;
     c->persistent = getenv("VADUSA_PHASE_LAUNCHES") ? 0 : 1;
-    c->profile = getenv("VADUSA_PHASE_CLOCK") ? 1 : 0;
+    c->profile = getenv("VADUSA_PHASE_CLOCK") ? std::max(1, atoi(getenv("VADUSA_PHASE_CLOCK"))) : 0;   // n: workgroup n - 1 records
     c->big_min = getenv("VADUSA_BIG_MIN_UNITS") ? std::max(1, atoi(getenv("VADUSA_BIG_MIN_UNITS"))) : 256;
     {
         int dev = 0;

@@ -308,7 +308,7 @@ struct StepParams {
     int ph_lo, ph_hi;   // phases to run: [ph_lo, ph_hi)
     int persistent;     // 1: one cooperative launch with grid barriers between phases
     int wide;           // 1: B * M >= 256 rows: the layer maps and the base head use 64 x 64 output tiles
-    int profile;        // 1: workgroup 0 records timing points (costs a few hundred ns each)
+    int profile;        // n > 0: workgroup n - 1 records timing points (costs a few hundred ns each)
     uint32_t epoch;     // barrier epoch before the first barrier of this launch
     int seq0, nseq;     // sequences the compaction phases act on
     // Every layer's parameters sit at the same offsets from the previous layer's:

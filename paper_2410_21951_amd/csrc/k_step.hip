@@ -136,11 +136,11 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     }
 }
 
-// Timing points of workgroup 0 (device clock, 100 MHz): tprof[phase][k]; k = 0 phase start,
+// Timing points of one workgroup (StepParams::profile - 1; device clock, 100 MHz): tprof[phase][k]; k = 0 phase start,
 // 1 own units done, 2.. points inside a unit.  Read back through vadusa_debug_read.
 __device__ __forceinline__ void tp(int ph, int k) {
     const StepParams& P = sP;
-    if (P.profile && blockIdx.x == 0 && threadIdx.x == 0 && ph < 128) P.s.tprof[ph * 8 + k] = wall_clock64();
+    if (P.profile && (int)blockIdx.x == P.profile - 1 && threadIdx.x == 0 && ph < 128) P.s.tprof[ph * 8 + k] = wall_clock64();
 }
 
 // ---------------------------------------------------------------------------
