@@ -145,13 +145,17 @@ __device__ __forceinline__ void tp(int ph, int k) {
 
 // ---------------------------------------------------------------------------
 // grid barrier, two levels, no cache maintenance (see the coherence note above):
-// workgroups arrive on one of 16 group counters; the last of a group arrives on
-// the top counter, waits for all groups and releases its group through a flag.
+// workgroups arrive on one of 16 group counters; the last of a group adds one to
+// each of 8 copies of the top counter, and every workgroup waits on one copy
+// (its number mod 8: 32 pollers and 16 additions per copy and barrier) until all
+// groups are in.  A release flag per group would put one more round trip between
+// the last arrival and the others' release.
 // All counters grow monotonically (epoch = number of barriers so far).
 // Bounded: after ST_SPIN_LIMIT polls, or when another workgroup has raised the
 // error flag, the workgroup gives up and the kernel ends (the host reports it).
 // ---------------------------------------------------------------------------
 #define BAR_GROUPS 16
+#define BAR_TOPS 8
 __device__ bool grid_sync(uint32_t epoch, int ph) {
     const StepParams& P = sP;
     __shared__ int s_ok;
@@ -169,17 +173,14 @@ __device__ bool grid_sync(uint32_t epoch, int ph) {
         int ok = 1, spins = 0;
         const uint32_t old = __hip_atomic_fetch_add(&bar[g * 64], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (old + 1 == epoch * members) {
-            __hip_atomic_fetch_add(&bar[1024], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            while ((int32_t)(__hip_atomic_load(&bar[1024], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch * ngroups) < 0) {
-                if (++spins > ST_SPIN_LIMIT || ((spins & 255) == 0 && ldci(P.s.kerr) != 0)) { ok = 0; break; }
-                __builtin_amdgcn_s_sleep(1);
-            }
-            if (ok) __hip_atomic_store(&bar[2048 + g * 64], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
-            while ((int32_t)(__hip_atomic_load(&bar[2048 + g * 64], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) < 0) {
-                if (++spins > ST_SPIN_LIMIT || ((spins & 255) == 0 && ldci(P.s.kerr) != 0)) { ok = 0; break; }
-                __builtin_amdgcn_s_sleep(1);
-            }
+#pragma unroll
+            for (int x = 0; x < BAR_TOPS; ++x)
+                __hip_atomic_fetch_add(&bar[1024 + x * 64], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        const uint32_t* top = &bar[1024 + (blockIdx.x % BAR_TOPS) * 64];
+        while ((int32_t)(__hip_atomic_load(top, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch * ngroups) < 0) {
+            if (++spins > ST_SPIN_LIMIT || ((spins & 255) == 0 && ldci(P.s.kerr) != 0)) { ok = 0; break; }
+            __builtin_amdgcn_s_sleep(1);
         }
         if (!ok) stwi(P.s.kerr, 1);
         s_ok = ok;
