@@ -242,7 +242,7 @@ static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vecto
     st.act_stride = Rp * d; st.stats_stride = (d / 16) * R * 2; st.hid_stride = Rp * F; st.draft_stride = Bp * d;
     st.xb = (bf16_t*)cv.take(nslots * Rp * d * 2);
     st.stats = (float*)cv.take(nslots * st.stats_stride * 4);
-    st.bar = (uint32_t*)cv.take(4096 * 4);
+    st.bar = (uint32_t*)cv.take((size_t)VADUSA_BAR_WORDS * 4);
     st.kerr = (int32_t*)cv.take(4 * 4);
     st.tprof = (long long*)cv.take(1024 * 8);
     st.gtab = (const uint32_t*)cv.take((size_t)5 * VADUSA_GREC_WORDS * 4);
@@ -373,7 +373,7 @@ extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena
         c->n_cus = std::min(prop.multiProcessorCount, 1024);
         // barrier flags and the error flag start at zero; an unwritten KV row must never hold NaN bits
         const size_t kv = (size_t)cfg->n_layers * cfg->max_batch * cfg->n_heads * cfg->max_positions * 64 * c->elem;
-        hipError_t e0 = hipMemset(c->s.bar, 0, 4096 * 4);
+        hipError_t e0 = hipMemset(c->s.bar, 0, (size_t)VADUSA_BAR_WORDS * 4);
         if (e0 == hipSuccess) e0 = hipMemset(c->s.tprof, 0, 1024 * 8);
         if (e0 == hipSuccess) e0 = hipMemset(c->s.kerr, 0, 16);
         if (e0 == hipSuccess) e0 = hipMemset(c->s.Kc, 0, kv);

@@ -322,6 +322,8 @@ struct StepParams {
 // Phases of the step kernel after the decoder layers, as offsets from H = 1 + 5 * n_layers.
 enum { TP_HEAD = 0, TP_EDGES, TP_SELECT, TP_FINAL, TP_COMMIT, TP_DRAFT2, TP_TOPK, TP_COUNT };
 int step_num_phases(int n_layers);
+// words of DevState::bar, the grid barrier's counters (16 of them, 64 words apart)
+#define VADUSA_BAR_WORDS 4096
 // One record per kind of layer phase: everything about a linear map that does not depend on the
 // launch (operand and result pointers of layer 0 with their advance per layer, K, N, epilogue),
 // written once per context by launch_build_gtab from the same code that otherwise derives it per unit.

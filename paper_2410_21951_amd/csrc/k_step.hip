@@ -145,17 +145,24 @@ __device__ __forceinline__ void tp(int ph, int k) {
 
 // ---------------------------------------------------------------------------
 // grid barrier, two levels, no cache maintenance (see the coherence note above):
-// workgroups arrive on one of 16 group counters; the last of a group adds one to
-// each of 8 copies of the top counter, and every workgroup waits on one copy
-// (its number mod 8: 32 pollers and 16 additions per copy and barrier) until all
-// groups are in.  A release flag per group would put one more round trip between
-// the last arrival and the others' release.
+// workgroups arrive on one of 8 group counters (number mod 8); the last of a
+// group adds one to each of 8 copies of the top counter, and every workgroup
+// waits on one copy (its number mod 8) until all groups are in.  Between the
+// last arrival and everybody's release lie one atomic with a result, one without
+// and one read; a release flag per group, written by the group's last member
+// after it has seen the top counter, put a further round trip there (+36 us per
+// step of 67 barriers).  Additions to one address are served one after another
+// (~5 ns each) and slow down under many watchers, which sets the shape: measured
+// 16 x 8 (groups x copies) 518 us per step, 8 x 8 513, 8 x 16 513, 4 x 8 519,
+// 32 x 8 527; arriving directly on the 8 copies (256 additions each) 612; one
+// level of 16 group counters in 8 copies, watched by 16 lanes, 533.
 // All counters grow monotonically (epoch = number of barriers so far).
 // Bounded: after ST_SPIN_LIMIT polls, or when another workgroup has raised the
 // error flag, the workgroup gives up and the kernel ends (the host reports it).
 // ---------------------------------------------------------------------------
-#define BAR_GROUPS 16
+#define BAR_GROUPS 8
 #define BAR_TOPS 8
+#define BAR_STRIDE 64   // words between counters
 __device__ bool grid_sync(uint32_t epoch, int ph) {
     const StepParams& P = sP;
     __shared__ int s_ok;
@@ -171,13 +178,13 @@ __device__ bool grid_sync(uint32_t epoch, int ph) {
         const uint32_t members = (gridDim.x - g + BAR_GROUPS - 1) / BAR_GROUPS;
         const uint32_t ngroups = gridDim.x < BAR_GROUPS ? gridDim.x : BAR_GROUPS;
         int ok = 1, spins = 0;
-        const uint32_t old = __hip_atomic_fetch_add(&bar[g * 64], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t old = __hip_atomic_fetch_add(&bar[g * BAR_STRIDE], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (old + 1 == epoch * members) {
 #pragma unroll
             for (int x = 0; x < BAR_TOPS; ++x)
-                __hip_atomic_fetch_add(&bar[1024 + x * 64], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(&bar[(BAR_GROUPS + x) * BAR_STRIDE], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        const uint32_t* top = &bar[1024 + (blockIdx.x % BAR_TOPS) * 64];
+        const uint32_t* top = &bar[(BAR_GROUPS + blockIdx.x % BAR_TOPS) * BAR_STRIDE];
         while ((int32_t)(__hip_atomic_load(top, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch * ngroups) < 0) {
             if (++spins > ST_SPIN_LIMIT || ((spins & 255) == 0 && ldci(P.s.kerr) != 0)) { ok = 0; break; }
             __builtin_amdgcn_s_sleep(1);
