@@ -475,12 +475,11 @@ static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode,
     // handles such rows slice by slice; the step kernel's own top-k phase would re-scan the row
     // once per list entry)
     const bool topk_apart = D.V1 > 4096 && hi == 1 + 5 * D.Ly + TP_COUNT;
-    if (topk_apart) --hi;
     StepParams P = base_params(c, D);
     if (rank_rows) P.s.logits = rank_rows;   // acceptance and continuation rank these rows instead of the logits
     P.table = table; P.prefill_mode = prefill_mode; P.tau = tau;
     P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent; P.profile = c->profile; P.wide = D.B * D.M >= 256;
-    P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq;
+    P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq; P.topk_apart = topk_apart;
     if (!c->gtab_ready) P.s.gtab = nullptr;
     hipError_t e;
     launch_step(P, c->n_cus, c->stream, &e);

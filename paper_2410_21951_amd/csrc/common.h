@@ -318,8 +318,11 @@ struct StepParams {
     DraftW dw0;
     size_t lw_stride, dw_stride;
     int big_min;        // many-row kernel: a map takes 128 x 128 units if it has at least this many of them
+    int topk_apart;     // 1: the last phase only compacts the KV cache; the draft lists come from the stand-alone top-k kernel
 };
 // Phases of the step kernel after the decoder layers, as offsets from H = 1 + 5 * n_layers.
+// TP_COMMIT: first map of the draft heads; TP_TOPK: draft lists and, beside them (most workgroups
+// are idle in that phase), the compaction of the KV cache.
 enum { TP_HEAD = 0, TP_EDGES, TP_SELECT, TP_FINAL, TP_COMMIT, TP_DRAFT2, TP_TOPK, TP_COUNT };
 int step_num_phases(int n_layers);
 // words of DevState::bar, the grid barrier's counters (16 of them, 64 words apart)

@@ -105,6 +105,8 @@ __host__ __device__ inline bool attn_allq(const StepParams& P) { return P.wide &
 // units pull through L2 (every unit reads its rows of X and its columns of W over the whole K):
 // a square unit needs (32 + 32) K values for the same 1024 outputs, not (64 + 16) K.
 __host__ __device__ inline bool sq_units(const StepParams& P, int N) { return !P.wide && P.D.B * P.D.M > 32 && N % 32 == 0; }
+// Units of the last phase that rank the draft heads' logits (none when a stand-alone kernel does it).
+__host__ __device__ inline int topk_units(const StepParams& P) { return P.topk_apart ? 0 : P.D.Hh * P.D.B; }
 __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     const Dims& D = P.D;
     const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
@@ -130,9 +132,9 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     case TP_EDGES: return P.prefill_mode ? 0 : cdiv(R, 4);
     case TP_SELECT: return P.prefill_mode ? 0 : P.nseq;
     case TP_FINAL: return P.nseq;
-    case TP_COMMIT: return D.Ly * cdiv(D.nH, 4) * P.nseq + D.Hh * (D.d / 16) * RGb;
+    case TP_COMMIT: return D.Hh * (D.d / 16) * RGb;
     case TP_DRAFT2: return D.Hh * cdiv(D.V1, 16) * RGb;
-    default: return D.Hh * D.B;
+    default: return topk_units(P) + D.Ly * cdiv(D.nH, 4) * P.nseq;   // TP_TOPK: draft lists, then KV compaction
     }
 }
 
@@ -369,9 +371,6 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
         g.stats = s.stats + (size_t)(2 * D.Ly) * s.stats_stride; g.epi = SE_LOGITS; g.outf = s.logits;
         return split(cdiv(D.V1, 16)) ? (row0 = rb * wrows, true) : false;
     case TP_COMMIT: {
-        const int ncommit = D.Ly * cdiv(D.nH, 4) * P.nseq;
-        if (u < ncommit) return false;
-        u -= ncommit;
         const int per = (D.d / 16) * RGb, i = u / per, v = u % per;
         DraftW dw;
         dw.W1 = (const char*)P.dw0.W1 + (size_t)i * P.dw_stride;
@@ -1556,8 +1555,8 @@ __device__ __forceinline__ void run_unit(int ph, int u, const uint32_t* gtab) {
         case TP_EDGES: kind = K_EDGE; break;
         case TP_SELECT: kind = K_SELECT; break;
         case TP_FINAL: kind = K_FINAL; break;
-        case TP_COMMIT: kind = u < D.Ly * cdiv(D.nH, 4) * P.nseq ? K_COMMIT : K_GEMM4; break;
-        case TP_TOPK: kind = K_TOPK; break;
+        case TP_COMMIT: kind = K_GEMM4; break;
+        case TP_TOPK: kind = u < topk_units(P) ? K_TOPK : K_COMMIT; break;
         default: kind = (WIDE && ph == H) ? K_GEMMW : K_GEMM4; break;   // TP_HEAD, TP_DRAFT2
         }
     }
@@ -1574,7 +1573,7 @@ __device__ __forceinline__ void run_unit(int ph, int u, const uint32_t* gtab) {
     case K_EDGE: edge_unit(u); break;
     case K_SELECT: select_unit(u); break;
     case K_FINAL: final_unit(u); break;
-    case K_COMMIT: commit_unit(u); break;
+    case K_COMMIT: commit_unit(u - topk_units(P)); break;
     default: topk_unit(u); break;
     }
 }
