@@ -1,5 +1,5 @@
 """Child process of tests/test_emulated_kernel.py: one lockstep run of the emulated kernels
-against the oracle.  usage: run_case.py <libvadusa_emu.so> <dtype>"""
+against the oracle.  usage: run_case.py <libvadusa_emu.so> <dtype | bf16-40rows>"""
 import os
 import sys
 import time
@@ -14,6 +14,27 @@ from synth import ModelConfig, make_weights, make_tree, make_uniforms
 from parity import Lockstep
 
 dtype = sys.argv[2]
+if dtype == "bf16-40rows":
+    # More than 32 rows: QKV and FFN1 run as 32 x 32 units, the second row block ragged (rows
+    # 32..39: one row tile of two); two layers, so the per-layer advance of the descriptor table counts.
+    cfg = ModelConfig(n_layers=2, d_model=64, n_heads=1, head_dim=64, d_ffn=192, speech_vocab=71, text_vocab=20,
+                      n_draft_heads=2, max_positions=192, dtype="bf16")
+    W = make_weights(cfg, 71, std=0.05)
+    rng = np.random.default_rng(72)
+    text = [rng.integers(0, cfg.text_vocab, 2).astype(np.int32)]
+    prompt = [rng.integers(0, cfg.speech_vocab, 45).astype(np.int32)]
+    tree = make_tree(40, (10, 10))
+    t0 = time.time()
+    ls = Lockstep(cfg, W, text, prompt, 40)
+    ls.step(tree, 2)
+    ls.step(tree, 1)
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    print(f"emulated {dtype}: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e} "
+          f"ties {s.tie_root}/{s.tie_list}/{s.tie_edge} in {time.time() - t0:.0f} s", flush=True)
+    assert s.compared >= 1
+    sys.stdout.flush()
+    os._exit(0)
 cfg = ModelConfig(n_layers=1, d_model=64, n_heads=1, head_dim=64, d_ffn=128, speech_vocab=70, text_vocab=20,
                   n_draft_heads=2, max_positions=64, dtype=dtype)
 W = make_weights(cfg, 71, std=0.08)
