@@ -221,7 +221,7 @@ struct DevState {
     bf16_t* xb;      // [2Ly+1][R][d]  bf16 copy of the residual stream
     float* stats;    // [2Ly+1][d/16][R][2] per 16-column tile: mean, sum of squared deviations
     size_t act_stride, stats_stride, hid_stride, draft_stride;   // rows padded to a multiple of 16
-    uint32_t* bar;   // grid barrier: [0..16*64) group counters, [1024] top counter, [2048 + 16*64) release flags
+    uint32_t* bar;   // grid barrier: VADUSA_BAR_WORDS words; counters 64 words apart: 8 group counters, then 8 copies of the top counter
     int32_t* kerr;   // [4] error flag raised by a kernel (barrier time-out)
     const uint32_t* gtab;   // bf16 model: [5][VADUSA_GREC_WORDS] descriptors of the layers' linear maps (null: none)
     long long* tprof; // [128][8] timing points of workgroup 0 in the last launch (device clock, 100 MHz)
