@@ -67,6 +67,11 @@ struct GemmD {
 // The kernel's parameters, copied once per workgroup from the kernel-argument segment (which
 // may live in host memory) into LDS.  Every device function reads them from here.
 __shared__ StepParams sP;
+// Committed length and row count of the first ST_SEQ_CACHE sequences, read once per launch: both
+// are fixed while the decoder layers run (the continuation phase advances L after them), and the
+// attention units need them before they can ask for their first key block.
+#define ST_SEQ_CACHE 256
+__shared__ int s_seqL[ST_SEQ_CACHE], s_seqRows[ST_SEQ_CACHE];
 
 // GELU with the exact (erf) definition; erf by the rational approximation 7.1.26 of Abramowitz &
 // Stegun (absolute error below 1.5e-7, the size of an fp32 rounding of the result, which is then
@@ -1302,8 +1307,9 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     else { h = bh % D.nH; b = bh / D.nH; }
     // everything the unit needs before its first key block is requested at once: row count,
     // committed length, the queries, the mask words (one memory latency instead of three)
-    const int n_rows = ldg(s.n_rows + b);
-    const int L = ldg(s.L + b);
+    const bool seq_cached = b < ST_SEQ_CACHE;
+    const int n_rows = seq_cached ? s_seqRows[b] : ldg(s.n_rows + b);
+    const int L = seq_cached ? s_seqL[b] : ldg(s.L + b);
     const int node = min(qt * 16 + c, D.M - 1);
     const bf16_t* ql = (const bf16_t*)s.q + (size_t)layer * s.act_stride;
     const int qrow = b * D.M + node;
@@ -1594,6 +1600,12 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
     // unit counts of the five layer phases and of the phases after the layers, once per launch
     __shared__ int s_nu[5 + TP_COUNT];
     const int H = 1 + 5 * P.D.Ly;
+    if ((int)threadIdx.x < P.D.B) {   // at most ST_SEQ_CACHE = 256 sequences are cached
+        const int b = threadIdx.x;
+        s_seqL[b] = ldg(P.s.L + b);
+        // tree rows: a finished sequence has none (what the embedding phase is about to store in n_rows)
+        s_seqRows[b] = P.prefill_mode ? ldg(P.s.n_rows + b) : (P.s.finished[b] ? 0 : P.D.M);
+    }
     if (threadIdx.x < 5 + TP_COUNT) s_nu[threadIdx.x] = phase_units(P, threadIdx.x < 5 ? 1 + (int)threadIdx.x : H + (int)threadIdx.x - 5);
     __syncthreads();
     // the few-row kernel takes the launch-independent part of a layer map's descriptor from the
