@@ -12,6 +12,10 @@ Parity status of the functions below
   * causal_forward           pinned (library transformer layer, closed forms)
   * tree_forward             pinned (brute force against causal_forward)
   * draft_heads / top_k      pinned (closed forms, sort with planted ties)
+  * topk_needed / draft_lists / expand_tree / ancestor_mask
+                             pinned (hand-drawn trees in tests/golden/tree_cases.json:
+                             the full top-2 tree of depth 3 of Fig. 1(c) and a sparse
+                             tree, node tokens, depths and mask written out by hand)
   * verify_branch / select   pinned (worked example of Sec. 2.1, Alg. 1 cases)
   * generate at tau = 1      pinned (equals plain greedy decoding, Sec. 2.1 "lossless")
   * generate at tau > 1      replay property only; the exact token stream at
@@ -185,9 +189,18 @@ def prefill(model, text, prompt):
                     root_logits=f["logits"][-1])
 
 
+def topk_needed(depth, rank, n_heads):
+    """K_i of Sec. 2.4's sparse tree: how many of draft head i's top entries the
+    tree uses = 1 + the largest rank among the nodes at depth i (0 if none)."""
+    need = [0] * n_heads
+    for dep, r in zip(np.asarray(depth)[1:], np.asarray(rank)[1:]):
+        need[int(dep) - 1] = max(need[int(dep) - 1], int(r) + 1)
+    return need
+
+
 def draft_lists(model, st, tree):
     """Per-head top-K_i candidate lists, K_i = what the tree uses of head i."""
-    need = tree.topk_needed(model.cfg.n_draft_heads)
+    need = topk_needed(tree.depth, tree.rank, model.cfg.n_draft_heads)
     return [top_k(z, k) for z, k in zip(st.draft_logits, need)]
 
 
@@ -201,6 +214,20 @@ def expand_tree(root, lists, tree):
     return tok
 
 
+def ancestor_mask(parent):
+    """Tree attention mask (Sec. 2.1, Fig. 1c): bool [M, M], entry (n, m) is True
+    iff m is n itself or lies on the way from the root to n."""
+    parent = np.asarray(parent)
+    M = len(parent)
+    A = np.zeros((M, M), bool)
+    for n in range(M):
+        m = n
+        while m >= 0:
+            A[n, m] = True
+            m = int(parent[m])
+    return A
+
+
 def tree_forward(model, st, tok, tree):
     """One forward of all tree nodes (Sec. 2.1, tree attention): a node sees the
     committed prefix and, inside the tree, itself and its ancestors only.
@@ -208,7 +235,7 @@ def tree_forward(model, st, tok, tree):
     W, cfg = model.W, model.cfg
     M, L = tree.n_nodes, st.L
     x = W["E_speech"][tok] + W["P"][L + tree.depth]
-    allow = np.concatenate([np.ones((M, L), bool), tree.ancestor_matrix()], axis=1)
+    allow = np.concatenate([np.ones((M, L), bool), ancestor_mask(tree.parent)], axis=1)
     ks, vs = [], []
     for l in range(cfg.n_layers):
         x, k, v = block(model, l, x, st.K[l, :L], st.V[l, :L], allow)
@@ -225,16 +252,16 @@ def tree_forward(model, st, tok, tree):
 # vanilla rule of Sec. 2.1.
 # --------------------------------------------------------------------------
 def verify_branch(logits_branch, cand, tau):
-    """Algorithm 1 for one branch.  cand = (c_0..c_k), logits_branch[i] = L(i).
-    Returns k*: the accepted sequence is (c_0..c_{k*})."""
+    """Algorithm 1 for one branch.  cand = (c_0..c_k), logits_branch[i] = the base
+    head's logits at c_i.  Returns k*: the accepted sequence is (c_0..c_{k*}).
+
+    c_{i+1} is tolerated at position i iff it is one of the tau "correct" ids of
+    logits_branch[i]; the accepted sequence is the longest prefix all of whose
+    steps are tolerated, so k* = the number of leading tolerated steps."""
+    cand = np.asarray(cand)
     k = len(cand) - 1
-    v = [set(top_k(logits_branch[i], tau).tolist()) for i in range(k + 1)]
-    k_star = k
-    for i in range(k):
-        if int(cand[i + 1]) not in v[i]:
-            k_star = i
-            break
-    return k_star
+    tolerated = np.array([cand[i + 1] in top_k(logits_branch[i], tau) for i in range(k)], dtype=bool)
+    return int(np.cumprod(tolerated).sum())
 
 
 def branches(tree):

@@ -14,7 +14,7 @@ p(head i, rank r) = alpha0 * decay**(i-1) * g(r),  g(r) = (1-q) q**r / (1-q**cap
 from dataclasses import dataclass
 import heapq
 import math
-from typing import List, Sequence, Tuple
+from typing import Sequence, Tuple
 
 import numpy as np
 
@@ -33,24 +33,6 @@ class TreeSpec:
     @property
     def max_depth(self) -> int:
         return int(self.depth.max())
-
-    def topk_needed(self, n_heads: int) -> List[int]:
-        """K_i: how many top entries of draft head i (1-based depth i) the tree uses."""
-        need = [0] * n_heads
-        for d, r in zip(self.depth[1:], self.rank[1:]):
-            need[d - 1] = max(need[d - 1], int(r) + 1)
-        return need
-
-    def ancestor_matrix(self) -> np.ndarray:
-        """bool [M, M]; row n marks n itself and all of its ancestors."""
-        M = self.n_nodes
-        A = np.zeros((M, M), bool)
-        for n in range(M):
-            m = n
-            while m >= 0:
-                A[n, m] = True
-                m = int(self.parent[m])
-        return A
 
 
 def _from_paths(paths: Sequence[Tuple[int, ...]]) -> TreeSpec:

@@ -1,6 +1,7 @@
 """Shared test helpers (no method arithmetic beyond what a test needs to state)."""
 import numpy as np
 
+from oracle import vadusa_oracle as O
 from synth import ModelConfig, make_weights
 
 SMALL = ModelConfig(n_layers=2, d_model=64, n_heads=4, head_dim=16, d_ffn=128,
@@ -20,7 +21,7 @@ def planted_lists(future, tree, n_heads, vocab, rng, p_hit=0.7):
     future[i] is the token that head i+1 should have predicted (may be missing
     near the end).  Lists hold distinct ids like a real top-k list.
     """
-    need = tree.topk_needed(n_heads)
+    need = O.topk_needed(tree.depth, tree.rank, n_heads)
     lists = []
     for i, k in enumerate(need):
         t = int(future[i]) if i < len(future) else -1

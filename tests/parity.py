@@ -147,7 +147,7 @@ class Lockstep:
         cfg, dev, S = self.cfg, self.dev, self.stats
         margin = MARGIN if sample is None else MARGIN / min(sample[0], 1.0)
         tarr = TreeArrays(tree.parent, tree.rank)
-        need = tree.topk_needed(cfg.n_draft_heads)
+        need = O.topk_needed(tree.depth, tree.rank, cfg.n_draft_heads)
         S.steps += 1
         # (a) roots and lists
         roots = dev.debug(DBG.ROOT)
@@ -291,72 +291,83 @@ class Lockstep:
         assert e < self.tol, f"scores seq {b}: rel-L2 {e}"
 
 
-def sampled_check(cfg, weights, text, prompt, tree, tau, sample, kv_layers=(0,)):
+def sampled_check(cfg, weights, text, prompt, tree, tau, sample, kv_layers=(0,), steps=1):
     """Full-batch run on the GPU, oracle on a sample of the sequences only (for batches whose
-    oracle run would take minutes): prefill, one verification, compaction.  Returns
-    (sequences compared, sequences skipped because a root or list decision sat inside the
-    margin, largest logit error).  Decisions are held to the same margin rule as Lockstep."""
+    oracle run would take minutes): prefill, then `steps` times verification and compaction
+    (tau: one value, or one per step).  Returns (sequence-steps compared, sequence-steps skipped
+    because a root or list decision sat inside the margin, largest logit error).  A sampled
+    sequence whose root flips inside the margin leaves the sample (the oracle cannot follow it
+    any further).  Decisions are held to the same margin rule as Lockstep."""
     B = len(text)
     model = O.Model(cfg, weights)
     tol = TOL[cfg.dtype]
+    taus = [tau] * steps if np.isscalar(tau) else list(tau)
+    assert len(taus) == steps
     dev = Vadusa(cfg, max_batch=B, max_tree_nodes=tree.n_nodes, ignore_eos=True)
     dev.load_weights(weights)
     dev.prefill(text, prompt)
-    roots = dev.debug(DBG.ROOT)
-    lists = dev.debug(DBG.DRAFT_TOPK)
-    need = tree.topk_needed(cfg.n_draft_heads)
-    sts, skipped = {}, 0
-    override = [[lists[b, i].tolist() for i in range(cfg.n_draft_heads)] for b in range(B)]
-    for b in sample:
-        st = O.prefill(model, text[b], prompt[b])
-        if roots[b] != st.root:
-            assert top_gap(st.root_logits) <= MARGIN, f"root mismatch seq {b}"
-            skipped += 1
-            continue
-        ol = O.draft_lists(model, st, tree)
-        for i, k in enumerate(need):
-            if k and lists[b, i, :k].tolist() != ol[i].tolist():
-                assert top_gap(st.draft_logits[i], k) <= MARGIN, f"draft list mismatch seq {b} head {i}"
-        override[b] = [np.asarray(a, np.int64).tolist() + [0] * (16 - len(a)) for a in ol]
-        sts[b] = (st, ol)
-    dev.verify(TreeArrays(tree.parent, tree.rank), tau, override=override)
-    tok = dev.debug(DBG.TREE_TOK)
-    logits = dev.debug(DBG.LOGITS)
-    edge = dev.debug(DBG.EDGE_OK)
-    path = dev.debug(DBG.PATH)
-    max_err, forced = 0.0, {}
-    for b, (st, ol) in sts.items():
-        r = O.step(model, st, tree, tau, draft_override=ol, ignore_eos=True)
-        assert tok[b].tolist() == r["tok"].tolist(), f"tree tokens differ seq {b}"
-        for n in range(tree.n_nodes):
-            e = rel_l2(logits[b, n], r["logits"][n])
-            max_err = max(max_err, e)
-            assert e < tol, f"logits seq {b} node {n}: rel-L2 {e}"
-        flipped = False
-        for n in range(1, tree.n_nodes):
-            z = r["logits"][tree.parent[n]]
-            t = int(r["tok"][n])
-            want = int((z > z[t]).sum() + (z[:t] == z[t]).sum()) < tau
-            if bool(edge[b, n]) != want:
-                assert edge_margin(z, t, tau) <= MARGIN, f"edge decision differs seq {b} node {n}"
-                flipped = True
-        got = path[b, 1:1 + path[b, 0]].tolist()
-        if not flipped:
-            assert got == r["path"], f"path differs seq {b}: {got} vs {r['path']}"
-        elif got != r["path"]:
-            forced[b] = r["path"]
-    for b in range(B):
-        if b in forced:
-            dev.kv_compact(b, forced[b])
-        else:
-            dev.kv_compact(b)
-    L = dev.debug(DBG.KV_LEN)
-    for b, (st, _) in sts.items():
-        assert L[b] == st.L, f"L differs seq {b}"
-        assert dev.read_output(b).tolist() == st.emitted, f"output differs seq {b}"
+    need = O.topk_needed(tree.depth, tree.rank, cfg.n_draft_heads)
+    states = {b: O.prefill(model, text[b], prompt[b]) for b in sample}
+    compared, skipped, max_err = 0, 0, 0.0
+    for step_i in range(steps):
+        tau_i = taus[step_i]
+        roots = dev.debug(DBG.ROOT)
+        lists = dev.debug(DBG.DRAFT_TOPK)
+        sts = {}
+        override = [[lists[b, i].tolist() for i in range(cfg.n_draft_heads)] for b in range(B)]
+        for b in list(states):
+            st = states[b]
+            if roots[b] != st.root:
+                assert top_gap(st.root_logits) <= MARGIN, f"root mismatch seq {b} step {step_i}"
+                skipped += 1
+                del states[b]
+                continue
+            ol = O.draft_lists(model, st, tree)
+            for i, k in enumerate(need):
+                if k and lists[b, i, :k].tolist() != ol[i].tolist():
+                    assert top_gap(st.draft_logits[i], k) <= MARGIN, f"draft list mismatch seq {b} head {i} step {step_i}"
+            override[b] = [np.asarray(a, np.int64).tolist() + [0] * (16 - len(a)) for a in ol]
+            sts[b] = (st, ol)
+        dev.verify(TreeArrays(tree.parent, tree.rank), tau_i, override=override)
+        tok = dev.debug(DBG.TREE_TOK)
+        logits = dev.debug(DBG.LOGITS)
+        edge = dev.debug(DBG.EDGE_OK)
+        path = dev.debug(DBG.PATH)
+        forced = {}
+        for b, (st, ol) in sts.items():
+            r = O.step(model, st, tree, tau_i, draft_override=ol, ignore_eos=True)
+            assert tok[b].tolist() == r["tok"].tolist(), f"tree tokens differ seq {b} step {step_i}"
+            for n in range(tree.n_nodes):
+                e = rel_l2(logits[b, n], r["logits"][n])
+                max_err = max(max_err, e)
+                assert e < tol, f"logits seq {b} node {n} step {step_i}: rel-L2 {e}"
+            flipped = False
+            for n in range(1, tree.n_nodes):
+                z = r["logits"][tree.parent[n]]
+                t = int(r["tok"][n])
+                want = int((z > z[t]).sum() + (z[:t] == z[t]).sum()) < tau_i
+                if bool(edge[b, n]) != want:
+                    assert edge_margin(z, t, tau_i) <= MARGIN, f"edge decision differs seq {b} node {n} step {step_i}"
+                    flipped = True
+            got = path[b, 1:1 + path[b, 0]].tolist()
+            if not flipped:
+                assert got == r["path"], f"path differs seq {b} step {step_i}: {got} vs {r['path']}"
+            elif got != r["path"]:
+                forced[b] = r["path"]
+            compared += 1
+        for b in range(B):
+            if b in forced:
+                dev.kv_compact(b, forced[b])
+            else:
+                dev.kv_compact(b)
+        L = dev.debug(DBG.KV_LEN)
+        for b, (st, _) in sts.items():
+            assert L[b] == st.L, f"L differs seq {b} step {step_i}"
+            assert dev.read_output(b).tolist() == st.emitted, f"output differs seq {b} step {step_i}"
+    for b, st in states.items():
         for l in kv_layers:
             for which, ref in ((0, st.K), (1, st.V)):
                 e = rel_l2(dev.read_kv(l, b, which, 0, st.L), ref[l, :st.L])
                 assert e < tol, f"KV layer {l} seq {b} which {which}: rel-L2 {e}"
     dev.close()
-    return len(sts), skipped, max_err
+    return compared, skipped, max_err

@@ -35,6 +35,51 @@ def test_golden_acceptance_cases(case):
     assert int(O.top_k(logits[path[-1]], 1)[0]) == case["expect_next_root"]
 
 
+TREES = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "tree_cases.json")))
+
+
+@pytest.mark.parametrize("case", TREES["cases"], ids=lambda c: c["name"])
+def test_golden_tree_expansion_and_mask(case):
+    """Hand-drawn trees (Fig. 1(c) and a sparse one): node tokens, depths, K_i and the
+    tree-attention mask, every value of the fixture written by hand."""
+    tree = tree_from_paths(case["paths"])
+    assert tree.parent.tolist() == case["expect_parent"]
+    assert tree.depth.tolist() == case["expect_depth"]
+    assert O.topk_needed(tree.depth, tree.rank, len(case["lists"])) == case["expect_need"]
+    tok = O.expand_tree(case["root"], [np.array(l) for l in case["lists"]], tree)
+    assert tok.tolist() == case["expect_tok"]
+    mask = np.array([[ch == "1" for ch in row] for row in case["expect_mask"]])
+    assert np.array_equal(O.ancestor_mask(tree.parent), mask)
+
+
+def test_golden_draft_lists():
+    """draft_lists = the first K_i ids of each head's logits in descending order, ties to the lower id."""
+    c = TREES["draft_lists_case"]
+    tree = tree_from_paths(c["paths"])
+
+    class _M:
+        class cfg:
+            n_draft_heads = 3
+    st = O.SeqState(K=None, V=None, L=0, root=0, draft_logits=[np.array(z) for z in c["draft_logits"]])
+    got = O.draft_lists(_M, st, tree)
+    assert [g.tolist() for g in got] == c["expect_lists"]
+
+
+def test_verify_branch_is_longest_tolerated_prefix():
+    """Algorithm 1 against its definition by exhaustive enumeration on tiny cases: k* is the largest k such that
+    every c_{i+1}, i < k, has fewer than tau ids ranked ahead of it in row i."""
+    rng = np.random.default_rng(3)
+    for trial in range(200):
+        k, V1 = int(rng.integers(0, 5)), 6
+        logits = rng.integers(0, 4, (k + 1, V1)).astype(float)
+        cand = rng.integers(0, V1, k + 1)
+        tau = int(rng.integers(1, V1 + 1))
+        want = 0
+        while want < k and _rank(logits[want], cand[want + 1]) < tau:
+            want += 1
+        assert O.verify_branch(logits, cand, tau) == want
+
+
 def _rank(z, t):
     return int((z > z[t]).sum() + (z[:t] == z[t]).sum())
 

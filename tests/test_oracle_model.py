@@ -134,7 +134,7 @@ def test_tree_forward_equals_brute_force_per_path(tree):
 @pytest.mark.parametrize("tree", [make_tree(16, (4, 2, 2)), make_tree(64, (10,) * 4),
                                   make_tree(128, (10,) * 5), full_tree((3, 2))])
 def test_tree_mask_invariants(tree):
-    A = tree.ancestor_matrix()
+    A = O.ancestor_mask(tree.parent)
     M = tree.n_nodes
     assert A.diagonal().all() and A[:, 0].all()
     assert not np.triu(A, 1).any()                      # lower triangular in canonical order
