@@ -16,6 +16,17 @@
  *    throws or aborts across this boundary.  After an error the decoding state
  *    of the context is unchanged unless the code is VADUSA_EHIP.  A text for the
  *    last error of a context is available from vadusa_last_error().
+ *  - The bf16 step runs as one persistent kernel whose workgroups meet at grid
+ *    barriers, launched as an ordinary kernel with one workgroup per compute
+ *    unit: it needs the GPU to itself while it runs (no other kernel on another
+ *    stream or from another process at the same time).  Every wait is bounded: if a
+ *    workgroup is not placed, the kernel gives up, the next call that
+ *    synchronises (a step with result pointers, vadusa_read_output, the debug
+ *    readers) returns VADUSA_EHIP, and from then on every call except
+ *    vadusa_prefill, vadusa_load_weights and vadusa_destroy returns
+ *    VADUSA_ESTATE; vadusa_prefill resets the barrier state and starts the
+ *    sequences again.  VADUSA_COOPERATIVE_LAUNCH=1 makes the runtime verify
+ *    residency at every launch instead (about 18 us per step).
  *  - "host" / "device" in a comment says where a pointer must point.  The
  *    library never keeps a caller's host pointer after the call returns.
  *  - The library allocates no device memory: the caller passes one device
@@ -135,6 +146,8 @@ int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena_bytes,
  *                               units on (default 256 = one per compute unit); lets tests
  *                               reach those code paths with small shapes */
 
+/* Frees the context (host object).  Makes no HIP call, so it is safe in a finaliser or an exit handler;
+ * the caller drains the stream before it frees or reuses the arena. */
 void vadusa_destroy(vadusa_ctx* ctx);
 
 const char* vadusa_last_error(const vadusa_ctx* ctx);
@@ -286,6 +299,11 @@ enum {
 /* Copies one of the items above to host memory after synchronising the stream.
  * bytes must equal the item's size for the current batch and tree. */
 int vadusa_debug_read(vadusa_ctx* ctx, int32_t what, void* host_buf, size_t bytes);
+
+/* Test aid for the failure path described under "Conventions": sets the error word a step kernel raises when
+ * it gives up at a grid barrier (bf16 contexts; VADUSA_ESTATE for fp32 ones).  No kernel is disturbed: the
+ * stream is drained first. */
+int vadusa_debug_raise_error(vadusa_ctx* ctx);
 
 /* Copies K (which = 0) or V (1) rows pos0..pos0+npos-1 of a layer and sequence
  * to host as float [npos][d_model] (heads concatenated), after synchronising. */

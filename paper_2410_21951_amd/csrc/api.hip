@@ -363,6 +363,7 @@ extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena
     c->L_ub.assign(cfg->max_batch, 0);
     c->pending.assign(cfg->max_batch, 0);
     c->epoch = 0;
+    c->errored = 0;
     c->persistent = getenv("VADUSA_PHASE_LAUNCHES") ? 0 : 1;
     c->profile = getenv("VADUSA_PHASE_CLOCK") ? std::max(1, atoi(getenv("VADUSA_PHASE_CLOCK"))) : 0;   // n: workgroup n - 1 records
     c->big_min = getenv("VADUSA_BIG_MIN_UNITS") ? std::max(1, atoi(getenv("VADUSA_BIG_MIN_UNITS"))) : 256;
@@ -397,10 +398,24 @@ extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena
     return VADUSA_OK;
 }
 
+// Frees host memory only and makes no HIP call: it may run while the process is shutting down (a binding's
+// finaliser, an exit handler), when the HIP runtime or a profiler's library has already been torn down; a stream
+// synchronisation at that point ended one profiled run with a segmentation fault inside the exit handlers.
+// The caller drains its stream before it frees the arena.
 extern "C" void vadusa_destroy(vadusa_ctx* c) {
     if (!c) return;
-    (void)hipStreamSynchronize(c->stream);
     delete c;
+}
+
+// Test aid: raises the error word as a kernel that gave up at a grid barrier would (the next synchronising call
+// reports VADUSA_EHIP and the context refuses work until vadusa_prefill has reset it).
+extern "C" int vadusa_debug_raise_error(vadusa_ctx* c) {
+    if (!c) return VADUSA_EINVAL;
+    if (!c->cfg.dtype) return fail(c, VADUSA_ESTATE, "the fp32 path has no persistent kernel and no error word");
+    const int32_t one = 1;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(c->s.kerr, &one, 4, hipMemcpyHostToDevice));
+    return VADUSA_OK;
 }
 
 extern "C" const char* vadusa_last_error(const vadusa_ctx* c) { return c ? c->err.c_str() : "null context"; }
@@ -494,7 +509,31 @@ static int check_kerr(vadusa_ctx* c) {
     if (!c->cfg.dtype) return VADUSA_OK;
     int32_t k = 0;
     HIP_TRY(c, hipMemcpy(&k, c->s.kerr, 4, hipMemcpyDeviceToHost));
-    if (k) return fail(c, VADUSA_EHIP, "the step kernel timed out at a grid barrier");
+    if (k) {
+        // The launch that gave up left the barrier counters and the decoding state half-way: nothing the context
+        // holds can be trusted until vadusa_prefill has reset it (see recover()).
+        c->errored = 1;
+        return fail(c, VADUSA_EHIP, "the step kernel timed out at a grid barrier; vadusa_prefill resets the context");
+    }
+    return VADUSA_OK;
+}
+
+// Every call except vadusa_prefill, vadusa_load_weights and vadusa_destroy refuses a context whose kernel gave up.
+static int refuse_errored(vadusa_ctx* c) {
+    if (c->errored) return fail(c, VADUSA_ESTATE, "a step kernel gave up at a grid barrier earlier; vadusa_prefill resets the context");
+    return VADUSA_OK;
+}
+
+// Back to a clean start after a kernel gave up: nothing is running (the stream is drained), the barrier counters,
+// the error word and the host's epoch start again from zero.  The decoding state is rebuilt by the prefill that follows.
+static int recover(vadusa_ctx* c) {
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemset(c->s.bar, 0, (size_t)VADUSA_BAR_WORDS * 4));
+    HIP_TRY(c, hipMemset(c->s.kerr, 0, 16));
+    c->epoch = 0;
+    c->errored = 0;
+    std::fill(c->pending.begin(), c->pending.end(), 0);
+    if (c->state > 1) c->state = 1;
     return VADUSA_OK;
 }
 
@@ -560,6 +599,7 @@ extern "C" int vadusa_prefill(vadusa_ctx* c, int32_t batch, const int32_t* text_
     if (c->state < 1) return fail(c, VADUSA_ESTATE, "weights not loaded");
     if (batch < 1 || batch > c->cfg.max_batch) return fail(c, VADUSA_EINVAL, "batch %d outside 1..%d", batch, c->cfg.max_batch);
     if (!text_len || !prompt_len) return fail(c, VADUSA_EINVAL, "length arrays are null");
+    if (c->errored) { int rc = recover(c); if (rc) return rc; }
     int Mc = prefill_rows(c->cfg);
     {   // no pass needs more rows per sequence than the longest sequence has (whole 16-row tiles)
         int longest = 1;
@@ -685,6 +725,7 @@ static void mark_compacted(vadusa_ctx* c, int seq0, int nseq, int n_forced) {
 static int verify_impl(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau, const int32_t* draft_override,
                        bool fuse_compact, const vadusa_sampling* sp = nullptr) {
     if (!c) return VADUSA_EINVAL;
+    { int rc = refuse_errored(c); if (rc) return rc; }
     if (c->state != 2) return fail(c, VADUSA_ESTATE, c->state == 3 ? "a verification is still waiting for vadusa_kv_compact" : "prefill first");
     if (tau < 1) return fail(c, VADUSA_EINVAL, "tau must be >= 1 (got %d)", tau);
     if (sp) {
@@ -780,6 +821,7 @@ extern "C" int vadusa_verify_sampled(vadusa_ctx* c, const vadusa_tree_spec* tree
 
 extern "C" int vadusa_kv_compact(vadusa_ctx* c, int32_t seq, const int32_t* path_nodes, int32_t n) {
     if (!c) return VADUSA_EINVAL;
+    { int rc = refuse_errored(c); if (rc) return rc; }
     if (c->state != 3) return fail(c, VADUSA_ESTATE, "no verification is pending");
     const int B = c->batch;
     if (seq < -1 || seq >= B) return fail(c, VADUSA_EINVAL, "seq %d outside -1..%d", seq, B - 1);
@@ -861,6 +903,7 @@ extern "C" int vadusa_step_sampled(vadusa_ctx* c, const vadusa_tree_spec* tree, 
 
 extern "C" int vadusa_read_output(vadusa_ctx* c, int32_t seq, int32_t* tok, int32_t capacity, int32_t* n_out) {
     if (!c) return VADUSA_EINVAL;
+    { int rc = refuse_errored(c); if (rc) return rc; }
     if (c->state < 2) return fail(c, VADUSA_ESTATE, "prefill first");
     if (seq < 0 || seq >= c->batch || !n_out) return fail(c, VADUSA_EINVAL, "bad seq or null n_out");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -880,11 +923,13 @@ extern "C" int vadusa_read_output(vadusa_ctx* c, int32_t seq, int32_t* tok, int3
 // ---------------------------------------------------------------------------
 extern "C" int vadusa_debug_read(vadusa_ctx* c, int32_t what, void* host, size_t bytes) {
     if (!c || !host) return VADUSA_EINVAL;
+    { int rc = refuse_errored(c); if (rc) return rc; }
     if (c->state < 2) return fail(c, VADUSA_ESTATE, "prefill first");
     const DevState& s = c->s;
     const size_t B = c->batch, M = c->M, d = c->cfg.d_model, V1 = c->cfg.speech_vocab + 1, Hh = c->cfg.n_draft_heads;
     const size_t Bmax = c->cfg.max_batch;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (what != VADUSA_DBG_PHASE_CLOCK) { int rc = check_kerr(c); if (rc) return rc; }   // data of a launch that gave up is never handed out
     const void* src = nullptr;
     size_t need = 0;
     switch (what) {
@@ -938,6 +983,7 @@ extern "C" int vadusa_debug_read(vadusa_ctx* c, int32_t what, void* host, size_t
 extern "C" int vadusa_debug_read_kv(vadusa_ctx* c, int32_t layer, int32_t seq, int32_t which, int32_t pos0,
                                     int32_t npos, float* host) {
     if (!c || !host) return VADUSA_EINVAL;
+    { int rc = refuse_errored(c); if (rc) return rc; }
     if (c->state < 2) return fail(c, VADUSA_ESTATE, "prefill first");
     if (layer < 0 || layer >= c->cfg.n_layers || seq < 0 || seq >= c->cfg.max_batch || (which != 0 && which != 1) ||
         pos0 < 0 || npos < 1 || pos0 + npos > c->cfg.max_positions)
@@ -946,6 +992,7 @@ extern "C" int vadusa_debug_read_kv(vadusa_ctx* c, int32_t layer, int32_t seq, i
     const size_t kv_layer = (size_t)D.Bmax * D.nH * D.maxpos * 64 * c->elem;
     const char* base = (const char*)(which ? c->s.Vc : c->s.Kc) + layer * kv_layer;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    { int rc = check_kerr(c); if (rc) return rc; }
     launch_read_kv(D, base, seq, which, pos0, npos, c->s.staging, c->cfg.dtype, c->stream);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     HIP_TRY(c, hipMemcpy(host, c->s.staging, (size_t)npos * D.d * 4, hipMemcpyDeviceToHost));

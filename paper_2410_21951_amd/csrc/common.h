@@ -271,6 +271,7 @@ struct vadusa_ctx {
     int gtab_ready;              // the descriptor table of the layer maps has been written (after the weights are placed)
     int big_min;                 // StepParams::big_min (256 = one unit per compute unit; environment VADUSA_BIG_MIN_UNITS, for tests of small shapes)
     uint32_t epoch;              // grid-barrier epoch reached so far
+    int errored;                 // a step kernel gave up at a grid barrier: every call but vadusa_prefill refuses until that resets the context
     std::string err;
 };
 

@@ -5,8 +5,10 @@ library's HIP kernels.  PyTorch is used to allocate the device arena and to
 supply the stream.  There is no CPU fallback: if the library is missing or no
 GPU is present, construction fails.
 """
+import atexit
 import ctypes as C
 import os
+import weakref
 
 import numpy as np
 
@@ -66,6 +68,7 @@ EXPORTS = {
     "vadusa_read_output": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]),
     "vadusa_debug_read": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t]),
     "vadusa_debug_read_kv": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
+    "vadusa_debug_raise_error": (C.c_int, [C.c_void_p]),
 }
 
 
@@ -144,6 +147,15 @@ def pack_blob(cfg, weights):
     return np.concatenate([np.asarray(weights[n], dtype=np.float32).ravel() for n in blob_order(cfg)])
 
 
+_OPEN = weakref.WeakSet()   # contexts not yet closed
+
+
+@atexit.register
+def _close_all():
+    for v in list(_OPEN):
+        v.close()
+
+
 class Vadusa:
     """One decoding context on the current CUDA/HIP device."""
 
@@ -168,21 +180,33 @@ class Vadusa:
         if rc:
             raise VadusaError(rc, "vadusa_create failed")
         self.h = h
+        _OPEN.add(self)
         self.batch = 0
         self.M = 0
         self.Hh = self.cfg.n_draft_heads
         self.V1 = self.cfg.speech_vocab + 1
 
     def close(self):
+        """Drains the stream and frees the context.  Idempotent.  Contexts still open at interpreter exit are
+        closed by an exit handler that runs before torch's own teardown; __del__ only frees the host object
+        (vadusa_destroy makes no HIP call), so a late finaliser cannot touch a runtime that is already gone."""
         if getattr(self, "h", None):
+            try:
+                self.stream.synchronize()
+            except Exception:
+                pass
             self.lib.vadusa_destroy(self.h)
             self.h = None
+        _OPEN.discard(self)
 
     def __del__(self):
-        try:
-            self.close()
-        except Exception:
-            pass
+        h = getattr(self, "h", None)
+        if h:
+            try:
+                self.lib.vadusa_destroy(h)
+            except Exception:
+                pass
+            self.h = None
 
     def _check(self, rc):
         if rc:
@@ -286,6 +310,10 @@ class Vadusa:
         out = np.zeros(shape, dt)
         self._check(self.lib.vadusa_debug_read(self.h, what, _ptr(out), out.nbytes))
         return out
+
+    def debug_raise_error(self):
+        """Test aid: sets the error word of a kernel that gave up at a grid barrier."""
+        self._check(self.lib.vadusa_debug_raise_error(self.h))
 
     def read_kv(self, layer, seq, which, pos0, npos):
         out = np.zeros((npos, self.cfg.d_model), np.float32)

@@ -35,6 +35,38 @@ if dtype == "bf16-40rows":
     assert s.compared >= 1
     sys.stdout.flush()
     os._exit(0)
+if dtype == "bf16-giveup":
+    # the failure path: the host raises the error word of a kernel that gave up at a grid barrier; the next
+    # synchronising call reports it, later calls refuse, a prefill recovers and decodes the same tokens
+    from paper_2410_21951_amd import Vadusa, TreeArrays, VadusaError, DBG
+    cfg = ModelConfig(n_layers=1, d_model=64, n_heads=1, head_dim=64, d_ffn=128, speech_vocab=70, text_vocab=20,
+                      n_draft_heads=2, max_positions=64, dtype="bf16")
+    W = make_weights(cfg, 71, std=0.08)
+    rng = np.random.default_rng(73)
+    text = [rng.integers(0, cfg.text_vocab, 3).astype(np.int32)]
+    prompt = [rng.integers(0, cfg.speech_vocab, 9).astype(np.int32)]
+    t = make_tree(8, (3, 2))
+    tree = TreeArrays(t.parent, t.rank)
+    dev = Vadusa(cfg, max_batch=1, max_tree_nodes=8, ignore_eos=True)
+    dev.load_weights(W)
+
+    def run():
+        dev.prefill(text, prompt)
+        return [dev.step(tree, 1 + i % 2) for i in range(3)]
+    want = run()
+    dev.debug_raise_error()
+    codes = []
+    for call in (lambda: dev.step(tree, 1), lambda: dev.debug(DBG.ROOT), lambda: dev.step(tree, 1)):
+        try:
+            call()
+            codes.append(0)
+        except VadusaError as e:
+            codes.append(e.code)
+    assert codes == [-5, -4, -4], codes
+    assert run() == want
+    print("emulated give-up path: reported, refused, recovered", flush=True)
+    sys.stdout.flush()
+    os._exit(0)
 cfg = ModelConfig(n_layers=1, d_model=64, n_heads=1, head_dim=64, d_ffn=128, speech_vocab=70, text_vocab=20,
                   n_draft_heads=2, max_positions=64, dtype=dtype)
 W = make_weights(cfg, 71, std=0.08)

@@ -125,6 +125,48 @@ def test_step_equals_verify_plus_compact_and_async_and_reproducible():
     assert all(len(o) >= 12 for o in outs[0])
 
 
+def test_a_kernel_that_gave_up_is_reported_and_prefill_recovers():
+    """The failure path of the persistent kernel without disturbing any kernel: the host sets the error word a
+    workgroup raises when its bounded barrier wait runs out.  The next synchronising call reports VADUSA_EHIP,
+    every later call (the debug readers included) refuses with VADUSA_ESTATE, vadusa_prefill resets the barrier
+    state, and the context then decodes the same tokens as a fresh one."""
+    from paper_2410_21951_amd import VadusaError, DBG
+    print("give-up path", flush=True)
+    W = make_weights(CFG, 4, std=0.08)
+    rng = np.random.default_rng(2)
+    text, prompt = _inputs(rng)
+    tree = _tree(make_tree(16, (4, 2, 2)))
+
+    def run(dev):
+        dev.prefill(text, prompt)
+        return [dev.step(tree, 1 + i % 3) for i in range(6)]
+
+    ref = _dev(max_batch=2, max_tree_nodes=16, ignore_eos=True)
+    ref.load_weights(W)
+    want = run(ref)
+    ref.close()
+    dev = _dev(max_batch=2, max_tree_nodes=16, ignore_eos=True)
+    dev.load_weights(W)
+    dev.prefill(text, prompt)
+    dev.step(tree, 1)
+    for how in ("sync step", "async step then reader"):
+        dev.debug_raise_error()
+        with pytest.raises(VadusaError) as e:
+            if how == "sync step":
+                dev.step(tree, 1)
+            else:
+                dev.step(tree, 1, sync=False)            # nothing is checked here ...
+                dev.debug(DBG.ROOT)                      # ... the reader must not hand out that launch's data
+        assert e.value.code == -5, how                   # VADUSA_EHIP
+        for call in (lambda: dev.step(tree, 1), lambda: dev.debug(DBG.LOGITS), lambda: dev.read_kv(0, 0, 0, 0, 4),
+                     lambda: dev.read_output(0), lambda: dev.verify(tree, 1)):
+            with pytest.raises(VadusaError) as e2:
+                call()
+            assert e2.value.code == -4, how              # VADUSA_ESTATE until the prefill
+        assert run(dev) == want, how
+    dev.close()
+
+
 def test_stochastic_entry_points():
     """vadusa_step_sampled = vadusa_verify_sampled + vadusa_kv_compact; uniforms from host or
     device memory give the same stream; argument errors are reported, not run."""
