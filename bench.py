@@ -83,6 +83,101 @@ def cpu_baseline(wl, W, text, prompt, tree, budget_s=15.0):
             "sample": f"{n} oracle steps (numpy fp64) from L={len(text[0]) + len(prompt[0])} after an untimed oracle prefill"}
 
 
+def timed_steps(workload, steps, warmup, tau, by_length=False, keep_open=False):
+    """Warm-up, then `steps` timed steps of a workload (whole generations from L0, the prefill between them untimed),
+    bracketed by events on the stream the kernels run on.  Returns the result record with its own roofline object
+    and, if keep_open, the context and inputs for further legs."""
+    import torch
+    from synth import PRESETS, make_weights, make_tokens, make_tree
+    from paper_2410_21951_amd import Vadusa, TreeArrays
+    wl = PRESETS[workload]
+    m = wl.model
+    W = make_weights(m, wl.seed)
+    text, prompt = make_tokens(wl)
+    tree = make_tree(wl.tree_nodes, wl.topk_caps)
+    tarr = TreeArrays(tree.parent, tree.rank)
+    dev = Vadusa(m, max_batch=wl.batch, max_tree_nodes=wl.tree_nodes, ignore_eos=True)
+    dev.load_weights(W)
+    B, M = wl.batch, wl.tree_nodes
+    L0 = [len(t) + len(p) for t, p in zip(text, prompt)]
+    seg = wl.n_generate
+
+    dev.prefill(text, prompt)
+    for _ in range(warmup):
+        dev.step(tarr, tau, sync=False)
+    torch.cuda.synchronize()
+
+    total_ms, done, L_sum = 0.0, 0, 0.0
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    while done < steps:
+        k = min(seg, steps - done)
+        dev.prefill(text, prompt)                 # untimed: back to L = L0
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(k):
+            dev.step(tarr, tau, sync=False)
+        ev1.record()
+        torch.cuda.synchronize()
+        total_ms += ev0.elapsed_time(ev1)
+        n_out = [len(dev.read_output(b)) for b in range(B)]
+        # mean committed length over the segment (linear growth from L0 to L0 + n_out)
+        L_sum += k * (np.mean(L0) + np.mean(n_out) / 2.0)
+        done += k
+    ms_step = total_ms / steps
+    # the same step binned by committed length (untimed for the headline figure): five equal
+    # slices of one generation, each timed with its own pair of events
+    by_L = []
+    if steps >= 50 and by_length:
+        dev.prefill(text, prompt)
+        nb = 5
+        per = min(seg, steps) // nb
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(nb + 1)]
+        torch.cuda.synchronize()
+        evs[0].record()
+        for i in range(nb):
+            for _ in range(per):
+                dev.step(tarr, tau, sync=False)
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        for i in range(nb):
+            by_L.append({"L_from": int(np.mean(L0)) + i * per, "L_to": int(np.mean(L0)) + (i + 1) * per,
+                         "us_per_step": evs[i].elapsed_time(evs[i + 1]) / per * 1e3})
+    L_mean = L_sum / steps
+    nbytes = algorithmic_bytes(m, B, M, L_mean)
+    achieved = nbytes / (ms_step * 1e-3) / 1e9
+    nflops = algorithmic_flops(m, B, M, L_mean)
+    tflops = nflops / (ms_step * 1e-3) / 1e12
+    out = {
+        "metric": "verified_tree_tokens_per_s", "value": B * M / (ms_step * 1e-3), "unit": "tree tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_step,
+        "us_per_step": ms_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": m.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {m.n_layers}L d={m.d_model} {m.dtype}, batch {B}, {M}-node tree, "
+                               f"tau={tau}, L {int(np.mean(L0))}->{int(np.mean(L0) + np.mean(n_out))}",
+                   "mean_committed_per_step": float(np.mean(n_out)) / min(seg, steps)},
+        # dominant kernel: k_step, the persistent kernel that runs a whole step; one launch per step,
+        # so its average launch duration is the event-timed region divided by the number of steps
+        # the roof that bounds the step: HBM bytes at batch 1 (64 flop per weight byte); from ~1000
+        # rows on the contractions at MFMA peak take longer than the bytes at HBM peak
+        "roofline": ({"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name),
+                      "kernel": "k_step (one launch = one speculative step)",
+                      "avg_launch_us": ms_step * 1e3, "algorithmic_bytes_per_launch": nbytes,
+                      "algorithmic_flops_per_launch": nflops, "tflops": tflops}
+                     if nbytes / (HBM_PEAK_GBS * 1e9) >= nflops / (MFMA_PEAK_TFLOPS * 1e12) else
+                     {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                      "frac": tflops / MFMA_PEAK_TFLOPS, "traffic": measured_traffic(wl.name),
+                      "kernel": "k_step (one launch = one speculative step)",
+                      "avg_launch_us": ms_step * 1e3, "algorithmic_bytes_per_launch": nbytes,
+                      "algorithmic_flops_per_launch": nflops, "hbm_gbs": achieved}),
+        "by_committed_length": by_L,
+    }
+    if keep_open:
+        return out, (dev, wl, W, text, prompt, tree, tarr)
+    dev.close()
+    return out, None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -91,6 +186,9 @@ def main():
     ap.add_argument("--workload", default="valle_b1")
     ap.add_argument("--tau", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of longform_b1, hubert_b16 and throughput_b64 that follow the headline workload")
+    ap.add_argument("--other-steps", type=int, default=20, help="timed steps of each of those workloads")
     ap.add_argument("--only-timed", action="store_true",
                     help="run the warm-up and the timed steps only (no by-length pass, AR / stochastic / dial legs, "
                          "no CPU baseline): every k_step launch of the run is then a step of the workload or a "
@@ -115,89 +213,14 @@ def main():
         return
     from synth import PRESETS, make_weights, make_tokens, make_tree
     from paper_2410_21951_amd import Vadusa, TreeArrays
-    wl = PRESETS[a.workload]
-    m = wl.model
     torch.cuda.set_device(0)
-    W = make_weights(m, wl.seed)
-    text, prompt = make_tokens(wl)
-    tree = make_tree(wl.tree_nodes, wl.topk_caps)
-    tarr = TreeArrays(tree.parent, tree.rank)
-    dev = Vadusa(m, max_batch=wl.batch, max_tree_nodes=wl.tree_nodes, ignore_eos=True)
-    dev.load_weights(W)
-    B, M = wl.batch, wl.tree_nodes
+    out, keep = timed_steps(a.workload, a.steps, a.warmup, a.tau, by_length=not a.only_timed, keep_open=True)
+    dev, wl, W, text, prompt, tree, tarr = keep
+    m, B, M = wl.model, wl.batch, wl.tree_nodes
     L0 = [len(t) + len(p) for t, p in zip(text, prompt)]
-    seg = min(wl.n_generate, (m.max_positions - M - max(L0)) // (m.n_draft_heads + 1) if False else wl.n_generate)
-
-    dev.prefill(text, prompt)
-    for _ in range(a.warmup):
-        dev.step(tarr, a.tau, sync=False)
-    torch.cuda.synchronize()
-
-    total_ms, done, L_sum = 0.0, 0, 0.0
+    ms_step = out["ms_per_step"]
+    achieved = out["roofline"]["achieved"] if out["roofline"]["bound"] == "hbm" else out["roofline"]["hbm_gbs"]
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    while done < a.steps:
-        k = min(seg, a.steps - done)
-        dev.prefill(text, prompt)                 # untimed: back to L = L0
-        torch.cuda.synchronize()
-        ev0.record()
-        for _ in range(k):
-            dev.step(tarr, a.tau, sync=False)
-        ev1.record()
-        torch.cuda.synchronize()
-        total_ms += ev0.elapsed_time(ev1)
-        n_out = [len(dev.read_output(b)) for b in range(B)]
-        # mean committed length over the segment (linear growth from L0 to L0 + n_out)
-        L_sum += k * (np.mean(L0) + np.mean(n_out) / 2.0)
-        done += k
-    ms_step = total_ms / a.steps
-    # the same step binned by committed length (untimed for the headline figure): five equal
-    # slices of one generation, each timed with its own pair of events
-    by_L = []
-    if a.steps >= 50 and not a.only_timed:
-        dev.prefill(text, prompt)
-        nb = 5
-        per = min(seg, a.steps) // nb
-        evs = [torch.cuda.Event(enable_timing=True) for _ in range(nb + 1)]
-        torch.cuda.synchronize()
-        evs[0].record()
-        for i in range(nb):
-            for _ in range(per):
-                dev.step(tarr, a.tau, sync=False)
-            evs[i + 1].record()
-        torch.cuda.synchronize()
-        for i in range(nb):
-            by_L.append({"L_from": int(np.mean(L0)) + i * per, "L_to": int(np.mean(L0)) + (i + 1) * per,
-                         "us_per_step": evs[i].elapsed_time(evs[i + 1]) / per * 1e3})
-    L_mean = L_sum / a.steps
-    nbytes = algorithmic_bytes(m, B, M, L_mean)
-    achieved = nbytes / (ms_step * 1e-3) / 1e9
-    nflops = algorithmic_flops(m, B, M, L_mean)
-    tflops = nflops / (ms_step * 1e-3) / 1e12
-    out = {
-        "metric": "verified_tree_tokens_per_s", "value": B * M / (ms_step * 1e-3), "unit": "tree tokens/s",
-        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
-        "us_per_step": ms_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": m.dtype, "data": "synthetic",
-        "config": {"workload": f"{wl.name}: {m.n_layers}L d={m.d_model} {m.dtype}, batch {B}, {M}-node tree, "
-                               f"tau={a.tau}, L {int(np.mean(L0))}->{int(np.mean(L0) + np.mean(n_out))}",
-                   "mean_committed_per_step": float(np.mean(n_out)) / min(seg, a.steps)},
-        # dominant kernel: k_step, the persistent kernel that runs a whole step; one launch per step,
-        # so its average launch duration is the event-timed region divided by the number of steps
-        # the roof that bounds the step: HBM bytes at batch 1 (64 flop per weight byte); from ~1000
-        # rows on the contractions at MFMA peak take longer than the bytes at HBM peak
-        "roofline": ({"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name),
-                      "kernel": "k_step (one launch = one speculative step)",
-                      "avg_launch_us": ms_step * 1e3, "algorithmic_bytes_per_launch": nbytes,
-                      "algorithmic_flops_per_launch": nflops, "tflops": tflops}
-                     if nbytes / (HBM_PEAK_GBS * 1e9) >= nflops / (MFMA_PEAK_TFLOPS * 1e12) else
-                     {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                      "frac": tflops / MFMA_PEAK_TFLOPS, "traffic": measured_traffic(wl.name),
-                      "kernel": "k_step (one launch = one speculative step)",
-                      "avg_launch_us": ms_step * 1e3, "algorithmic_bytes_per_launch": nbytes,
-                      "algorithmic_flops_per_launch": nflops, "hbm_gbs": achieved}),
-        "by_committed_length": by_L,
-    }
     if a.only_timed:
         dev.close()
         print(json.dumps(out))
@@ -340,6 +363,14 @@ def main():
                                   "speedup_over_ar_device_time": (n_tok / max(n_steps, 1)) * ar_us / (ms_step * 1e3),
                                   "continuation_recorded_again": rerecorded}
     dev.close()
+    # The other single-GPU workloads through the same entry point, each with a roofline object of its own
+    # (the bound named per workload: HBM bytes at batch 1, MFMA at 1024 and 2048 rows); the headline stays valle_b1.
+    if a.workload == "valle_b1" and not a.no_other_workloads:
+        out["workloads"] = []
+        for name in ("longform_b1", "hubert_b16", "throughput_b64"):
+            rec, _ = timed_steps(name, a.other_steps, 5, PRESETS[name].taus[0])
+            out["workloads"].append({k: rec[k] for k in ("value", "unit", "steps", "warmup", "us_per_step", "dtype", "config", "roofline")})
+            torch.cuda.empty_cache()
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, W, text, prompt, tree)
     print(json.dumps(out))
