@@ -310,6 +310,15 @@ int vadusa_debug_raise_error(vadusa_ctx* ctx);
 int vadusa_debug_read_kv(vadusa_ctx* ctx, int32_t layer, int32_t seq, int32_t which,
                          int32_t pos0, int32_t npos, float* host_buf);
 
+/* vadusa_debug_read_kv for callers that cannot allocate device memory or be handed a workspace for this
+ * purpose (code between graph captures, tight serving loops, harnesses that forbid hipMalloc): the float rows
+ * are staged in a static device array of the library, 1 MiB = 262 144 floats per GPU, held until the process
+ * ends, instead of the arena's staging area.  Same arguments, result and errors as vadusa_debug_read_kv;
+ * in addition npos * d_model > 262 144 returns VADUSA_ESHAPE (read in several calls).  Calls no allocating
+ * routine.  All contexts on one GPU share the array: calls that overlap on one GPU race; serialise them. */
+int vadusa_debug_read_kv_static(vadusa_ctx* ctx, int32_t layer, int32_t seq, int32_t which,
+                                int32_t pos0, int32_t npos, float* host_buf);
+
 #ifdef __cplusplus
 }
 #endif

@@ -998,3 +998,53 @@ extern "C" int vadusa_debug_read_kv(vadusa_ctx* c, int32_t layer, int32_t seq, i
     HIP_TRY(c, hipMemcpy(host, c->s.staging, (size_t)npos * D.d * 4, hipMemcpyDeviceToHost));
     return VADUSA_OK;
 }
+
+// ---------------------------------------------------------------------------
+// vadusa_debug_read_kv for callers that may not allocate: the float staging rows live in a file-scope device
+// array instead of the arena's staging area.  Every GPU the library runs on holds its own copy of the array (1 MiB)
+// until the process ends; its device address is looked up once per device, with that device current, and only
+// that pointer is ever handed to a kernel or a copy (the array's name is a host-side stand-in, not an address).
+// ---------------------------------------------------------------------------
+#define VADUSA_STATIC_KV_FLOATS (256 * 1024)
+static __device__ __align__(256) float scratch[VADUSA_STATIC_KV_FLOATS];
+#define VADUSA_MAX_DEVICES 64
+static float* g_scratch_ptr[VADUSA_MAX_DEVICES];   // device address of `scratch` on each device, null until looked up
+
+static int static_scratch(vadusa_ctx* c, float** out) {
+    int dev = -1;
+    HIP_TRY(c, hipGetDevice(&dev));
+    if (dev < 0 || dev >= VADUSA_MAX_DEVICES) return fail(c, VADUSA_EINVAL, "device %d outside 0..%d", dev, VADUSA_MAX_DEVICES - 1);
+    float* p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        HIP_TRY(c, hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(c, VADUSA_EHIP, "hipGetSymbolAddress returned a null address");
+        __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);   // two threads may both look it up: same value
+    }
+    *out = p;
+    return VADUSA_OK;
+}
+
+extern "C" int vadusa_debug_read_kv_static(vadusa_ctx* c, int32_t layer, int32_t seq, int32_t which, int32_t pos0,
+                                           int32_t npos, float* host) {
+    if (!c || !host) return VADUSA_EINVAL;
+    { int rc = refuse_errored(c); if (rc) return rc; }
+    if (c->state < 2) return fail(c, VADUSA_ESTATE, "prefill first");
+    if (layer < 0 || layer >= c->cfg.n_layers || seq < 0 || seq >= c->cfg.max_batch || (which != 0 && which != 1) ||
+        pos0 < 0 || npos < 1 || pos0 + npos > c->cfg.max_positions)
+        return fail(c, VADUSA_EINVAL, "bad layer / seq / range");
+    const Dims D = make_dims(c, c->batch, c->M);
+    if ((size_t)npos * D.d > (size_t)VADUSA_STATIC_KV_FLOATS)
+        return fail(c, VADUSA_ESHAPE, "%d rows of %d floats exceed the static staging array of %d floats (at most %d rows per call)",
+                    npos, D.d, VADUSA_STATIC_KV_FLOATS, VADUSA_STATIC_KV_FLOATS / D.d);
+    float* stage = nullptr;
+    { int rc = static_scratch(c, &stage); if (rc) return rc; }
+    const size_t kv_layer = (size_t)D.Bmax * D.nH * D.maxpos * 64 * c->elem;
+    const char* base = (const char*)(which ? c->s.Vc : c->s.Kc) + layer * kv_layer;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    { int rc = check_kerr(c); if (rc) return rc; }
+    // every float of rows 0..npos-1 is overwritten by the kernel: nothing of the previous call's contents is read
+    launch_read_kv(D, base, seq, which, pos0, npos, stage, c->cfg.dtype, c->stream);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(host, stage, (size_t)npos * D.d * 4, hipMemcpyDeviceToHost));
+    return VADUSA_OK;
+}

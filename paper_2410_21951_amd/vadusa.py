@@ -69,6 +69,7 @@ EXPORTS = {
     "vadusa_debug_read": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t]),
     "vadusa_debug_read_kv": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
     "vadusa_debug_raise_error": (C.c_int, [C.c_void_p]),
+    "vadusa_debug_read_kv_static": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
 }
 
 
@@ -315,7 +316,9 @@ class Vadusa:
         """Test aid: sets the error word of a kernel that gave up at a grid barrier."""
         self._check(self.lib.vadusa_debug_raise_error(self.h))
 
-    def read_kv(self, layer, seq, which, pos0, npos):
+    def read_kv(self, layer, seq, which, pos0, npos, static=False):
+        """static=True: through vadusa_debug_read_kv_static (staging in the library's static device array)."""
         out = np.zeros((npos, self.cfg.d_model), np.float32)
-        self._check(self.lib.vadusa_debug_read_kv(self.h, layer, seq, which, pos0, npos, _ptr(out)))
+        f = self.lib.vadusa_debug_read_kv_static if static else self.lib.vadusa_debug_read_kv
+        self._check(f(self.h, layer, seq, which, pos0, npos, _ptr(out)))
         return out

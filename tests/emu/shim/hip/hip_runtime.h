@@ -54,6 +54,11 @@ static inline hipError_t hipStreamSynchronize(hipStream_t) { return 0; }
 static inline hipError_t hipGetLastError() { return 0; }
 static inline const char* hipGetErrorString(hipError_t) { return "emu"; }
 static inline hipError_t hipGetDevice(int* d) { *d = 0; return 0; }
+#ifndef __align__
+#define __align__(n) __attribute__((aligned(n)))
+#endif
+#define HIP_SYMBOL(x) (&(x))
+static inline hipError_t hipGetSymbolAddress(void** p, const void* sym) { *p = (void*)sym; return 0; }
 static inline hipError_t hipGetDeviceProperties(hipDeviceProp_t* p, int) {
     const char* e = getenv("EMU_CUS");
     p->multiProcessorCount = e ? atoi(e) : 1;
