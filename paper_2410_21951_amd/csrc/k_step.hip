@@ -20,7 +20,8 @@
 // so the map reads the bf16 copy of the raw residual stream and applies the
 // row statistics in its epilogue.  The statistics are produced, per 16-column
 // tile, by whoever wrote the residual stream (exact fp32 values), and merged
-// by the consumer (pairwise mean / sum-of-squared-deviations merge).
+// by the consumer (mean of the tile means; squared deviations = the tiles' own plus 16 x the
+// spread of the tile means, summed as distances from the row's first tile mean).
 // No atomics combine data: results are bit-reproducible.
 //
 // Coherence inside the one launch: the eight XCDs have private L2 caches and a
@@ -473,7 +474,10 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
 
     // row statistics of the LayerNorm folded into this map: four threads per row, each
     // merges a quarter of the 16-column tiles (loads issued with the first operand chunk)
-    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    // The tile means are summed as distances from c0 = the row's first tile mean (a shift close to the row mean):
+    // the spread between the tiles then comes out of small numbers, also for rows whose mean is far larger than
+    // their spread (sum m_t^2 - tiles mean^2 would lose it to cancellation).
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f, c0 = 0.f;
     const int tiles = g.K >> 4;
     const bool do_stats = g.stats != nullptr && tid < ROWS * 4;
 
@@ -481,6 +485,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
         const int row = tid >> 2, part = tid & 3, r = row0 + row;
         if (r < g.R) {
             const float2* sp = (const float2*)g.stats + r;
+            c0 = ldgf2(sp).x;
             for (int t0 = part; t0 < tiles; t0 += 32) {
                 float2 v[8];
 #pragma unroll
@@ -489,7 +494,8 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
                     v[j] = t < tiles ? ldgf2(sp + (size_t)t * g.R) : make_float2(0.f, 0.f);
                 }
 #pragma unroll
-                for (int j = 0; j < 8; ++j) { s1 += v[j].x; s2 += v[j].y; s3 += v[j].x * v[j].x; }
+                for (int j = 0; j < 8; ++j)
+                    if (t0 + 4 * j < tiles) { const float dv = v[j].x - c0; s1 += dv; s2 += v[j].y; s3 += dv * dv; }
             }
         }
     };
@@ -502,6 +508,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
     if (stats_early) {
         const int r = row0 + (tid >> 2);
         const float2* sp = (const float2*)g.stats + (r < g.R ? r : 0);
+        c0 = ldgf2(sp).x;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int t = (tid & 3) + 4 * j;
@@ -550,7 +557,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
     if (stats_early && row0 + (tid >> 2) < g.R) {
 #pragma unroll
         for (int j = 0; j < 16; ++j)
-            if ((tid & 3) + 4 * j < tiles) { s1 += sv[j].x; s2 += sv[j].y; s3 += sv[j].x * sv[j].x; }
+            if ((tid & 3) + 4 * j < tiles) { const float dv = sv[j].x - c0; s1 += dv; s2 += sv[j].y; s3 += dv * dv; }
     }
     if (g.stats) {
         s1 = quad_sum(s1);
@@ -558,8 +565,8 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
         s3 = quad_sum(s3);
         if (do_stats && (tid & 3) == 0) {
             // mean of tile means; M2 = sum M2_t + 16 sum (mean_t - mean)^2
-            const float mean = s1 / tiles;
-            const float m2 = s2 + 16.f * fmaxf(s3 - tiles * mean * mean, 0.f);
+            const float mean = c0 + s1 / tiles;   // s1, s3: sums of the tile means' distances from c0 and of their squares
+            const float m2 = s2 + 16.f * fmaxf(s3 - s1 * s1 / tiles, 0.f);
             s_stat[tid >> 2] = mean;
             s_stat[64 + (tid >> 2)] = rsqrtf(m2 / g.K + LN_EPS);
         }
@@ -722,7 +729,7 @@ __device__ __forceinline__ void gemm_unit22(int ph_, int u_, const uint32_t* gta
         }
     }
     // LayerNorm statistics of the unit's 32 rows: four threads per row (threads 0..127)
-    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f, c0 = 0.f;   // c0: shift of the tile means, see gemm_unit
     const int tiles = g.K >> 4;
     const bool do_stats = g.stats != nullptr && tid < 128;
     const bool stats_early = do_stats && tiles <= 64;
@@ -730,6 +737,7 @@ __device__ __forceinline__ void gemm_unit22(int ph_, int u_, const uint32_t* gta
     if (stats_early) {
         const int r = row0 + (tid >> 2);
         const float2* sp = (const float2*)g.stats + (r < g.R ? r : 0);
+        c0 = ldgf2(sp).x;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int t = (tid & 3) + 4 * j;
@@ -763,9 +771,10 @@ __device__ __forceinline__ void gemm_unit22(int ph_, int u_, const uint32_t* gta
             const int r = row0 + (tid >> 2);
             if (r < g.R) {
                 const float2* sp = (const float2*)g.stats + r;
+                c0 = ldgf2(sp).x;
                 for (int t = tid & 3; t < tiles; t += 4) {
                     const float2 v = ldgf2(sp + (size_t)t * g.R);
-                    s1 += v.x; s2 += v.y; s3 += v.x * v.x;
+                    const float dv = v.x - c0; s1 += dv; s2 += v.y; s3 += dv * dv;
                 }
             }
         }
@@ -782,15 +791,15 @@ __device__ __forceinline__ void gemm_unit22(int ph_, int u_, const uint32_t* gta
     if (stats_early && row0 + (tid >> 2) < g.R) {
 #pragma unroll
         for (int j = 0; j < 16; ++j)
-            if ((tid & 3) + 4 * j < tiles) { s1 += sv[j].x; s2 += sv[j].y; s3 += sv[j].x * sv[j].x; }
+            if ((tid & 3) + 4 * j < tiles) { const float dv = sv[j].x - c0; s1 += dv; s2 += sv[j].y; s3 += dv * dv; }
     }
     if (g.stats) {
         s1 = quad_sum(s1);
         s2 = quad_sum(s2);
         s3 = quad_sum(s3);
         if (do_stats && (tid & 3) == 0) {
-            const float mean = s1 / tiles;
-            const float m2 = s2 + 16.f * fmaxf(s3 - tiles * mean * mean, 0.f);
+            const float mean = c0 + s1 / tiles;   // s1, s3: sums of the tile means' distances from c0 and of their squares
+            const float m2 = s2 + 16.f * fmaxf(s3 - s1 * s1 / tiles, 0.f);
             s_stat[tid >> 2] = mean;
             s_stat[64 + (tid >> 2)] = rsqrtf(m2 / g.K + LN_EPS);
         }
@@ -1005,9 +1014,10 @@ __device__ __forceinline__ void gemm_big_impl(const GemmD& g, int nt, int row0) 
     const int tiles = g.K >> 4;
     if (do_stats) {
         const int srow = tid >> 1, sr = row0 + srow;
-        float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        float s1 = 0.f, s2 = 0.f, s3 = 0.f, c0 = 0.f;   // c0: shift of the tile means, see gemm_unit
         if (sr < g.R) {
             const float2* sp = (const float2*)g.stats + sr;
+            c0 = ldgf2(sp).x;
             for (int t0 = tid & 1; t0 < tiles; t0 += 64) {   // 32 loads in flight: one latency up to K = 1024
                 float2 v[32];
 #pragma unroll
@@ -1017,15 +1027,15 @@ __device__ __forceinline__ void gemm_big_impl(const GemmD& g, int nt, int row0) 
                 }
 #pragma unroll
                 for (int j = 0; j < 32; ++j)
-                    if (t0 + 2 * j < tiles) { s1 += v[j].x; s2 += v[j].y; s3 += v[j].x * v[j].x; }
+                    if (t0 + 2 * j < tiles) { const float dv = v[j].x - c0; s1 += dv; s2 += v[j].y; s3 += dv * dv; }
             }
         }
         s1 = pair_sum(s1);
         s2 = pair_sum(s2);
         s3 = pair_sum(s3);
         if ((tid & 1) == 0) {
-            const float mean = s1 / tiles;
-            const float m2 = s2 + 16.f * fmaxf(s3 - tiles * mean * mean, 0.f);
+            const float mean = c0 + s1 / tiles;   // s1, s3: sums of the tile means' distances from c0 and of their squares
+            const float m2 = s2 + 16.f * fmaxf(s3 - s1 * s1 / tiles, 0.f);
             s_stat[srow] = mean;
             s_stat[128 + srow] = rsqrtf(m2 / g.K + LN_EPS);
         }
@@ -1171,11 +1181,12 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
             if (g.epi == SE_RESID && er < g.R) xr4[ct] = ldg4(s.x + (size_t)er * g.N + n0);
         }
     }
-    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f, c0 = 0.f;   // c0: shift of the tile means, see gemm_unit
     const int tiles = g.K >> 4;
     const bool do_stats = g.stats != nullptr;
     if (do_stats && er < g.R) {   // four threads per row, each merges a quarter of the row's tile statistics
         const float2* sp = (const float2*)g.stats + er;
+        c0 = ldgf2(sp).x;
         for (int t0 = tid & 3; t0 < tiles; t0 += 32) {
             float2 v[8];
 #pragma unroll
@@ -1184,7 +1195,8 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
                 v[j] = t < tiles ? ldgf2(sp + (size_t)t * g.R) : make_float2(0.f, 0.f);
             }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) { s1 += v[j].x; s2 += v[j].y; s3 += v[j].x * v[j].x; }
+            for (int j = 0; j < 8; ++j)
+                    if (t0 + 4 * j < tiles) { const float dv = v[j].x - c0; s1 += dv; s2 += v[j].y; s3 += dv * dv; }
         }
     }
     // two chunks of CH k-steps in flight alternately: the loads of one chunk overlap the MFMAs of
@@ -1231,8 +1243,8 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
         s2 = quad_sum(s2);
         s3 = quad_sum(s3);
         if ((tid & 3) == 0) {
-            const float mean = s1 / tiles;
-            const float m2 = s2 + 16.f * fmaxf(s3 - tiles * mean * mean, 0.f);
+            const float mean = c0 + s1 / tiles;   // s1, s3: sums of the tile means' distances from c0 and of their squares
+            const float m2 = s2 + 16.f * fmaxf(s3 - s1 * s1 / tiles, 0.f);
             s_stat[erow] = mean;
             s_stat[64 + erow] = rsqrtf(m2 / g.K + LN_EPS);
         }

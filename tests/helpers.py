@@ -15,8 +15,9 @@ def small_model(seed=7, ln_jitter=0.1, std=0.2, cfg=SMALL):
     return Model(cfg, make_weights(cfg, seed=seed, std=std, ln_jitter=ln_jitter))
 
 
-def planted_lists(future, tree, n_heads, vocab, rng, p_hit=0.7):
-    """Per-head candidate lists with the true future token planted at a random rank.
+def planted_lists(future, tree, n_heads, vocab, rng, p_hit=0.7, p_first=0.0):
+    """Per-head candidate lists with the true future token planted at a random rank (with probability
+    p_first at rank 0: sparse trees reach their full depth along low ranks only).
 
     future[i] is the token that head i+1 should have predicted (may be missing
     near the end).  Lists hold distinct ids like a real top-k list.
@@ -28,6 +29,6 @@ def planted_lists(future, tree, n_heads, vocab, rng, p_hit=0.7):
         pool = np.array([v for v in range(vocab) if v != t], dtype=np.int64)
         ids = rng.choice(pool, size=k, replace=False)
         if t >= 0 and k > 0 and rng.random() < p_hit:
-            ids[int(rng.integers(0, k))] = t
+            ids[0 if rng.random() < p_first else int(rng.integers(0, k))] = t
         lists.append(ids)
     return lists

@@ -141,9 +141,12 @@ class Lockstep:
         self.dev.prefill(self.text, prompts)
         self.out_base = [len(st.emitted) for st in self.sts]
 
-    def step(self, tree, tau, override=None, sample=None):
+    def step(self, tree, tau, override=None, sample=None, fused=False):
         """One lockstep step.  override: per-sequence per-head candidate lists (or None).
-        sample: None, or (temperature, top_p, uniforms [B][M][V+1]) for the stochastic rule."""
+        sample: None, or (temperature, top_p, uniforms [B][M][V+1]) for the stochastic rule.
+        fused: run the library's one-call step (vadusa_step, the call the benchmark times) instead of
+        verification + compaction; its intermediate results stay readable afterwards.  A path can then not be
+        forced where a tie flipped an edge: the library is re-synchronised by a fresh prefill instead."""
         cfg, dev, S = self.cfg, self.dev, self.stats
         margin = MARGIN if sample is None else MARGIN / min(sample[0], 1.0)
         tarr = TreeArrays(tree.parent, tree.rank)
@@ -186,7 +189,11 @@ class Lockstep:
                 return None
             use_override = True
         # (b) verification
-        dev.verify(tarr, tau, override=o_lists if use_override else None, sample=sample)
+        fused_out = None
+        if fused:
+            fused_out = dev.step(tarr, tau, override=o_lists if use_override else None, sample=sample)
+        else:
+            dev.verify(tarr, tau, override=o_lists if use_override else None, sample=sample)
         tok = dev.debug(DBG.TREE_TOK)
         logits = dev.debug(DBG.LOGITS)
         scores = dev.debug(DBG.SCORES) if sample is not None else None
@@ -227,18 +234,30 @@ class Lockstep:
                     assert not firm, f"edge decision differs seq {b} node {n}"
                     S.tie_edge += 1
                     flipped = True
-            got_path = path[b, 1:1 + path[b, 0]].tolist()
-            if not flipped:
-                assert got_path == r["path"], f"path differs seq {b}: {got_path} vs {r['path']}"
-            elif got_path != r["path"]:
-                forced[b] = r["path"]
+            if fused:
+                # the compaction has consumed the path: the accepted tokens the call returned stand for it
+                # (with equal edge decisions the path choice is a function of the tree alone)
+                if not flipped:
+                    assert fused_out[b] == r["accepted"], f"accepted tokens differ seq {b}: {fused_out[b]} vs {r['accepted']}"
+                elif fused_out[b] != r["accepted"]:
+                    forced[b] = r["path"]
+            else:
+                got_path = path[b, 1:1 + path[b, 0]].tolist()
+                if not flipped:
+                    assert got_path == r["path"], f"path differs seq {b}: {got_path} vs {r['path']}"
+                elif got_path != r["path"]:
+                    forced[b] = r["path"]
             S.accepted_hist.append(len(r["path"]))
             if sample is not None:
                 self.root_gap[b] = firm_top(variants, r["path"][-1], margin)
             else:
                 self.root_gap.pop(b, None)
         # (c) compaction (forced to the oracle's path where a tie flipped an edge)
-        if forced:
+        if fused:
+            if forced:
+                self.resync()
+                return None
+        elif forced:
             for b in range(self.B):
                 if b in forced:
                     dev.kv_compact(b, forced[b])

@@ -61,6 +61,7 @@ def test_tiny_fp32_full_generation(tau):
     _say(f"  steps {s.steps} compared {s.compared} ties root/list/edge {s.tie_root}/{s.tie_list}/{s.tie_edge} "
          f"logit err {s.max_logit_err:.2e} kv err {s.max_kv_err:.2e}")
     assert s.compared >= 0.8 * s.steps
+    assert s.tie_edge + s.tie_root <= 0.05 * s.steps, "more than 5 % of the steps lost to decisions inside the margin"
     assert s.max_logit_err < 1e-4
 
 
@@ -483,3 +484,140 @@ def test_many_row_kernel_with_128_node_tree(monkeypatch):
     s = ls.stats
     _say(f"  compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e}")
     assert s.compared >= 1
+
+
+def test_valle_b1_planted_drafts_fused_step(valle):
+    """Configuration 2 at full size through the one-call step the benchmark times (vadusa_step), with the true
+    continuation planted among the candidates: accepted paths of every length 1..5, so the compaction units
+    of all 12 layers and 16 heads move several rows, the continuation starts from deep nodes, and the cache
+    is compared with the oracle's on every layer."""
+    wl, W = valle
+    cfg = wl.model
+    text, prompt = make_tokens(wl)
+    tree = make_tree(wl.tree_nodes, wl.topk_caps)
+    model = O.Model(cfg, W)
+    _say("valle_b1 planted drafts, fused step: greedy continuation on the oracle")
+    greedy = O.generate(model, text[0], prompt[0], chain_tree(1), 1, 90, ignore_eos=True)[0]
+    rng = np.random.default_rng(31)
+    ls = _lock(cfg, W, text, prompt, wl.tree_nodes)
+    steps = 0
+    while steps < 26 and len(ls.sts[0].emitted) < 84:
+        st = ls.sts[0]
+        n = len(st.emitted)
+        on = st.emitted == greedy[:n] and st.root == greedy[n]
+        fut = greedy[n + 1:n + 1 + cfg.n_draft_heads] if on else []
+        lists = planted_lists(fut, tree, cfg.n_draft_heads, cfg.n_logits, rng, p_hit=0.9, p_first=0.8)
+        ls.step(tree, 1 + steps % 2, override=[lists], fused=True)
+        steps += 1
+    ls.check_kv(layers=list(range(cfg.n_layers)))
+    s = ls.stats
+    _say(f"  steps {s.steps} compared {s.compared} accepted lengths {np.bincount(s.accepted_hist).tolist()} "
+         f"ties {s.tie_root}/{s.tie_list}/{s.tie_edge} logit err {s.max_logit_err:.2e} kv err {s.max_kv_err:.2e}")
+    assert s.steps >= 20 and s.compared >= 16
+    assert set(s.accepted_hist) >= {1, 2, 3, 4, 5}
+
+
+@pytest.mark.parametrize("heads,nodes", [(4, 96), (6, 64), (6, 128)])
+def test_ablation_trees_full_size(heads, nodes):
+    """The ablation shapes of Sec. 3.1.3 (four or six draft heads, 64 / 96 / 128 candidates) on the 12-layer
+    d = 1024 model: 96 nodes are six query tiles, six heads give paths of up to seven rows."""
+    cfg = dataclasses.replace(PRESETS["valle_b1"].model, n_draft_heads=heads, max_positions=640)
+    _say(f"ablation shape: {heads} heads, {nodes} nodes")
+    W = make_weights(cfg, 20241021 + heads)
+    rng = np.random.default_rng(61 + nodes)
+    text, prompt = rand_tokens(cfg, rng, 1, (64, 64), (225, 225))
+    tree = make_tree(nodes, (10,) * heads)
+    assert tree.n_nodes == nodes
+    ls = _lock(cfg, W, text, prompt, nodes)
+    ls.step(tree, 1)
+    ls.step(tree, 3, fused=True)
+    ls.check_kv(layers=[0, 11])
+    s = ls.stats
+    _say(f"  compared {s.compared}/{s.steps} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} logit err {s.max_logit_err:.2e}")
+    assert s.compared >= 1
+
+
+def test_large_vocabulary_16k_full_depth():
+    """The 16 001-logit vocabulary on all 12 layers: one step."""
+    wl = PRESETS["vocab16k_b1"]
+    cfg = dataclasses.replace(wl.model, max_positions=512)
+    _say("vocabulary 16k, 12 layers")
+    W = make_weights(cfg, wl.seed)
+    rng = np.random.default_rng(46)
+    text, prompt = rand_tokens(cfg, rng, 1, (32, 32), (100, 100))
+    tree = make_tree(64, (10,) * 4)
+    ls = _lock(cfg, W, text, prompt, 64)
+    ls.step(tree, 4, fused=True)
+    s = ls.stats
+    _say(f"  compared {s.compared}/{s.steps} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} logit err {s.max_logit_err:.2e}")
+    assert s.compared + s.tie_root + s.tie_edge >= 1
+
+
+def _extended(prompt, vocab, extra, seed):
+    rng = np.random.default_rng(seed)
+    return [np.concatenate([p, rng.integers(0, vocab, extra).astype(np.int32)]) for p in prompt]
+
+
+def test_hubert_b16_consecutive_steps_and_end_of_generation():
+    """Configuration 3 at full size beyond one verification: three consecutive steps from the start of
+    generation, and one verification at the committed lengths of its end (620..780), the oracle following
+    sampled sequences."""
+    from parity import sampled_check
+    wl = PRESETS["hubert_b16"]
+    _say("hubert_b16: three consecutive steps")
+    W = make_weights(wl.model, wl.seed)
+    text, prompt = make_tokens(wl)
+    tree = make_tree(wl.tree_nodes, wl.topk_caps)
+    n, skipped, err = sampled_check(wl.model, W, text, prompt, tree, 3, [2, 13], kv_layers=(0, 6, 11), steps=3)
+    _say(f"  compared {n} skipped {skipped} logit err {err:.2e}")
+    assert n >= 4
+    deep = _extended(prompt, wl.model.speech_vocab, wl.n_generate, 71)
+    _say(f"hubert_b16 at the end of generation: L = {min(len(t) + len(p) for t, p in zip(text, deep))}.."
+         f"{max(len(t) + len(p) for t, p in zip(text, deep))}")
+    n, skipped, err = sampled_check(wl.model, W, text, deep, tree, 3, [7, 15], kv_layers=(11,))
+    _say(f"  compared {n} skipped {skipped} logit err {err:.2e}")
+    assert n >= 1
+
+
+def test_throughput_b64_consecutive_steps_and_end_of_generation():
+    """Configuration 5 at full size beyond one verification at tau = 8: three consecutive steps at tau = 1, 8, 1
+    and one verification at L = 1039 (the end of generation; the cache holds 1200 rows per sequence)."""
+    from parity import sampled_check
+    wl = PRESETS["throughput_b64"]
+    _say("throughput_b64: three consecutive steps, tau 1 / 8 / 1")
+    W = make_weights(wl.model, wl.seed)
+    text, prompt = make_tokens(wl)
+    tree = make_tree(wl.tree_nodes, wl.topk_caps)
+    n, skipped, err = sampled_check(wl.model, W, text, prompt, tree, [1, 8, 1], [9, 50], kv_layers=(0, 11), steps=3)
+    _say(f"  compared {n} skipped {skipped} logit err {err:.2e}")
+    assert n >= 4
+    deep = _extended(prompt, wl.model.speech_vocab, wl.n_generate, 72)
+    _say(f"throughput_b64 at the end of generation: L = {len(text[0]) + len(deep[0])}")
+    n, skipped, err = sampled_check(wl.model, W, text, deep, tree, 1, [33], kv_layers=(11,))
+    _say(f"  compared {n} skipped {skipped} logit err {err:.2e}")
+    assert n + skipped == 1
+
+
+def test_residual_rows_with_large_mean():
+    """Rows of the residual stream whose mean is several times their spread (a common offset on the
+    out-projection and FFN biases; the N(0, 0.02) weights never produce one): the LayerNorm folded into the
+    next map works on the bf16 copy of the raw residual row and on tile statistics, so its error grows with
+    mean / spread (the copy's rounding is relative to the row's magnitude); this case sits where the bf16
+    copy still carries the spread to within the tolerance."""
+    cfg = small_cfg("bf16", layers=3, d=256, heads=3, V=300, maxpos=256)
+    _say("residual rows with a large mean")
+    W = make_weights(cfg, 33, std=STD["bf16"], ln_jitter=0.1)
+    from synth.weights import round_to_bf16
+    for l in range(cfg.n_layers):
+        W[f"L{l}.bo"] = round_to_bf16(W[f"L{l}.bo"] + 0.25)
+        W[f"L{l}.b2"] = round_to_bf16(W[f"L{l}.b2"] + 0.5)
+    rng = np.random.default_rng(34)
+    text, prompt = rand_tokens(cfg, rng, 2, (5, 9), (30, 45))
+    tree = make_tree(40, (6, 4, 3))
+    ls = _lock(cfg, W, text, prompt, 40)
+    for tau in (1, 3, 2):
+        ls.step(tree, tau)
+    ls.check_kv(layers=[0, 2])
+    s = ls.stats
+    _say(f"  compared {s.compared}/{s.steps} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} logit err {s.max_logit_err:.2e} kv err {s.max_kv_err:.2e}")
+    assert s.compared >= 2
