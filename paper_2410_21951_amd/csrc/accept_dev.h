@@ -343,7 +343,7 @@ __device__ inline void dev_commit_kv(const Dims& D, const DevState& s, int layer
     const int cnt = ldci(s.acc_len + b);
     if (cnt <= 0) return;
     const int L0 = ldci(s.L + b) - cnt;
-    const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
+    const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
     T* Kh = (T*)s.Kc + hb;
     T* Vh = (T*)s.Vc + hb;
     T kr[VADUSA_MAX_DRAFT_HEADS + 1], vr[VADUSA_MAX_DRAFT_HEADS + 1];
@@ -351,14 +351,14 @@ __device__ inline void dev_commit_kv(const Dims& D, const DevState& s, int layer
     for (int j = 0; j < VADUSA_MAX_DRAFT_HEADS + 1; ++j)
         if (j < cnt) {
             const int src = ldci(path + 1 + j);
-            kr[j] = Kh[(size_t)(L0 + src) * 64 + dim];
-            vr[j] = Vh[(size_t)dim * D.maxpos + L0 + src];
+            kr[j] = Kh[kc_off(L0 + src, dim)];
+            vr[j] = Vh[vc_off(L0 + src, dim)];
         }
 #pragma unroll
     for (int j = 0; j < VADUSA_MAX_DRAFT_HEADS + 1; ++j)
         if (j < cnt) {
-            Kh[(size_t)(L0 + j) * 64 + dim] = kr[j];
-            Vh[(size_t)dim * D.maxpos + L0 + j] = vr[j];
+            Kh[kc_off(L0 + j, dim)] = kr[j];
+            Vh[vc_off(L0 + j, dim)] = vr[j];
         }
 }
 

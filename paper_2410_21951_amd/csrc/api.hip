@@ -233,7 +233,7 @@ static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vecto
     for (size_t i = 0; i < Hh; ++i) {
         mat(&dw[i].W1, d, d); vec(&dw[i].b1, d); mat(&dw[i].W2, V1, d);
     }
-    const size_t kv = (size_t)c.n_layers * B * c.n_heads * P * 64 * e;
+    const size_t kv = (size_t)c.n_layers * B * c.n_heads * kv_cap((int)P) * 64 * e;
     st.Kc = cv.take(kv);
     st.Vc = cv.take(kv);
     st.x = (float*)cv.take(R * d * 4);
@@ -542,7 +542,7 @@ static void forward(vadusa_ctx* c, const Dims& D, int table, int prefill_mode, b
     const DevState& s = c->s;
     hipStream_t st = c->stream;
     const int R = D.B * D.M;
-    const size_t kv_layer = (size_t)D.Bmax * D.nH * D.maxpos * 64 * c->elem;
+    const size_t kv_layer = (size_t)D.Bmax * D.nH * kv_cap(D.maxpos) * 64 * c->elem;
     launch_embed(D, s, dt, prefill_mode, table, st);
     for (int l = 0; l < D.Ly; ++l) {
         const LayerW& w = c->layers[l];
@@ -989,7 +989,7 @@ extern "C" int vadusa_debug_read_kv(vadusa_ctx* c, int32_t layer, int32_t seq, i
         pos0 < 0 || npos < 1 || pos0 + npos > c->cfg.max_positions)
         return fail(c, VADUSA_EINVAL, "bad layer / seq / range");
     const Dims D = make_dims(c, c->batch, c->M);
-    const size_t kv_layer = (size_t)D.Bmax * D.nH * D.maxpos * 64 * c->elem;
+    const size_t kv_layer = (size_t)D.Bmax * D.nH * kv_cap(D.maxpos) * 64 * c->elem;
     const char* base = (const char*)(which ? c->s.Vc : c->s.Kc) + layer * kv_layer;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     { int rc = check_kerr(c); if (rc) return rc; }
@@ -1038,7 +1038,7 @@ extern "C" int vadusa_debug_read_kv_static(vadusa_ctx* c, int32_t layer, int32_t
                     npos, D.d, VADUSA_STATIC_KV_FLOATS, VADUSA_STATIC_KV_FLOATS / D.d);
     float* stage = nullptr;
     { int rc = static_scratch(c, &stage); if (rc) return rc; }
-    const size_t kv_layer = (size_t)D.Bmax * D.nH * D.maxpos * 64 * c->elem;
+    const size_t kv_layer = (size_t)D.Bmax * D.nH * kv_cap(D.maxpos) * 64 * c->elem;
     const char* base = (const char*)(which ? c->s.Vc : c->s.Kc) + layer * kv_layer;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     { int rc = check_kerr(c); if (rc) return rc; }

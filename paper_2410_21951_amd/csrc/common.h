@@ -88,6 +88,23 @@ __device__ __forceinline__ float ldcf(const float* p) {
 __device__ __forceinline__ size_t toff(int r, int k, int nks) {
     return ((size_t)((r >> 4) * nks + (k >> 5)) * 64 + (r & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
 }
+// KV cache of one (layer, sequence, head): kv_cap(max_positions) positions (whole blocks of 32) x 64 dimensions,
+// kept in the operand tiles of the attention units, so that every operand of a 32-key block is one contiguous KiB
+// per wave load (a row-major cache makes such a load touch 16 cache lines and use half of each):
+//   K: [block of 32 keys][key tile t][k-step s][lane][8]: key k = pos & 31 sits in tile t = (k >> 2) & 1 (tile 0:
+//      keys 0-3, 8-11, 16-19, 24-27 of the block; tile 1: the others) at row c = ((k >> 3) << 2) | (k & 3); k-step
+//      s = dim >> 5; lane = c + 16 * ((dim & 31) >> 3).  (With this row order the lane that holds query c's scores
+//      after S^T = K Q^T holds them for eight consecutive keys: exactly a B fragment of P^T for O^T += V^T P^T.)
+//   V: [block of 32 keys][dimension tile dt = dim >> 4][lane][8]: lane = (dim & 15) + 16 * ((pos & 31) >> 3),
+//      element pos & 7 (V transposed: a lane holds eight consecutive positions of one dimension).
+__host__ __device__ inline int kv_cap(int maxpos) { return (maxpos + 31) & ~31; }
+__host__ __device__ inline size_t kc_off(int pos, int dim) {
+    const int k = pos & 31, t = (k >> 2) & 1, c = ((k >> 3) << 2) | (k & 3);
+    return (size_t)(pos >> 5) * 2048 + (size_t)(((t * 2 + (dim >> 5)) * 64 + c + 16 * ((dim & 31) >> 3)) * 8 + (dim & 7));
+}
+__host__ __device__ inline size_t vc_off(int pos, int dim) {
+    return (size_t)(pos >> 5) * 2048 + (size_t)((((dim >> 4) * 64) + (dim & 15) + 16 * ((pos & 31) >> 3)) * 8 + (pos & 7));
+}
 // Two floats to a pair of bf16 (round to nearest even): one v_cvt_pk_bf16_f32 on the device.
 #if defined(__HIP_DEVICE_COMPILE__)
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {

@@ -102,9 +102,9 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, int r, int n, float 
         const int b = r / a.M, node = r % a.M;
         const int pos = a.L[b] + node;
         if (pos < a.maxpos) {
-            const size_t hb = ((size_t)b * a.nH + head) * a.maxpos * 64;
-            if (which) stf((T*)a.Vc + hb + (size_t)dim * a.maxpos + pos, acc);   // V is kept [dim][pos]
-            else stf((T*)a.Kc + hb + (size_t)pos * 64 + dim, acc);               // K is kept [pos][dim]
+            const size_t hb = ((size_t)b * a.nH + head) * kv_cap(a.maxpos) * 64;
+            if (which) stf((T*)a.Vc + hb + vc_off(pos, dim), acc);
+            else stf((T*)a.Kc + hb + kc_off(pos, dim), acc);
         }
         break;
     }
@@ -161,7 +161,7 @@ __global__ void k_attn_simple(Dims D, DevState s, int layer, int table) {
     T* out = (T*)s.att + (size_t)r * D.d + head * 64;
     if (n >= s.n_rows[b]) { stf(out + lane, 0.f); return; }
     const int L = s.L[b];
-    const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
+    const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
     const T* Kh = (const T*)s.Kc + hb;
     const T* Vh = (const T*)s.Vc + hb;
     const T* qp = (const T*)s.q + (size_t)r * D.d + head * 64;
@@ -180,16 +180,14 @@ __global__ void k_attn_simple(Dims D, DevState s, int layer, int table) {
             const int mm = j - L;
             if (table == 1 ? mm > n : !((mrow[(mm >> 5) & (MASK_WORDS - 1)] >> (mm & 31)) & 1u)) continue;
         }
-        const T* kr = Kh + (size_t)j * 64;
         float sc = 0.f;
 #pragma unroll
-        for (int i = 0; i < 64; ++i) sc = fmaf(q[i], ldf(kr + i), sc);
+        for (int i = 0; i < 64; ++i) sc = fmaf(q[i], ldf(Kh + kc_off(j, i)), sc);
         const float mn = fmaxf(m, sc);
         const float corr = __expf(m - mn), p = __expf(sc - mn);
         l = l * corr + p;
-        const T* vr = Vh + j;
 #pragma unroll
-        for (int i = 0; i < 64; ++i) o[i] = o[i] * corr + p * ldf(vr + (size_t)i * D.maxpos);
+        for (int i = 0; i < 64; ++i) o[i] = o[i] * corr + p * ldf(Vh + vc_off(j, i));
         m = mn;
     }
     const float mx = wave_max(m);
@@ -249,15 +247,14 @@ void launch_advance(const DevState& s, int B, hipStream_t st) {
     hipLaunchKernelGGL(k_advance, dim3((B + 63) / 64), dim3(64), 0, st, s, B);
 }
 
-// out[p][head*64 + dim] = K[seq][head][pos0 + p][dim]  or  V[seq][head][dim][pos0 + p]
+// out[p][head*64 + dim] = K or V of (seq, head, position pos0 + p, dim)
 template <class T>
 __global__ void k_read_kv(Dims D, const T* __restrict__ cache, int seq, int which, int pos0, int npos, float* out) {
     const int p = blockIdx.x;
     for (int c = threadIdx.x; c < D.d; c += blockDim.x) {
         const int head = c >> 6, dim = c & 63;
-        const size_t hb = ((size_t)seq * D.nH + head) * D.maxpos * 64;
-        out[(size_t)p * D.d + c] = which ? ldf(cache + hb + (size_t)dim * D.maxpos + pos0 + p)
-                                         : ldf(cache + hb + (size_t)(pos0 + p) * 64 + dim);
+        const size_t hb = ((size_t)seq * D.nH + head) * kv_cap(D.maxpos) * 64;
+        out[(size_t)p * D.d + c] = which ? ldf(cache + hb + vc_off(pos0 + p, dim)) : ldf(cache + hb + kc_off(pos0 + p, dim));
     }
 }
 void launch_read_kv(const Dims& D, const void* cache_layer, int seq, int which, int pos0, int npos, float* out, int dtype, hipStream_t st) {

@@ -625,13 +625,13 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
                 const int which = kv_which, cc = kv_cc + (tid & 3) * 4, head = cc >> 6, dim = cc & 63;
                 const int pos = kv_L + node;
                 if (pos < D.maxpos && kv_rows > 0) {
-                    const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
+                    const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
                     if (which) {
-                        bf16_t* vp = (bf16_t*)s.Vc + hb + (size_t)dim * D.maxpos + pos;   // V is kept [dim][pos]
+                        bf16_t* vp = (bf16_t*)s.Vc + hb + vc_off(pos, dim);   // four dimensions of one position: four lanes of a value tile
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) stw16(vp + (size_t)j * D.maxpos, f2bf(v[j]));
+                        for (int j = 0; j < 4; ++j) stw16(vp + j * 8, f2bf(v[j]));
                     } else {
-                        stw64((bf16_t*)s.Kc + hb + (size_t)pos * 64 + dim, pk);             // K is kept [pos][dim]
+                        stw64((bf16_t*)s.Kc + hb + kc_off(pos, dim), pk);   // four dimensions of one key: half of a lane's piece
                     }
                 }
                 break;
@@ -843,13 +843,13 @@ __device__ __forceinline__ void gemm_unit22(int ph_, int u_, const uint32_t* gta
                     const int cc = kv_cc + ecg * 4, head = cc >> 6, dim = cc & 63;
                     const int pos = kv_L + node;
                     if (pos < D.maxpos && kv_rows > 0) {
-                        const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
+                        const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
                         if (kv_which) {
-                            bf16_t* vp = (bf16_t*)s.Vc + hb + (size_t)dim * D.maxpos + pos;   // V is kept [dim][pos]
+                            bf16_t* vp = (bf16_t*)s.Vc + hb + vc_off(pos, dim);   // four dimensions of one position: four lanes of a value tile
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) stw16(vp + (size_t)j * D.maxpos, f2bf(v[j]));
+                            for (int j = 0; j < 4; ++j) stw16(vp + j * 8, f2bf(v[j]));
                         } else {
-                            stw64((bf16_t*)s.Kc + hb + (size_t)pos * 64 + dim, pk);         // K is kept [pos][dim]
+                            stw64((bf16_t*)s.Kc + hb + kc_off(pos, dim), pk);   // four dimensions of one key: half of a lane's piece
                         }
                     }
                 }
@@ -908,13 +908,13 @@ __device__ __forceinline__ void wide_store(const GemmD& g, int r, int n0, int ti
             const int which = n0 / D.d - 1, cc = n0 % D.d, head = cc >> 6, dim = cc & 63;
             const int pos = ldg(s.L + b) + node;
             if (pos < D.maxpos && ldg(s.n_rows + b) > 0) {
-                const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * D.maxpos) * 64;
+                const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
                 if (which) {
-                    bf16_t* vp = (bf16_t*)s.Vc + hb + (size_t)dim * D.maxpos + pos;
+                    bf16_t* vp = (bf16_t*)s.Vc + hb + vc_off(pos, dim);   // four dimensions of one position: four lanes of a value tile
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) stw16(vp + (size_t)j * D.maxpos, f2bf(v[j]));
+                    for (int j = 0; j < 4; ++j) stw16(vp + j * 8, f2bf(v[j]));
                 } else {
-                    stw64((bf16_t*)s.Kc + hb + (size_t)pos * 64 + dim, pk);
+                    stw64((bf16_t*)s.Kc + hb + kc_off(pos, dim), pk);   // four dimensions of one key: half of a lane's piece
                 }
             }
             break;
@@ -1346,7 +1346,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
         return;
     }
     const int T = min(L + D.M, D.maxpos);
-    const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + h) * D.maxpos) * 64;
+    const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + h) * kv_cap(D.maxpos)) * 64;
     const bf16_t* Kh = (const bf16_t*)s.Kc + hb;
     const bf16_t* Vh = (const bf16_t*)s.Vc + hb;
 
@@ -1356,16 +1356,13 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     for (int i = 0; i < 4; ++i) O[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
     const int nblk = (T + 31) >> 5;
     // operands of one 32-key block: K rows of the two 16-key tiles (two k-steps each), V^T tiles
+    // (the cache keeps them as the MFMA operands themselves: eight contiguous KiB per block; rows of the last block
+    // beyond the sequence's end exist, the cache holds whole blocks, and are masked out below)
     auto load_block = [&](int blk, uint4* kv /*[8]*/) {
-        const int p0 = blk << 5;
-        const int keyA = p0 + 8 * (c >> 2) + (c & 3), keyB = keyA + 4;
-        const bf16_t* ka = Kh + (size_t)(keyA < T ? keyA : 0) * 64 + 8 * gq;
-        const bf16_t* kb = Kh + (size_t)(keyB < T ? keyB : 0) * 64 + 8 * gq;
-        kv[0] = ldg4(ka); kv[1] = ldg4(ka + 32);
-        kv[2] = ldg4(kb); kv[3] = ldg4(kb + 32);
-        const int v0 = p0 + 8 * gq, vv = v0 < T ? v0 : 0;
+        const bf16_t* kb = Kh + (size_t)blk * 2048 + lane * 8;
+        const bf16_t* vb = Vh + (size_t)blk * 2048 + lane * 8;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) kv[4 + dt] = ldg4(Vh + (size_t)(dt * 16 + c) * D.maxpos + vv);
+        for (int i = 0; i < 4; ++i) { kv[i] = ldg4(kb + i * 512); kv[4 + i] = ldg4(vb + i * 512); }
     };
     uint4 cur[8], nxt[8], nx2[8];   // two blocks in flight behind the one being computed
     const int blk0 = ALLQ ? wave % wpq : wave, bstep = ALLQ ? wpq : 4;   // the waves of a query tile split its key blocks
@@ -1516,6 +1513,206 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
 }
 
 // ---------------------------------------------------------------------------
+// Attention unit of the few-row kernel (one head, 16 query rows of one sequence; the algorithm, operand layouts and
+// merge of attn_unit<false>), in two parts.
+//  * attn_prepare works out everything that does not depend on the phase before it: which (sequence, head, query
+//    tile) the unit is, lengths, block count, the lane's offsets and its mask words (the tree tables are fixed during
+//    a launch).  The kernel calls it BEFORE the grid barrier in front of the attention phase, while the workgroup
+//    would only wait, so that after the barrier the first thing a wave does is to ask for the queries and its keys
+//    (the first key block is requested ~0.4 us into the phase instead of ~2 us).
+//  * attn_few is the unit itself.
+// ---------------------------------------------------------------------------
+struct AttnPrep {
+    int valid;                 // the descriptor describes unit `u` of phase `ph`
+    int ph, u;
+    int live;                  // 0: padding unit (nothing to do)
+    int layer, b, h, qt, L, T, n_rows, nblk;
+    const bf16_t *Kh, *Vh, *ql;
+    bf16_t* att;
+    uint32_t mword[4];         // per lane: tree-mask words of the lane's query
+    int node;                  // per lane: the lane's query row inside the tree
+    uint32_t qoff, koff;       // per lane: element offsets of the lane's query piece and of its piece of a key / value tile
+};
+
+template <bool CAUSAL>
+__device__ __forceinline__ void attn_prepare(int ph_, int u_, AttnPrep& A) {
+    const int ph = __builtin_amdgcn_readfirstlane(ph_), u = __builtin_amdgcn_readfirstlane(u_);
+    const StepParams& P = sP;
+    const Dims& D = P.D;
+    const DevState& s = P.s;
+    const int lane = threadIdx.x & 63, gq = lane >> 4, c = lane & 15;
+    A.valid = 1; A.ph = ph; A.u = u; A.live = 0;
+    A.layer = (ph - 1) / 5;
+    // unit = (query tile) * pad8(B * nH) + (sequence, head): the query tiles of one head run on one XCD
+    // (workgroup i is on XCD i mod 8) and share its L2 for that head's K / V rows
+    const int BH = pad8(D.B * D.nH);
+    int bh;
+    if ((BH & (BH - 1)) == 0) { bh = u & (BH - 1); A.qt = u >> __builtin_ctz(BH); }
+    else { bh = u % BH; A.qt = u / BH; }
+    if (bh >= D.B * D.nH) return;
+    if ((D.nH & (D.nH - 1)) == 0) { A.h = bh & (D.nH - 1); A.b = bh >> __builtin_ctz(D.nH); }
+    else { A.h = bh % D.nH; A.b = bh / D.nH; }
+    A.live = 1;
+    A.b = __builtin_amdgcn_readfirstlane(A.b); A.h = __builtin_amdgcn_readfirstlane(A.h); A.qt = __builtin_amdgcn_readfirstlane(A.qt);
+    const bool seq_cached = A.b < ST_SEQ_CACHE;
+    A.n_rows = __builtin_amdgcn_readfirstlane(seq_cached ? s_seqRows[A.b] : ldg(s.n_rows + A.b));
+    A.L = __builtin_amdgcn_readfirstlane(seq_cached ? s_seqL[A.b] : ldg(s.L + A.b));
+    A.T = __builtin_amdgcn_readfirstlane(min(A.L + D.M, D.maxpos));
+    A.nblk = (A.T + 31) >> 5;
+    const size_t hb = ((((size_t)A.layer * D.Bmax + A.b) * D.nH + A.h) * kv_cap(D.maxpos)) * 64;
+    A.Kh = uniform_ptr((const bf16_t*)s.Kc + hb);
+    A.Vh = uniform_ptr((const bf16_t*)s.Vc + hb);
+    A.ql = uniform_ptr((const bf16_t*)s.q + (size_t)A.layer * s.act_stride);
+    A.att = uniform_ptr((bf16_t*)s.att + (size_t)A.layer * s.act_stride);
+    A.node = min(A.qt * 16 + c, D.M - 1);
+    A.qoff = (uint32_t)toff(A.b * D.M + A.node, A.h * 64 + 8 * gq, D.d >> 5);
+    A.koff = (uint32_t)(lane * 8);
+    uint4 mw = make_uint4(0, 0, 0, 0);
+    if constexpr (!CAUSAL) mw = ldg4(s.t_mask[P.table] + (size_t)A.node * MASK_WORDS);
+    A.mword[0] = mw.x; A.mword[1] = mw.y; A.mword[2] = mw.z; A.mword[3] = mw.w;
+}
+
+template <bool CAUSAL>
+__device__ __forceinline__ void attn_few(const AttnPrep& A) {
+    if (!A.live) return;
+    const StepParams& P = sP;
+    extern __shared__ uint4 smem[];
+    const Dims& D = P.D;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, gq = lane >> 4, c = lane & 15;
+    const int b = A.b, h = A.h, qt = A.qt, L = A.L, T = A.T, node = A.node, nblk = A.nblk;
+    bf16_t* att = A.att;
+    if (A.n_rows == 0) {
+        const int q = tid >> 4, d0 = (tid & 15) * 4, nd = qt * 16 + q;
+        if (nd < D.M) stw64(att + toff(b * D.M + nd, h * 64 + d0, D.d >> 5), 0ull);
+        return;
+    }
+    tp(A.ph, 5);
+    const bf16x8_t Q0 = __builtin_bit_cast(bf16x8_t, ldg4(A.ql + A.qoff));
+    const bf16x8_t Q1 = __builtin_bit_cast(bf16x8_t, ldg4(A.ql + A.qoff + 512));   // 32 columns on: the next k-step of the tile (64 lanes x 8 values)
+    // operands of one 32-key block: the two 16-key tiles of K (two k-steps each) and the four dimension tiles of V^T,
+    // kept in the cache as the MFMA operands themselves: eight contiguous KiB.  Rows of the last block beyond the
+    // sequence's end exist (the cache holds whole blocks) and are masked out below.
+    auto load_block = [&](int blk, uint4* kv /*[8]*/) {
+        const bf16_t* kb = A.Kh + (uint32_t)blk * 2048u + A.koff;
+        const bf16_t* vb = A.Vh + (uint32_t)blk * 2048u + A.koff;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { kv[i] = ldg4(kb + i * 512); kv[4 + i] = ldg4(vb + i * 512); }
+    };
+    float m_run = -1e30f, l_run = 0.f;
+    f32x4_t O[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) O[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    // The waves take the blocks round-robin, two blocks in flight behind the one being computed.  (Measured
+    // alternatives on the 64-node workload, attention phase at L ~ 400: this loop 8.0 us; contiguous quarters in
+    // groups of three blocks, six blocks in flight and one softmax update per group, 9.4 us: a block costs a wave
+    // ~0.4 us of softmax arithmetic and MFMA issue, and the deeper queue only delays the first block's work.)
+    uint4 cur[8], nxt[8], nx2[8];
+    if (wave < nblk) load_block(wave, cur);
+    if (wave + 4 < nblk) load_block(wave + 4, nxt);
+    tp(A.ph, 6);
+    for (int blk = wave; blk < nblk; blk += 4) {
+        if (blk + 8 < nblk) load_block(blk + 8, nx2);
+        const int p0 = blk << 5;
+        const int v0 = p0 + 8 * gq;
+        f32x4_t sa = (f32x4_t){0.f, 0.f, 0.f, 0.f}, sb = sa;
+        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, cur[0]), Q0, sa, 0, 0, 0);
+        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, cur[1]), Q1, sa, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, cur[2]), Q0, sb, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, cur[3]), Q1, sb, 0, 0, 0);
+        // this lane: query c, keys v0 + 0..3 (sa) and v0 + 4..7 (sb)
+        // online softmax of the block: scores -> probabilities (bf16 pairs in pk), running max / sum.
+        // Instantiated twice: blocks inside the committed cache need no mask tests at all.
+        uint32_t pk[4];
+        float m_new, corr, psum = 0.f;
+        auto softmax_block = [&](const unsigned okm) {
+            float sc[8];
+            float mx = -1e30f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float sv = (j < 4 ? sa[j] : sb[j - 4]) * 0.125f;
+                sc[j] = (okm >> j) & 1u ? sv : -1e30f;
+                mx = fmaxf(mx, sc[j]);
+            }
+            mx = rows_max(mx);
+            m_new = fmaxf(m_run, mx);
+            corr = __expf(m_run - m_new);
+#pragma unroll
+            for (int j = 0; j < 8; j += 2) {
+                const float p0f = (okm >> j) & 1u ? __expf(sc[j] - m_new) : 0.f;
+                const float p1f = (okm >> (j + 1)) & 1u ? __expf(sc[j + 1] - m_new) : 0.f;
+                psum += p0f + p1f;
+                pk[j >> 1] = pack_bf16(p0f, p1f);
+            }
+        };
+        if (p0 + 32 > L) {   // the block reaches into the tree rows (same for the whole wave)
+            unsigned okm = 0;   // which of the lane's 8 keys the query may see
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int key = v0 + j;
+                bool okj = key < L;
+                if (!okj && key < T) {
+                    const int mm = key - L;
+                    if constexpr (CAUSAL) okj = mm <= node;
+                    else {
+                        const uint32_t mw_ = mm < 32 ? A.mword[0] : mm < 64 ? A.mword[1] : mm < 96 ? A.mword[2] : A.mword[3];   // no indexed access: the words stay in registers
+                        okj = (mw_ >> (mm & 31)) & 1u;
+                    }
+                }
+                okm |= okj ? (1u << j) : 0u;
+            }
+            softmax_block(okm);
+        } else {
+            softmax_block(0xffu);
+        }
+        l_run = l_run * corr + psum;
+        m_run = m_new;
+        const bf16x8_t pfrag = __builtin_bit_cast(bf16x8_t, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            O[dt] *= corr;
+            O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, cur[4 + dt]), pfrag, O[dt], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { cur[i] = nxt[i]; nxt[i] = nx2[i]; }
+    }
+    tp(A.ph, 3);
+    l_run = rows_sum(l_run);
+    // merge the four waves: sm_m / sm_l [wave][query], sm_o [wave][dim][query]
+    float* sm_o = (float*)smem;
+    float* sm_m = sm_o + 4 * 64 * 16;
+    float* sm_l = sm_m + 64;
+    __syncthreads();
+    tp(A.ph, 7);
+    if (gq == 0) { sm_m[wave * 16 + c] = m_run; sm_l[wave * 16 + c] = l_run; }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sm_o[(wave * 64 + dt * 16 + 4 * gq + i) * 16 + c] = O[dt][i];
+    __syncthreads();
+    {
+        const int q = tid >> 4, d0 = (tid & 15) * 4, nd = qt * 16 + q;
+        float mstar = sm_m[q];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) mstar = fmaxf(mstar, sm_m[w * 16 + q]);
+        float f[4], lsum = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { f[w] = __expf(sm_m[w * 16 + q] - mstar); lsum += f[w] * sm_l[w * 16 + q]; }
+        const float inv = 1.f / lsum;
+        float o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float a = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) a += f[w] * sm_o[(w * 64 + d0 + j) * 16 + q];
+            o[j] = a * inv;
+        }
+        if (nd < D.M)
+            stw64(att + toff(b * D.M + nd, h * 64 + d0, D.d >> 5),
+                  (uint64_t)pack_bf16(o[0], o[1]) | ((uint64_t)pack_bf16(o[2], o[3]) << 32));
+    }
+}
+
+// ---------------------------------------------------------------------------
 // The units after the decoder layers.  Every kind of unit is a function of its own (not
 // inlined into the kernel): each gets its own register allocation, and a change to one does
 // not move the code of the others.
@@ -1581,8 +1778,8 @@ __device__ __forceinline__ void run_unit(int ph, int u, const uint32_t* gtab) {
     switch (kind) {
     case K_EMBED: embed_unit(u); break;
     case K_ATTN:
+        // (the few-row kernels run their attention units from the kernel's loop: attn_prepare / attn_few)
         if constexpr (WIDE) { if (attn_allq(P)) attn_unit<true, CAUSAL>(ph, u); else attn_unit<false, CAUSAL>(ph, u); }
-        else attn_unit<false, CAUSAL>(ph, u);
         break;
     case K_GEMM4: gemm_unit<4>(ph, u, gtab); break;
     case K_GEMM1: if constexpr (!WIDE) gemm_unit<1>(ph, u, gtab); break;
@@ -1623,15 +1820,31 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
     // the few-row kernel takes the launch-independent part of a layer map's descriptor from the
     // context's table (null: derived per unit)
     const uint32_t* gtab = WIDE ? nullptr : uniform_ptr(P.s.gtab);
+    AttnPrep ap;   // few-row kernel: the descriptor of this workgroup's first attention unit, prepared ahead of the barrier
+    ap.valid = 0; ap.ph = -1; ap.u = -1;
     for (int ph = P.ph_lo; ph < P.ph_hi; ++ph) {
         tp(ph, 0);
         const int nu = ph == 0 ? P.D.B * P.D.M : ph < H ? s_nu[(ph - 1) % 5] : s_nu[5 + ph - H];
+        const bool few_attn = !WIDE && ph > 0 && ph < H && (ph - 1) % 5 == 1;
         for (int u = blockIdx.x; u < nu; u += gridDim.x) {
-            run_unit<WIDE, CAUSAL>(ph, u, gtab);
+            if constexpr (!WIDE) {
+                if (few_attn) {
+                    if (!(ap.valid && ap.ph == ph && ap.u == u)) attn_prepare<CAUSAL>(ph, u, ap);
+                    attn_few<CAUSAL>(ap);
+                } else {
+                    run_unit<WIDE, CAUSAL>(ph, u, gtab);
+                }
+            } else {
+                run_unit<WIDE, CAUSAL>(ph, u, gtab);
+            }
             __syncthreads();
         }
         tp(ph, 1);
         if (P.persistent && ph + 1 < P.ph_hi) {
+            if constexpr (!WIDE) {
+                // the next phase is an attention phase and this workgroup has a unit of it: describe it now
+                if (ph + 1 < H && ph % 5 == 1 && (int)blockIdx.x < s_nu[1]) attn_prepare<CAUSAL>(ph + 1, blockIdx.x, ap);
+            }
             ++epoch;
             if (!grid_sync(epoch, ph)) return;
         }
