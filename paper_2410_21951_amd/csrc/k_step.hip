@@ -1515,15 +1515,15 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
 // ---------------------------------------------------------------------------
 // Attention unit of the few-row kernel (one head, 16 query rows of one sequence; the algorithm, operand layouts and
 // merge of attn_unit<false>), in two parts.
-//  * attn_prepare works out everything that does not depend on the phase before it: which (sequence, head, query
-//    tile) the unit is, lengths, block count, the lane's offsets and its mask words (the tree tables are fixed during
-//    a launch).  The kernel calls it BEFORE the grid barrier in front of the attention phase, while the workgroup
-//    would only wait, so that after the barrier the first thing a wave does is to ask for the queries and its keys
-//    (the first key block is requested ~0.4 us into the phase instead of ~2 us).
+//  * attn_prepare works out which (sequence, head, query tile) the unit is, lengths, block count, base addresses (as
+//    workgroup-uniform values: they stay in scalar registers) and the lane's offsets and mask words;
 //  * attn_few is the unit itself.
+// With the descriptor in scalar registers the first key block is requested ~0.7 us into the phase (~2 us before).
+// Calling attn_prepare on the other side of the grid barrier that precedes the phase, where the workgroup would
+// only wait, was measured 8 us per step SLOWER: the workgroup that arrives last has no wait to hide it in, and it
+// is that workgroup which sets the length of the phase.
 // ---------------------------------------------------------------------------
 struct AttnPrep {
-    int valid;                 // the descriptor describes unit `u` of phase `ph`
     int ph, u;
     int live;                  // 0: padding unit (nothing to do)
     int layer, b, h, qt, L, T, n_rows, nblk;
@@ -1541,7 +1541,7 @@ __device__ __forceinline__ void attn_prepare(int ph_, int u_, AttnPrep& A) {
     const Dims& D = P.D;
     const DevState& s = P.s;
     const int lane = threadIdx.x & 63, gq = lane >> 4, c = lane & 15;
-    A.valid = 1; A.ph = ph; A.u = u; A.live = 0;
+    A.ph = ph; A.u = u; A.live = 0;
     A.layer = (ph - 1) / 5;
     // unit = (query tile) * pad8(B * nH) + (sequence, head): the query tiles of one head run on one XCD
     // (workgroup i is on XCD i mod 8) and share its L2 for that head's K / V rows
@@ -1820,8 +1820,6 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
     // the few-row kernel takes the launch-independent part of a layer map's descriptor from the
     // context's table (null: derived per unit)
     const uint32_t* gtab = WIDE ? nullptr : uniform_ptr(P.s.gtab);
-    AttnPrep ap;   // few-row kernel: the descriptor of this workgroup's first attention unit, prepared ahead of the barrier
-    ap.valid = 0; ap.ph = -1; ap.u = -1;
     for (int ph = P.ph_lo; ph < P.ph_hi; ++ph) {
         tp(ph, 0);
         const int nu = ph == 0 ? P.D.B * P.D.M : ph < H ? s_nu[(ph - 1) % 5] : s_nu[5 + ph - H];
@@ -1829,7 +1827,8 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
         for (int u = blockIdx.x; u < nu; u += gridDim.x) {
             if constexpr (!WIDE) {
                 if (few_attn) {
-                    if (!(ap.valid && ap.ph == ph && ap.u == u)) attn_prepare<CAUSAL>(ph, u, ap);
+                    AttnPrep ap;
+                    attn_prepare<CAUSAL>(ph, u, ap);
                     attn_few<CAUSAL>(ap);
                 } else {
                     run_unit<WIDE, CAUSAL>(ph, u, gtab);
@@ -1841,10 +1840,6 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
         }
         tp(ph, 1);
         if (P.persistent && ph + 1 < P.ph_hi) {
-            if constexpr (!WIDE) {
-                // the next phase is an attention phase and this workgroup has a unit of it: describe it now
-                if (ph + 1 < H && ph % 5 == 1 && (int)blockIdx.x < s_nu[1]) attn_prepare<CAUSAL>(ph + 1, blockIdx.x, ap);
-            }
             ++epoch;
             if (!grid_sync(epoch, ph)) return;
         }
