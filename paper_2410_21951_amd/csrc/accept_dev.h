@@ -29,7 +29,6 @@ __device__ __forceinline__ void row16_argbest(float& bv, int& bi) {
 }
 __device__ __forceinline__ void wave_argbest(float& bv, int& bi) {
     row16_argbest(bv, bi);
-#if defined(__HIP_DEVICE_COMPILE__)
     {
         const vadusa_u32x2 rv = __builtin_amdgcn_permlane16_swap(__float_as_uint(bv), __float_as_uint(bv), false, false);
         const vadusa_u32x2 ri = __builtin_amdgcn_permlane16_swap((unsigned)bi, (unsigned)bi, false, false);
@@ -42,14 +41,6 @@ __device__ __forceinline__ void wave_argbest(float& bv, int& bi) {
         const bool x = before(__uint_as_float(rv.x), (int)ri.x, __uint_as_float(rv.y), (int)ri.y);
         bv = __uint_as_float(x ? rv.x : rv.y); bi = (int)(x ? ri.x : ri.y);
     }
-#else
-#pragma unroll
-    for (int o = 16; o <= 32; o <<= 1) {
-        const float ov = __shfl_xor(bv, o, 64);
-        const int oi = __shfl_xor(bi, o, 64);
-        if (before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-    }
-#endif
 }
 
 // Block-wide arg-best under the order above, restricted to entries that come

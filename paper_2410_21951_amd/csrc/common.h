@@ -106,16 +106,12 @@ __host__ __device__ inline size_t vc_off(int pos, int dim) {
     return (size_t)(pos >> 5) * 2048 + (size_t)((((dim >> 4) * 64) + (dim & 15) + 16 * ((pos & 31) >> 3)) * 8 + (pos & 7));
 }
 // Two floats to a pair of bf16 (round to nearest even): one v_cvt_pk_bf16_f32 on the device.
-#if defined(__HIP_DEVICE_COMPILE__)
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     typedef __attribute__((ext_vector_type(2))) float f32x2_cvt;
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_cvt;
     const f32x2_cvt v = {a, b};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_cvt));
 }
-#else
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) { return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16); }
-#endif
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -158,7 +154,6 @@ __device__ __forceinline__ float row16_sum(float v) {
 // same value, one register then holds rows {0, 0, 2, 2} and the other rows {1, 1, 3, 3} (16-lane
 // swap), or halves {lo, lo} and {hi, hi} (32-lane swap), and combining the two registers lane by
 // lane is the exchange, without a trip through the LDS permute unit.
-#if defined(__HIP_DEVICE_COMPILE__)
 typedef unsigned int vadusa_u32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float rows_max(float v) {
     vadusa_u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
@@ -172,16 +167,6 @@ __device__ __forceinline__ float rows_sum(float v) {
     r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
     return __uint_as_float(r.x) + __uint_as_float(r.y);
 }
-#else
-__device__ __forceinline__ float rows_max(float v) {
-    v = fmaxf(v, __shfl_xor(v, 16, 64));
-    return fmaxf(v, __shfl_xor(v, 32, 64));
-}
-__device__ __forceinline__ float rows_sum(float v) {
-    v += __shfl_xor(v, 16, 64);
-    return v + __shfl_xor(v, 32, 64);
-}
-#endif
 __device__ __forceinline__ int wave_sum_i_dpp(int v) {
     v += dpp_perm<0xB1>(v);    // quad_perm [1,0,3,2]
     v += dpp_perm<0x4E>(v);    // quad_perm [2,3,0,1]

@@ -104,8 +104,86 @@ __global__ __launch_bounds__(256) void k_perturb(const float* __restrict__ logit
     }
 }
 
+
+// Rows of up to 4096 logits: one WAVE per row, the row in registers (values of lane l: l, l + 64, ...), no LDS
+// and no workgroup barrier.  The same search as in k_perturb, as a plain bisection over the 32-bit keys: a round is a
+// compare and two conditional adds per value and two wave sums by lane permutations.  The values are kept as their
+// keys (key_value gives a value back), entries beyond the row have key 0 (below every key) and mass 0.
+__device__ __forceinline__ float key_value(uint32_t k) { return __uint_as_float(k ^ ((k >> 31) ? 0x80000000u : 0xffffffffu)); }
+__device__ __forceinline__ float wave_max_dpp(float v) {
+    v = fmaxf(v, __int_as_float(dpp_perm<0xB1>(__float_as_int(v))));
+    v = fmaxf(v, __int_as_float(dpp_perm<0x4E>(__float_as_int(v))));
+    v = fmaxf(v, __int_as_float(dpp_perm<0x141>(__float_as_int(v))));
+    v = fmaxf(v, __int_as_float(dpp_perm<0x140>(__float_as_int(v))));
+    return fmaxf(fmaxf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0)), __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16))),
+                 fmaxf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32)), __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48))));
+}
+template <int GROUPS>   // groups of four 64-value chunks the row may have: GROUPS * 256 >= V1
+__global__ __launch_bounds__(64) void k_perturb_wave(const float* __restrict__ logits, const float* __restrict__ u,
+                                                     float* __restrict__ scores, int V1, float temperature, float top_p, int tau) {
+    const size_t row = blockIdx.x;
+    const int lane = threadIdx.x;
+    const float* z = logits + row * V1;
+    const float* ur = u + row * V1;
+    float* y = scores + row * V1;
+    float e[GROUPS][4];
+    uint32_t key[GROUPS][4];
+    float m = -INFINITY;
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int v = g * 256 + q * 64 + lane;
+            const float sv = v < V1 ? z[v] / temperature + 0.f : -INFINITY;   // -0 becomes +0: equal values, equal keys
+            key[g][q] = v < V1 ? order_key(sv) : 0u;
+            m = fmaxf(m, sv);
+        }
+    m = wave_max_dpp(m);
+    uint32_t kmin = 0;   // keep everything
+    if (top_p < 1.f) {
+        float zsum = 0.f;
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                e[g][q] = g * 256 + q * 64 + lane < V1 ? expf(key_value(key[g][q]) - m) : 0.f;
+                zsum += e[g][q];
+            }
+        const float target = top_p * wave_sum_dpp(zsum);
+        uint32_t lo = 0, hi = 0xffffffffu;   // the predicate holds at hi: nothing lies above the largest key
+        while (lo < hi) {
+            const uint32_t mid = lo + ((hi - lo) >> 1);
+            float a = 0.f;
+            int cnt = 0;
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bool above = key[g][q] > mid;
+                    a += above ? e[g][q] : 0.f;
+                    cnt += above ? 1 : 0;
+                }
+            const float A = wave_sum_dpp(a);
+            const int C = wave_sum_i_dpp(cnt);
+            if (A < target || C < tau) hi = mid;
+            else lo = mid + 1;
+        }
+        kmin = hi;
+    }
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int v = g * 256 + q * 64 + lane;
+            if (v < V1) y[v] = key[g][q] >= kmin ? key_value(key[g][q]) - logf(-logf(ur[v])) : -INFINITY;
+        }
+}
+
 void launch_perturb(const float* logits, const float* u, float* scores, int rows, int V1, float temperature,
                     float top_p, int tau, hipStream_t st) {
-    hipLaunchKernelGGL(k_perturb, dim3(rows), dim3(256), (size_t)V1 * sizeof(float), st, logits, u, scores, V1,
-                       temperature, top_p, tau);
+    if (V1 <= 1280) hipLaunchKernelGGL(k_perturb_wave<5>, dim3(rows), dim3(64), 0, st, logits, u, scores, V1, temperature, top_p, tau);
+    else if (V1 <= 2304) hipLaunchKernelGGL(k_perturb_wave<9>, dim3(rows), dim3(64), 0, st, logits, u, scores, V1, temperature, top_p, tau);
+    else if (V1 <= 4096) hipLaunchKernelGGL(k_perturb_wave<16>, dim3(rows), dim3(64), 0, st, logits, u, scores, V1, temperature, top_p, tau);
+    else hipLaunchKernelGGL(k_perturb, dim3(rows), dim3(256), (size_t)V1 * sizeof(float), st, logits, u, scores, V1,
+                            temperature, top_p, tau);
 }

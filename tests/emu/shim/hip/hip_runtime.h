@@ -148,6 +148,21 @@ static inline int emu_dpp_mask(int ctrl) {
 #define __builtin_amdgcn_update_dpp(old, v, ctrl, rm, bm, bc) \
     (EMU_MARK, (int)emu_shfl_xor32((uint32_t)(v), emu_dpp_mask(ctrl)))
 
+// Row swaps of gfx950 (v_permlane16_swap / v_permlane32_swap) as the kernels use them, with both operands the same
+// value: the first result holds the value of the lane in the even row (lower half), the second that of the lane in
+// the odd row (upper half).
+typedef unsigned int emu_u32x2 __attribute__((ext_vector_type(2)));
+static inline emu_u32x2 emu_permlane_swap(uint32_t a, uint32_t b, int bit) {
+    (void)b;   // only called with a == b
+    const int lane = (int)(threadIdx.x & 63);
+    emu_u32x2 r;
+    r.x = emu_shfl_idx32(a, lane & ~bit);
+    r.y = emu_shfl_idx32(a, lane | bit);
+    return r;
+}
+#define __builtin_amdgcn_permlane16_swap(a, b, fi, bc) (EMU_MARK, emu_permlane_swap((a), (b), 16))
+#define __builtin_amdgcn_permlane32_swap(a, b, fi, bc) (EMU_MARK, emu_permlane_swap((a), (b), 32))
+
 // ---- math / bits ----
 static inline float __uint_as_float(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
 static inline uint32_t __float_as_uint(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
