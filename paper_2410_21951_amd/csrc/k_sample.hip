@@ -153,18 +153,18 @@ __global__ __launch_bounds__(64) void k_perturb_wave(const float* __restrict__ l
         uint32_t lo = 0, hi = 0xffffffffu;   // the predicate holds at hi: nothing lies above the largest key
         while (lo < hi) {
             const uint32_t mid = lo + ((hi - lo) >> 1);
-            float a = 0.f;
-            int cnt = 0;
+            float a4[4] = {0.f, 0.f, 0.f, 0.f};   // four independent partial sums: no chain of dependent additions
+            int c4[4] = {0, 0, 0, 0};
 #pragma unroll
             for (int g = 0; g < GROUPS; ++g)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const bool above = key[g][q] > mid;
-                    a += above ? e[g][q] : 0.f;
-                    cnt += above ? 1 : 0;
+                    a4[q] += above ? e[g][q] : 0.f;
+                    c4[q] += above ? 1 : 0;
                 }
-            const float A = wave_sum_dpp(a);
-            const int C = wave_sum_i_dpp(cnt);
+            const float A = wave_sum_dpp((a4[0] + a4[1]) + (a4[2] + a4[3]));
+            const int C = wave_sum_i_dpp((c4[0] + c4[1]) + (c4[2] + c4[3]));
             if (A < target || C < tau) hi = mid;
             else lo = mid + 1;
         }
