@@ -493,7 +493,7 @@ static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode,
     StepParams P = base_params(c, D);
     if (rank_rows) P.s.logits = rank_rows;   // acceptance and continuation rank these rows instead of the logits
     P.table = table; P.prefill_mode = prefill_mode; P.tau = tau;
-    P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent; P.profile = c->profile; P.wide = D.B * D.M >= 256;
+    P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent; P.profile = c->profile; P.wide = D.B * D.M >= 256; P.mid = !P.wide && D.B * D.M > 64;
     P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq; P.topk_apart = topk_apart;
     if (!c->gtab_ready) P.s.gtab = nullptr;
     hipError_t e;

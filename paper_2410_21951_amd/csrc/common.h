@@ -311,6 +311,7 @@ struct StepParams {
     int ph_lo, ph_hi;   // phases to run: [ph_lo, ph_hi)
     int persistent;     // 1: one cooperative launch with grid barriers between phases
     int wide;           // 1: B * M >= 256 rows: the layer maps and the base head use 64 x 64 output tiles
+    int mid;            // 1: 65 to 255 rows: QKV / FFN1 in 64 x 32 units, out-projection / FFN2 in 32 x 16 units
     int profile;        // n > 0: workgroup n - 1 records timing points (costs a few hundred ns each)
     uint32_t epoch;     // barrier epoch before the first barrier of this launch
     int seq0, nseq;     // sequences the compaction phases act on

@@ -43,6 +43,8 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 #define ST_TILE_BYTES (20 * 1024)           // reduction buffer of the linear maps (16 KiB), attention merge buffers
 #define ST_LDS_BYTES (ST_TILE_BYTES + 1024)  // + row statistics
+#define ST_MID_TILE_BYTES (32 * 1024)       // reduction buffer of the 64 x 32 units (65 to 255 rows): 4 waves x 8 tiles x 1 KiB
+#define ST_MID_LDS_BYTES (ST_MID_TILE_BYTES + 1024)
 #define ST_WIDE_TILE_BYTES (64 * 1024)      // reduction buffer of the 64 x 64 units: 4 waves x 16 tiles x 1 KiB
 #define ST_WIDE_LDS_BYTES (ST_WIDE_TILE_BYTES + 1024)
 #define ST_SPIN_LIMIT (1 << 22)
@@ -125,11 +127,11 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     }
     if (ph < H) {
         switch ((ph - 1) % 5) {
-        case 0: return sq_units(P, 3 * D.d) ? pad8(3 * D.d / 32) * cdiv(R, 32) : pad8(3 * D.d / 16) * RG;
+        case 0: return sq_units(P, 3 * D.d) ? pad8(3 * D.d / 32) * cdiv(R, P.mid ? 64 : 32) : pad8(3 * D.d / 16) * RG;
         case 1: return attn_allq(P) ? pad8(D.B * D.nH) : pad8(D.B * D.nH) * cdiv(D.M, 16);
-        case 2: return pad8(D.d / 16) * RB;
-        case 3: return sq_units(P, D.F) ? pad8(D.F / 32) * cdiv(R, 32) : pad8(D.F / 16) * RG;
-        default: return pad8(D.d / 16) * RB;
+        case 2: return pad8(D.d / 16) * (P.mid ? cdiv(R, 32) : RB);
+        case 3: return sq_units(P, D.F) ? pad8(D.F / 32) * cdiv(R, P.mid ? 64 : 32) : pad8(D.F / 16) * RG;
+        default: return pad8(D.d / 16) * (P.mid ? cdiv(R, 32) : RB);
         }
     }
     const int RGb = cdiv(D.B, 64);
@@ -277,7 +279,7 @@ __device__ __forceinline__ void embed_unit(int r_) {
 
 // Descriptor of linear-map unit u of phase ph (all values are workgroup-uniform).  Returns false
 // for an empty unit (padding of the XCD-aware numbering) and for phases that are not linear maps.
-template <bool WIDE>
+template <bool WIDE, bool MID = false>   // MID: few-row kernel for 65 to 255 rows (residual maps in 32-row units)
 __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, int& row0, const uint32_t* gtab = nullptr) {
     const StepParams& P = sP;
     const Dims& D = P.D;
@@ -306,7 +308,7 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
         if (u < NTp) { nt = u; rb = 0; }
         else if ((NTp & (NTp - 1)) == 0) { nt = u & (NTp - 1); rb = u >> __builtin_ctz(NTp); }
         else { nt = u % NTp; rb = u / NTp; }
-        row0 = rb * (g.epi == SE_RESID ? 16 : 64);
+        row0 = rb * (g.epi == SE_RESID ? (MID ? 32 : 16) : 64);
         return nt < NT;
     }
     g.R = R; g.stats = nullptr; g.colsum = nullptr; g.bias = nullptr; g.out = nullptr; g.outf = nullptr;
@@ -358,7 +360,7 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
         case 2:
             g.X = att_l; g.K = D.d; g.N = D.d; g.Wp = (const uint4*)w.Wo; g.bias = w.bo;
             g.epi = SE_RESID; g.out = xb0 + s.act_stride; g.stats_out = st0 + s.stats_stride;
-            return split(D.d / 16) ? (row0 = rb * (wide ? wrows : 16), true) : false;
+            return split(D.d / 16) ? (row0 = rb * (wide ? wrows : MID ? 32 : 16), true) : false;
         case 3:
             g.X = xb0 + s.act_stride; g.K = D.d; g.N = D.F; g.Wp = (const uint4*)w.W1; g.bias = w.t_w1; g.colsum = w.cs_w1;
             g.stats = st0 + s.stats_stride; g.epi = SE_GELU; g.out = hid_l;
@@ -366,7 +368,7 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
         default:
             g.X = hid_l; g.K = D.F; g.N = D.d; g.Wp = (const uint4*)w.W2; g.bias = w.b2;
             g.epi = SE_RESID; g.out = xb0 + 2 * s.act_stride; g.stats_out = st0 + 2 * s.stats_stride;
-            return split(D.d / 16) ? (row0 = rb * (wide ? wrows : 16), true) : false;
+            return split(D.d / 16) ? (row0 = rb * (wide ? wrows : MID ? 32 : 16), true) : false;
         }
     }
     const int RGb = cdiv(D.B, 64);
@@ -419,10 +421,10 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
     const StepParams& P = sP;
     GemmD g;
     int nt, row0;
-    if (!describe_gemm<false>(ph_u, u_u, g, nt, row0, gtab)) return;
+    if (!describe_gemm<false, NRT == 2>(ph_u, u_u, g, nt, row0, gtab)) return;
     extern __shared__ uint4 smem[];
     float* s_stat = (float*)((char*)smem + ST_TILE_BYTES);
-    constexpr int CH = NRT == 4 ? 8 : 16;     // k-steps per chunk
+    constexpr int CH = NRT == 4 ? 8 : NRT == 2 ? 8 : 16;     // k-steps per chunk
     constexpr int ROWS = NRT * 16;
     const Dims& D = P.D;
     const DevState& s = P.s;
@@ -450,7 +452,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
     // epilogue inputs, requested now so that they arrive with the operands (the vectors are
     // padded to whole 16-column tiles)
     uint4 cs4 = make_uint4(0, 0, 0, 0), b4 = cs4;
-    float xres = 0.f, bres = 0.f;
+    float xres[NRT == 4 ? 1 : NRT], bres = 0.f;
     int kv_b = 0, kv_L = 0, kv_rows = 0, kv_which = 0, kv_cc = 0;   // QKV map: where this thread's key / value row goes
     if (NRT == 4) {
         const int n0 = nt * 16 + (tid & 3) * 4;
@@ -467,8 +469,12 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
             }
         }
     } else {
-        const int r = row0 + (tid >> 4), n = nt * 16 + (tid & 15);
-        if (r < g.R) xres = ldg(s.x + (size_t)r * g.N + n);
+        const int n = nt * 16 + (tid & 15);
+#pragma unroll
+        for (int it = 0; it < (NRT == 4 ? 1 : NRT); ++it) {
+            const int r = row0 + it * 16 + (tid >> 4);
+            xres[it] = r < g.R ? ldg(s.x + (size_t)r * g.N + n) : 0.f;
+        }
         bres = ldg(g.bias + n);
     }
 
@@ -640,28 +646,31 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
             }
         }
     } else {
-        // residual update: one element per thread, statistics over the 16 columns of the tile
-        const int row = tid >> 4, col = tid & 15, r = row0 + row, n = nt * 16 + col;
-        const int src = ((row >> 2) * 16 + col) * 4 + (row & 3);
-        float v = red[src];
+        // residual update: one element per thread and row tile, statistics over the 16 columns of the tile
 #pragma unroll
-        for (int w = 1; w < 4; ++w) v += red[w * 256 + src];
-        const bool ok = r < g.R;
-        float xn = 0.f;
-        if (ok) {
-            xn = xres + v + bres;
-            stwf(s.x + (size_t)r * g.N + n, xn);
+        for (int it = 0; it < (NRT == 4 ? 1 : NRT); ++it) {
+            const int row = tid >> 4, col = tid & 15, r = row0 + it * 16 + row, n = nt * 16 + col;
+            const int src = it * 256 + ((row >> 2) * 16 + col) * 4 + (row & 3);
+            float v = red[src];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) v += red[w * (NRT * 256) + src];
+            const bool ok = r < g.R;
+            float xn = 0.f;
+            if (ok) {
+                xn = xres[it] + v + bres;
+                stwf(s.x + (size_t)r * g.N + n, xn);
+            }
+            {
+                const float nb = __int_as_float(dpp_perm<0xB1>(__float_as_int(xn)));   // the neighbouring column (used by even columns): a pair -> one 32-bit store
+                if (ok && !(col & 1)) stw32(g.out + toff(r, n, g.N >> 5), pack_bf16(xn, nb));
+            }
+            float sum = xn;
+            sum = row16_sum(sum);
+            const float mean = sum * (1.f / 16.f);
+            float m2 = (xn - mean) * (xn - mean);
+            m2 = row16_sum(m2);
+            if (ok && col == 0) stwf2(g.stats_out + ((size_t)nt * g.R + r) * 2, mean, m2);
         }
-        {
-            const float nb = __int_as_float(dpp_perm<0xB1>(__float_as_int(xn)));   // the neighbouring column (used by even columns): a pair -> one 32-bit store
-            if (ok && !(col & 1)) stw32(g.out + toff(r, n, g.N >> 5), pack_bf16(xn, nb));
-        }
-        float sum = xn;
-        sum = row16_sum(sum);
-        const float mean = sum * (1.f / 16.f);
-        float m2 = (xn - mean) * (xn - mean);
-        m2 = row16_sum(m2);
-        if (ok && col == 0) stwf2(g.stats_out + ((size_t)nt * g.R + r) * 2, mean, m2);
     }
 }
 
@@ -843,6 +852,209 @@ __device__ __forceinline__ void gemm_unit22(int ph_, int u_, const uint32_t* gta
                     const int cc = kv_cc + ecg * 4, head = cc >> 6, dim = cc & 63;
                     const int pos = kv_L + node;
                     if (pos < D.maxpos && kv_rows > 0) {
+                        const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
+                        if (kv_which) {
+                            bf16_t* vp = (bf16_t*)s.Vc + hb + vc_off(pos, dim);   // four dimensions of one position: four lanes of a value tile
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) stw16(vp + j * 8, f2bf(v[j]));
+                        } else {
+                            stw64((bf16_t*)s.Kc + hb + kc_off(pos, dim), pk);   // four dimensions of one key: half of a lane's piece
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// 64 x 32 unit (four row tiles x two column tiles) of the few-row kernels for 65 to 255 rows (trees of
+// more than 64 nodes, small batches): gemm_unit22 with twice the rows, so that QKV and FFN1 of a 128-row step
+// are one round of units (192 and 256) instead of two, and a weight fragment feeds four row tiles.  Units are
+// numbered (row block of 64) * pad8(column pairs) + column pair.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void gemm_unit42(int ph_, int u_, const uint32_t* gtab) {
+    const int ph_u = __builtin_amdgcn_readfirstlane(ph_), u_u = __builtin_amdgcn_readfirstlane(u_);
+    const StepParams& P = sP;
+    GemmD g;
+    int nt, row0;
+    if (!describe_gemm<false>(ph_u, 0, g, nt, row0, gtab)) return;   // unit 0 always exists: the map itself
+    {
+        const int NG = g.N >> 5, NGp = pad8(NG);
+        int gi, rb;
+        if (u_u < NGp) { gi = u_u; rb = 0; }
+        else if ((NGp & (NGp - 1)) == 0) { gi = u_u & (NGp - 1); rb = u_u >> __builtin_ctz(NGp); }
+        else { gi = u_u % NGp; rb = u_u / NGp; }
+        if (gi >= NG) return;
+        nt = gi * 2; row0 = rb * 64;
+    }
+    extern __shared__ uint4 smem[];
+    float* s_stat = (float*)((char*)smem + ST_MID_TILE_BYTES);
+    constexpr int CH = 8;
+    const Dims& D = P.D;
+    const DevState& s = P.s;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int nks = g.K >> 5;
+    const int ks_lo = (nks * wave) >> 2, ks_hi = (nks * (wave + 1)) >> 2;
+    const uint4* Wp[2];
+    const uint4* Ap[4];
+    bool rowok[4];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) Wp[t] = uniform_ptr(g.Wp + (size_t)(nt + t) * nks * 64);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        rowok[t] = row0 + t * 16 < g.R;
+        Ap[t] = uniform_ptr((const uint4*)g.X + (size_t)(rowok[t] ? (row0 >> 4) + t : 0) * nks * 64);
+    }
+    const uint32_t ulane = (uint32_t)lane;
+    f32x4_t acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    tp(g.ph, 5);
+    // epilogue inputs of this thread's four columns, requested with the operands
+    const int erow = tid >> 3, ecg = tid & 7;                 // rows erow and erow + 32 of the unit, group of four columns (of 32)
+    const int n0 = nt * 16 + ecg * 4;
+    uint4 cs4 = make_uint4(0, 0, 0, 0), b4 = cs4;
+    if (g.colsum) cs4 = ldg4(g.colsum + n0);
+    if (g.bias) b4 = ldg4(g.bias + n0);
+    int kv_b[2] = {0, 0}, kv_L[2] = {0, 0}, kv_rows[2] = {0, 0}, kv_which = 0, kv_cc = 0;
+    if (g.epi == SE_QKV && nt * 16 >= D.d) {
+        kv_which = (nt * 16) / D.d - 1;
+        kv_cc = (nt * 16) % D.d;
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const int r = row0 + 32 * hh + erow;
+            if (r < g.R) {
+                kv_b[hh] = r / D.M;
+                kv_L[hh] = ldg(s.L + kv_b[hh]);
+                kv_rows[hh] = ldg(s.n_rows + kv_b[hh]);
+            }
+        }
+    }
+    // LayerNorm statistics of the unit's 64 rows: four threads per row
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f, c0 = 0.f;   // c0: shift of the tile means, see gemm_unit
+    const int tiles = g.K >> 4;
+    const bool do_stats = g.stats != nullptr;
+    const bool stats_early = do_stats && tiles <= 64;
+    float2 sv[16];
+    if (stats_early) {
+        const int r = row0 + (tid >> 2);
+        const float2* sp = (const float2*)g.stats + (r < g.R ? r : 0);
+        c0 = ldgf2(sp).x;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int t = (tid & 3) + 4 * j;
+            sv[j] = ldgf2(sp + (size_t)(t < tiles ? t : 0) * g.R);
+        }
+    }
+    for (int kb = ks_lo; kb == ks_lo || kb < ks_hi; kb += CH) {
+        uint4 bw[2][CH], aw[4][CH];
+        if (kb + CH <= ks_hi) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < CH; ++i) bw[t][i] = ldg4((const char*)Wp[t] + ((uint32_t)(kb + i) * 1024u + ulane * 16u));
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int i = 0; i < CH; ++i)
+                    aw[t][i] = rowok[t] ? ldg4((const char*)Ap[t] + ((uint32_t)(kb + i) * 1024u + ulane * 16u)) : make_uint4(0, 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < CH; ++i) {
+                    const int ks = kb + i;
+                    bw[t][i] = ks < ks_hi ? ldg4((const char*)Wp[t] + ((uint32_t)ks * 1024u + ulane * 16u)) : make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int i = 0; i < CH; ++i) {
+                    const int ks = kb + i;
+                    aw[t][i] = (ks < ks_hi && rowok[t]) ? ldg4((const char*)Ap[t] + ((uint32_t)ks * 1024u + ulane * 16u)) : make_uint4(0, 0, 0, 0);
+                }
+        }
+        if (kb == ks_lo) tp(g.ph, 6);
+        if (kb == ks_lo && do_stats && !stats_early) {
+            const int r = row0 + (tid >> 2);
+            if (r < g.R) {
+                const float2* sp = (const float2*)g.stats + r;
+                c0 = ldgf2(sp).x;
+                for (int t = tid & 3; t < tiles; t += 4) {
+                    const float2 v = ldgf2(sp + (size_t)t * g.R);
+                    const float dv = v.x - c0; s1 += dv; s2 += v.y; s3 += dv * dv;
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < 2; ++ct)
+                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aw[rt][i]),
+                                                                          __builtin_bit_cast(bf16x8_t, bw[ct][i]), acc[rt][ct], 0, 0, 0);
+    }
+    tp(g.ph, 2);
+    if (stats_early && row0 + (tid >> 2) < g.R) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if ((tid & 3) + 4 * j < tiles) { const float dv = sv[j].x - c0; s1 += dv; s2 += sv[j].y; s3 += dv * dv; }
+    }
+    if (g.stats) {
+        s1 = quad_sum(s1);
+        s2 = quad_sum(s2);
+        s3 = quad_sum(s3);
+        if (do_stats && (tid & 3) == 0) {
+            const float mean = c0 + s1 / tiles;   // s1, s3: sums of the tile means' distances from c0 and of their squares
+            const float m2 = s2 + 16.f * fmaxf(s3 - s1 * s1 / tiles, 0.f);
+            s_stat[tid >> 2] = mean;
+            s_stat[64 + (tid >> 2)] = rsqrtf(m2 / g.K + LN_EPS);
+        }
+    }
+    __syncthreads();
+    float* red = (float*)smem;   // [wave][row tile][column tile][lane][4]
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[((wave * 8 + rt * 2 + ct) * 64 + lane) * 4 + i] = acc[rt][ct][i];
+    __syncthreads();
+    tp(g.ph, 3);
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        const int urow = erow + 32 * hh, rt = urow >> 4, rr = urow & 15, ct = ecg >> 2, r = row0 + urow;
+        if (r < g.R) {
+            const float mu = g.stats ? s_stat[urow] : 0.f, rstd = g.stats ? s_stat[64 + urow] : 1.f;
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = (ecg & 3) * 4 + j;
+                const int src = (((rt * 2 + ct) * 64) + (rr >> 2) * 16 + col) * 4 + (rr & 3);
+                float a = red[src];
+#pragma unroll
+                for (int w = 1; w < 4; ++w) a += red[w * 2048 + src];
+                const float csj = __uint_as_float(j == 0 ? cs4.x : j == 1 ? cs4.y : j == 2 ? cs4.z : cs4.w);
+                const float bj = __uint_as_float(j == 0 ? b4.x : j == 1 ? b4.y : j == 2 ? b4.z : b4.w);
+                if (g.stats) a = rstd * (a - mu * csj);
+                v[j] = a + bj;
+            }
+            if (g.epi == SE_GELU) {
+                stw64(g.out + toff(r, n0, g.N >> 5),
+                      (uint64_t)pack_bf16(gelu_s(v[0]), gelu_s(v[1])) | ((uint64_t)pack_bf16(gelu_s(v[2]), gelu_s(v[3])) << 32));
+            } else if (g.epi == SE_QKV) {
+                const uint64_t pk = (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32);
+                if (n0 < D.d) {
+                    stw64(g.out + toff(r, n0, D.d >> 5), pk);
+                } else {
+                    const int b = kv_b[hh], node = r - b * D.M;
+                    const int cc = kv_cc + ecg * 4, head = cc >> 6, dim = cc & 63;
+                    const int pos = kv_L[hh] + node;
+                    if (pos < D.maxpos && kv_rows[hh] > 0) {
                         const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
                         if (kv_which) {
                             bf16_t* vp = (bf16_t*)s.Vc + hb + vc_off(pos, dim);   // four dimensions of one position: four lanes of a value tile
@@ -1752,7 +1964,7 @@ __device__ __forceinline__ void topk_unit(int u_) { const int u = __builtin_amdg
 // ---------------------------------------------------------------------------
 // one unit of one phase: dispatch to the unit's own function
 // ---------------------------------------------------------------------------
-template <bool WIDE, bool CAUSAL>
+template <bool WIDE, bool CAUSAL, bool MID>
 __device__ __forceinline__ void run_unit(int ph, int u, const uint32_t* gtab) {
     const StepParams& P = sP;
     const Dims& D = P.D;
@@ -1782,8 +1994,8 @@ __device__ __forceinline__ void run_unit(int ph, int u, const uint32_t* gtab) {
         if constexpr (WIDE) { if (attn_allq(P)) attn_unit<true, CAUSAL>(ph, u); else attn_unit<false, CAUSAL>(ph, u); }
         break;
     case K_GEMM4: gemm_unit<4>(ph, u, gtab); break;
-    case K_GEMM1: if constexpr (!WIDE) gemm_unit<1>(ph, u, gtab); break;
-    case K_GEMM22: if constexpr (!WIDE) gemm_unit22(ph, u, gtab); break;
+    case K_GEMM1: if constexpr (!WIDE) { if constexpr (MID) gemm_unit<2>(ph, u, gtab); else gemm_unit<1>(ph, u, gtab); } break;
+    case K_GEMM22: if constexpr (!WIDE) { if constexpr (MID) gemm_unit42(ph, u, gtab); else gemm_unit22(ph, u, gtab); } break;
     case K_GEMMW: if constexpr (WIDE) gemm_wide_unit(ph, u); break;
     case K_EDGE: edge_unit(u); break;
     case K_SELECT: select_unit(u); break;
@@ -1793,10 +2005,11 @@ __device__ __forceinline__ void run_unit(int ph, int u, const uint32_t* gtab) {
     }
 }
 
-// Four kernels from one body: the ordinary one (up to 255 rows) and the one whose layer maps and
-// base head run as 64 x 64 or 128 x 128 units (StepParams::wide), each for tree rows and for the
-// causal passes of the prefill; each carries only the unit code it uses.
-template <bool WIDE, bool CAUSAL>
+// Six kernels from one body: the ordinary one (up to 64 rows), the one for 65 to 255 rows (StepParams::mid: QKV and
+// FFN1 in 64 x 32 units, the residual maps in 32 x 16 units, so that a 128-row step has one round of units per
+// phase) and the one whose layer maps and base head run as 64 x 64 or 128 x 128 units (StepParams::wide), each for
+// tree rows and for the causal passes of the prefill; each carries only the unit code it uses.
+template <bool WIDE, bool CAUSAL, bool MID>
 __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
     {
         const uint32_t* src = (const uint32_t*)&Parg;
@@ -1831,10 +2044,10 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
                     attn_prepare<CAUSAL>(ph, u, ap);
                     attn_few<CAUSAL>(ap);
                 } else {
-                    run_unit<WIDE, CAUSAL>(ph, u, gtab);
+                    run_unit<WIDE, CAUSAL, MID>(ph, u, gtab);
                 }
             } else {
-                run_unit<WIDE, CAUSAL>(ph, u, gtab);
+                run_unit<WIDE, CAUSAL, MID>(ph, u, gtab);
             }
             __syncthreads();
         }
@@ -1890,26 +2103,29 @@ void launch_build_gtab(const StepParams& p, uint32_t* tab, hipStream_t st) {
 void launch_step(const StepParams& p, int n_cus, hipStream_t st, hipError_t* err) {
     static bool once = false;
     if (!once) {
-        (void)hipFuncSetAttribute((const void*)k_step<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_WIDE_LDS_BYTES);
-        (void)hipFuncSetAttribute((const void*)k_step<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_WIDE_LDS_BYTES);
-        (void)hipFuncSetAttribute((const void*)k_step<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS_BYTES);
-        (void)hipFuncSetAttribute((const void*)k_step<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step<true, false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_WIDE_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step<true, true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_WIDE_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step<false, false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step<false, true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step<false, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_MID_LDS_BYTES);
+        (void)hipFuncSetAttribute((const void*)k_step<false, true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_MID_LDS_BYTES);
         once = true;
     }
     *err = hipSuccess;
-    const size_t lds = p.wide ? ST_WIDE_LDS_BYTES : ST_LDS_BYTES;
-    // four kernels from one body: few or many rows, tree (table 0) or causal pass of the prefill (table 1)
-    void (*kfn)(StepParams) = p.wide ? (p.table == 1 ? k_step<true, true> : k_step<true, false>)
-                                     : (p.table == 1 ? k_step<false, true> : k_step<false, false>);
+    const size_t lds = p.wide ? ST_WIDE_LDS_BYTES : p.mid ? ST_MID_LDS_BYTES : ST_LDS_BYTES;
+    // six kernels from one body: up to 64 rows, 65 to 255 rows, 256 rows and more; tree (table 0) or causal pass of the prefill (table 1)
+    void (*kfn)(StepParams) = p.wide ? (p.table == 1 ? k_step<true, true, false> : k_step<true, false, false>)
+                              : p.mid ? (p.table == 1 ? k_step<false, true, true> : k_step<false, false, true>)
+                                      : (p.table == 1 ? k_step<false, true, false> : k_step<false, false, false>);
     if (p.persistent) {
         // every workgroup of the grid must fit on the GPU at once
         static int resident = -1;
         if (resident < 0) {
-            int nb = 0;
-            int nw = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_step<false, false>, 256, ST_LDS_BYTES) != hipSuccess) nb = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nw, k_step<true, true>, 256, ST_WIDE_LDS_BYTES) != hipSuccess) nw = 0;
-            nb = std::min(nb, nw);
+            int nb = 0, nm = 0, nw = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_step<false, false, false>, 256, ST_LDS_BYTES) != hipSuccess) nb = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nm, k_step<false, true, true>, 256, ST_MID_LDS_BYTES) != hipSuccess) nm = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nw, k_step<true, true, false>, 256, ST_WIDE_LDS_BYTES) != hipSuccess) nw = 0;
+            nb = std::min(nb, std::min(nm, nw));
             resident = nb;
         }
         if (resident < 1) { *err = hipErrorCooperativeLaunchTooLarge; return; }

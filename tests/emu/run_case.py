@@ -35,6 +35,27 @@ if dtype == "bf16-40rows":
     assert s.compared >= 1
     sys.stdout.flush()
     os._exit(0)
+if dtype == "bf16-72rows":
+    # 65 to 255 rows: the kernel variant whose QKV / FFN1 run as 64 x 32 units and whose residual maps run as
+    # 32 x 16 units; 72 rows leave the second row block of 64 (and the third of 32) ragged.  The prompt of 70 tokens
+    # goes through one causal pass of 72 rows (the same variant for the prefill).
+    cfg = ModelConfig(n_layers=2, d_model=64, n_heads=1, head_dim=64, d_ffn=192, speech_vocab=71, text_vocab=20,
+                      n_draft_heads=3, max_positions=224, dtype="bf16")
+    W = make_weights(cfg, 81, std=0.05)
+    rng = np.random.default_rng(82)
+    text = [rng.integers(0, cfg.text_vocab, 3).astype(np.int32)]
+    prompt = [rng.integers(0, cfg.speech_vocab, 67).astype(np.int32)]
+    tree = make_tree(72, (10, 10, 10))
+    t0 = time.time()
+    ls = Lockstep(cfg, W, text, prompt, 72)
+    ls.step(tree, 2)
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    print(f"emulated {dtype}: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e} "
+          f"ties {s.tie_root}/{s.tie_list}/{s.tie_edge} in {time.time() - t0:.0f} s", flush=True)
+    assert s.compared >= 1
+    sys.stdout.flush()
+    os._exit(0)
 if dtype == "bf16-giveup":
     # the failure path: the host raises the error word of a kernel that gave up at a grid barrier; the next
     # synchronising call reports it, later calls refuse, a prefill recovers and decodes the same tokens

@@ -27,7 +27,7 @@ def emu_lib(tmp_path_factory):
     shutil.rmtree(str(out), ignore_errors=True)
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "fp32", "bf16-40rows", "bf16-giveup"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp32", "bf16-40rows", "bf16-72rows", "bf16-giveup"])
 def test_emulated_step_matches_oracle(emu_lib, dtype):
     r = subprocess.run([sys.executable, os.path.join(HERE, "emu", "run_case.py"), emu_lib, dtype],
                        stdout=subprocess.PIPE, stderr=subprocess.STDOUT, timeout=600, text=True)
