@@ -82,7 +82,7 @@ __shared__ int s_seqL[ST_SEQ_CACHE], s_seqRows[ST_SEQ_CACHE];
 // library routine's two branches.
 __device__ __forceinline__ float gelu_s(float v) {
     const float x = fabsf(v) * 0.70710678118654752f;
-    const float t = __frcp_rn(1.f + 0.3275911f * x);
+    const float t = __builtin_amdgcn_rcpf(1.f + 0.3275911f * x);   // one instruction, 1 ulp: far below the approximation's own error
     const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
     const float erfc_x = poly * __expf(-x * x);            // 1 - erf(|x|)
     const float one_plus_erf = v < 0.f ? erfc_x : 2.f - erfc_x;
@@ -1079,15 +1079,19 @@ __device__ __forceinline__ void gemm_unit42(int ph_, int u_, const uint32_t* gta
 // ---------------------------------------------------------------------------
 // Epilogue of the many-row units for one thread's four outputs v[0..3] of row r, columns
 // n0 .. n0 + 3 (inside column tile `tile`): activation / residual / cache scatter as the map
-// asks.  The four threads of a row (tid & 3) hold a tile's 16 columns between them.
-__device__ __forceinline__ void wide_store(const GemmD& g, int r, int n0, int tile, const float (&v)[4], const uint4& xr) {
+// asks.  The four threads of a row (tid & 3) hold a tile's 16 columns between them; ACC: the four lanes c, c + 16,
+// c + 32, c + 48 of a wave do (the layout of an MFMA result whose first operand was the weight tile), and for the
+// residual update every lane of the wave calls (its tile statistics are lane exchanges), `live` saying whether the
+// lane's outputs exist.
+template <bool ACC = false, int EPI = -1>   // EPI >= 0: the map's epilogue as a compile-time constant (the caller has branched on it once)
+__device__ __forceinline__ void wide_store(const GemmD& g, int r, int n0, int tile, const float (&v)[4], const uint4& xr, bool live = true) {
     const StepParams& P = sP;
     const Dims& D = P.D;
     const DevState& s = P.s;
     const int tid = threadIdx.x;
     {
         const bool full = n0 + 3 < g.N;
-        switch (g.epi) {
+        switch (EPI >= 0 ? EPI : g.epi) {
         case SE_GELU:
             stw64(g.out + toff(r, n0, g.N >> 5),
                   (uint64_t)pack_bf16(gelu_s(v[0]), gelu_s(v[1])) | ((uint64_t)pack_bf16(gelu_s(v[2]), gelu_s(v[3])) << 32));
@@ -1102,15 +1106,17 @@ __device__ __forceinline__ void wide_store(const GemmD& g, int r, int n0, int ti
             // residual update; the statistics of the tile's 16 columns come from the four threads of the row
             const float x0 = __uint_as_float(xr.x) + v[0], x1 = __uint_as_float(xr.y) + v[1];
             const float x2 = __uint_as_float(xr.z) + v[2], x3 = __uint_as_float(xr.w) + v[3];
-            stwf2(s.x + (size_t)r * g.N + n0, x0, x1);
-            stwf2(s.x + (size_t)r * g.N + n0 + 2, x2, x3);
-            stw64(g.out + toff(r, n0, g.N >> 5), (uint64_t)pack_bf16(x0, x1) | ((uint64_t)pack_bf16(x2, x3) << 32));
+            if (live) {
+                stwf2(s.x + (size_t)r * g.N + n0, x0, x1);
+                stwf2(s.x + (size_t)r * g.N + n0 + 2, x2, x3);
+                stw64(g.out + toff(r, n0, g.N >> 5), (uint64_t)pack_bf16(x0, x1) | ((uint64_t)pack_bf16(x2, x3) << 32));
+            }
             float sum = x0 + x1 + x2 + x3;
-            sum = quad_sum(sum);
+            sum = ACC ? rows_sum(sum) : quad_sum(sum);
             const float mean = sum * (1.f / 16.f);
             float m2 = (x0 - mean) * (x0 - mean) + (x1 - mean) * (x1 - mean) + (x2 - mean) * (x2 - mean) + (x3 - mean) * (x3 - mean);
-            m2 = quad_sum(m2);
-            if ((tid & 3) == 0) stwf2(g.stats_out + ((size_t)tile * g.R + r) * 2, mean, m2);
+            m2 = ACC ? rows_sum(m2) : quad_sum(m2);
+            if (live && (ACC ? (tid & 48) == 0 : (tid & 3) == 0)) stwf2(g.stats_out + ((size_t)tile * g.R + r) * 2, mean, m2);
             break;
         }
         case SE_QKV: {
@@ -1207,39 +1213,45 @@ __device__ __forceinline__ void gemm_big_impl(const GemmD& g, int nt, int row0) 
             for (int ct = 0; ct < NCT; ++ct) {
                 const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, b[kk][ct]);
 #pragma unroll
-                for (int rt = 0; rt < NRT; ++rt)
-                    acc[ct][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[kk][rt]), bfrag,
+                for (int rt = 0; rt < NRT; ++rt)   // weights first: a lane then holds four consecutive columns of one row
+                    acc[ct][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfrag, __builtin_bit_cast(bf16x8_t, a[kk][rt]),
                                                                           acc[ct][rt], 0, 0, 0);
             }
     };
     // four stages are in flight in registers besides the one being multiplied: with ~2 us from a
     // load's issue to its data under load, a compute unit needs over 100 KB outstanding to keep
     // its matrix cores fed
+    // row statistics of the LayerNorm folded into the map: two threads per row merge the row's tile statistics.
+    // Their first 64 tiles (all of them up to K = 1024) are requested BEFORE the operand stages: asked for after
+    // them they would return behind 128 KB of operands and the first stage's copy into LDS would wait for them.
+    const bool do_stats = g.stats != nullptr;
+    const int tiles = g.K >> 4;
+    const int srow = tid >> 1, sr = row0 + srow;
+    const float2* sp = (const float2*)g.stats + (sr < g.R ? sr : 0);
+    float2 sv[32];
+    float c0 = 0.f;   // shift of the tile means, see gemm_unit
+    if (do_stats) {
+        c0 = ldgf2(sp).x;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            const int t = (tid & 1) + 2 * j;
+            sv[j] = ldgf2(sp + (size_t)(t < tiles ? t : 0) * g.R);
+        }
+    }
     uint4 G0[8], G1[8], G2[8], G3[8];
     gload(0, G0);
     gload(1, G1);
     gload(2, G2);
     gload(3, G3);
-    // row statistics of the LayerNorm folded into the map: two threads per row merge the row's
-    // tile statistics (while the first stages are on their way)
-    const bool do_stats = g.stats != nullptr;
-    const int tiles = g.K >> 4;
     if (do_stats) {
-        const int srow = tid >> 1, sr = row0 + srow;
-        float s1 = 0.f, s2 = 0.f, s3 = 0.f, c0 = 0.f;   // c0: shift of the tile means, see gemm_unit
+        float s1 = 0.f, s2 = 0.f, s3 = 0.f;
         if (sr < g.R) {
-            const float2* sp = (const float2*)g.stats + sr;
-            c0 = ldgf2(sp).x;
-            for (int t0 = tid & 1; t0 < tiles; t0 += 64) {   // 32 loads in flight: one latency up to K = 1024
-                float2 v[32];
 #pragma unroll
-                for (int j = 0; j < 32; ++j) {
-                    const int t = t0 + 2 * j;
-                    v[j] = ldgf2(sp + (size_t)(t < tiles ? t : 0) * g.R);
-                }
-#pragma unroll
-                for (int j = 0; j < 32; ++j)
-                    if (t0 + 2 * j < tiles) { const float dv = v[j].x - c0; s1 += dv; s2 += v[j].y; s3 += dv * dv; }
+            for (int j = 0; j < 32; ++j)
+                if ((tid & 1) + 2 * j < tiles) { const float dv = sv[j].x - c0; s1 += dv; s2 += sv[j].y; s3 += dv * dv; }
+            for (int t = 64 + (tid & 1); t < tiles; t += 2) {   // K > 1024
+                const float2 v = ldgf2(sp + (size_t)t * g.R);
+                const float dv = v.x - c0; s1 += dv; s2 += v.y; s3 += dv * dv;
             }
         }
         s1 = pair_sum(s1);
@@ -1283,68 +1295,65 @@ __device__ __forceinline__ void gemm_big_impl(const GemmD& g, int nt, int row0) 
     for (; c + 8 < nch; c += 4) round(c, std::true_type{});
     for (; c < nch; c += 4) round(c, std::false_type{});
     tp(g.ph, 2);   // reduction done
-    // epilogue inputs of this thread for the four 64 x 64 quarters (row tid / 4 of the quarter,
-    // columns 4 (tid % 4) .. + 3 of each of its column tiles), fetched before the accumulators
-    // travel through LDS
-    const int erow = tid >> 2;
+    // Epilogue straight from the accumulators: with the weight tile as the MFMA's first operand, lane (lc, gq) of wave
+    // (wr, wc) holds, for each of its 4 x 4 tiles, row 16 rt + lc of the wave's 64 rows and columns 4 gq .. 4 gq + 3 of
+    // the tile: four consecutive outputs of one row, which is what every store of the epilogue takes (no trip of
+    // the 128 x 128 results through LDS).
+    const int lc = lane & 15, gq = lane >> 4;
     const bool resid = g.epi == SE_RESID;
-    uint4 cs4[2][NCT], b4[2][NCT], xr4[4][NCT];
+    uint4 cs4[NCT], b4[NCT];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int ct = 0; ct < NCT; ++ct) {
-            const int tile = nt + 4 * h + ct, n0 = tile * 16 + (tid & 3) * 4;
-            cs4[h][ct] = b4[h][ct] = make_uint4(0, 0, 0, 0);
-            if (tile < NT) {
-                if (g.colsum) cs4[h][ct] = ldg4(g.colsum + n0);
-                if (g.bias) b4[h][ct] = ldg4(g.bias + n0);
-            }
-        }
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int ct = 0; ct < NCT; ++ct) {
-            const int tile = nt + 4 * (q & 1) + ct, n0 = tile * 16 + (tid & 3) * 4;
-            const int er = row0 + 64 * (q >> 1) + erow;
-            xr4[q][ct] = make_uint4(0, 0, 0, 0);
-            if (resid && tile < NT && er < g.R) xr4[q][ct] = ldg4(s.x + (size_t)er * g.N + n0);
-        }
-    float* red = (float*)smem;   // [wave][ct][rt][lane][4]: wave (wr, wc) holds quarter q = 2 wr + wc
-#pragma unroll
-    for (int ct = 0; ct < NCT; ++ct)
-#pragma unroll
-        for (int rt = 0; rt < NRT; ++rt)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) red[(((wave * NCT + ct) * NRT + rt) * 64 + lane) * 4 + i] = acc[ct][rt][i];
-    __syncthreads();
-    tp(g.ph, 3);   // accumulators in LDS
-    const int rt = erow >> 4, rr = erow & 15;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int r = row0 + 64 * (q >> 1) + erow;
-        if (r >= g.R) continue;
-        const float mu = do_stats ? s_stat[64 * (q >> 1) + erow] : 0.f;
-        const float rstd = do_stats ? s_stat[128 + 64 * (q >> 1) + erow] : 1.f;
-#pragma unroll
-        for (int ct = 0; ct < NCT; ++ct) {
-            const int tile = nt + 4 * (q & 1) + ct, n0 = tile * 16 + (tid & 3) * 4;
-            if (tile >= NT || n0 >= g.N) continue;
-            float v[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int col = (tid & 3) * 4 + j;
-                float a = red[q * (NCT * NRT * 256) + ((ct * NRT + rt) * 64 + (rr >> 2) * 16 + col) * 4 + (rr & 3)];
-                const uint4 &csv = cs4[q & 1][ct], &bv = b4[q & 1][ct];
-                const float csj = __uint_as_float(j == 0 ? csv.x : j == 1 ? csv.y : j == 2 ? csv.z : csv.w);
-                const float bj = __uint_as_float(j == 0 ? bv.x : j == 1 ? bv.y : j == 2 ? bv.z : bv.w);
-                if (do_stats) a = rstd * (a - mu * csj);
-                v[j] = a + bj;
-            }
-            wide_store(g, r, n0, tile, v, xr4[q][ct]);
+    for (int ct = 0; ct < NCT; ++ct) {
+        const int tile = nt + 4 * wc + ct, n0 = tile * 16 + 4 * gq;
+        cs4[ct] = b4[ct] = make_uint4(0, 0, 0, 0);
+        if (tile < NT) {
+            if (g.colsum) cs4[ct] = ldg4(g.colsum + n0);
+            if (g.bias) b4[ct] = ldg4(g.bias + n0);
         }
     }
+    tp(g.ph, 3);
+    // one copy of the loops per kind of epilogue, chosen once: inside them the kind is a compile-time constant, so
+    // the 16 stores of a lane are straight-line code (no branch chain and no read of the parameter block per store)
+    auto finish = [&](auto kind) {
+        constexpr int EPI = decltype(kind)::value;
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) {
+            const int urow = 64 * wr + 16 * rt + lc, r = row0 + urow;
+            const float mu = do_stats ? s_stat[urow] : 0.f;
+            const float rstd = do_stats ? s_stat[128 + urow] : 1.f;
+            uint4 xr4[NCT];
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                const int tile = nt + 4 * wc + ct, n0 = tile * 16 + 4 * gq;
+                xr4[ct] = make_uint4(0, 0, 0, 0);
+                if (EPI == SE_RESID && tile < NT && r < g.R) xr4[ct] = ldg4(s.x + (size_t)r * g.N + n0);
+            }
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                const int tile = nt + 4 * wc + ct, n0 = tile * 16 + 4 * gq;
+                const bool live = r < g.R && tile < NT && n0 < g.N;
+                float v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float a = acc[ct][rt][j];
+                    const float csj = __uint_as_float(j == 0 ? cs4[ct].x : j == 1 ? cs4[ct].y : j == 2 ? cs4[ct].z : cs4[ct].w);
+                    const float bj = __uint_as_float(j == 0 ? b4[ct].x : j == 1 ? b4[ct].y : j == 2 ? b4[ct].z : b4[ct].w);
+                    if (do_stats) a = rstd * (a - mu * csj);
+                    v[j] = a + bj;
+                }
+                // the residual update's tile statistics are lane exchanges: every lane takes part, live or not
+                if (EPI == SE_RESID || live) wide_store<true, EPI>(g, r, n0, tile, v, xr4[ct], live);
+            }
+        }
+    };
+    switch (g.epi) {
+    case SE_GELU: finish(std::integral_constant<int, SE_GELU>{}); break;
+    case SE_QKV: finish(std::integral_constant<int, SE_QKV>{}); break;
+    case SE_RESID: finish(std::integral_constant<int, SE_RESID>{}); break;
+    case SE_LOGITS: finish(std::integral_constant<int, SE_LOGITS>{}); break;
+    default: finish(std::integral_constant<int, SE_F32>{}); break;
+    }
 }
-
 __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
     constexpr int NRT = 4, NCT = 4, CH = 2;
     const int ph_u = __builtin_amdgcn_readfirstlane(ph_), u_u = __builtin_amdgcn_readfirstlane(u_);

@@ -170,6 +170,7 @@ static inline float __int_as_float(int u) { float f; memcpy(&f, &u, 4); return f
 static inline int __float_as_int(float f) { int u; memcpy(&u, &f, 4); return u; }
 #define __expf(x) expf(x)
 static inline float __frcp_rn(float x) { return 1.0f / x; }
+static inline float __builtin_amdgcn_rcpf(float x) { return 1.0f / x; }
 static inline float rsqrtf(float x) { return 1.0f / sqrtf(x); }
 static inline int min(int a, int b) { return a < b ? a : b; }
 static inline int max(int a, int b) { return a > b ? a : b; }
