@@ -353,6 +353,57 @@ __device__ inline void dev_commit_kv(const Dims& D, const DevState& s, int layer
         }
 }
 
+// The same for nl consecutive layers from layer0 on (the step kernel's compaction units: with many sequences a unit
+// takes several layers, so that a workgroup has one unit instead of a chain of them, each a few dependent trips to
+// memory).  The path is read once; four layers' rows are in flight together; a path whose rows already sit where they
+// belong (the root alone, or nodes 0, 1, .. of the tree) moves nothing.
+template <class T>
+__device__ inline void dev_commit_kv_layers(const Dims& D, const DevState& s, int layer0, int nl, int b, int head, int dim) {
+    constexpr int W = VADUSA_MAX_DRAFT_HEADS + 1, LB = 4;
+    const int32_t* path = s.path + (size_t)b * (VADUSA_MAX_DRAFT_HEADS + 2);
+    const int cnt = ldci(s.acc_len + b);
+    if (cnt <= 0) return;
+    const int L0 = ldci(s.L + b) - cnt;
+    int src[W];
+    bool moves = false;
+#pragma unroll
+    for (int j = 0; j < W; ++j) {
+        src[j] = j < cnt ? ldci(path + 1 + j) : j;
+        moves |= src[j] != j;
+    }
+    if (!moves) return;
+    size_t so_k[W], so_v[W], do_k[W], do_v[W];
+#pragma unroll
+    for (int j = 0; j < W; ++j) {
+        so_k[j] = kc_off(L0 + src[j], dim); so_v[j] = vc_off(L0 + src[j], dim);
+        do_k[j] = kc_off(L0 + j, dim); do_v[j] = vc_off(L0 + j, dim);
+    }
+    const size_t lstride = (size_t)D.Bmax * D.nH * kv_cap(D.maxpos) * 64;
+    const size_t hb0 = ((((size_t)layer0 * D.Bmax + b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
+    for (int l0 = 0; l0 < nl; l0 += LB) {
+        T kr[LB][W], vr[LB][W];
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const size_t hb = hb0 + (size_t)(l0 + i < nl ? l0 + i : nl - 1) * lstride;
+            const T* Kh = (const T*)s.Kc + hb;
+            const T* Vh = (const T*)s.Vc + hb;
+#pragma unroll
+            for (int j = 0; j < W; ++j)
+                if (j < cnt) { kr[i][j] = Kh[so_k[j]]; vr[i][j] = Vh[so_v[j]]; }
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            if (l0 + i >= nl) break;
+            const size_t hb = hb0 + (size_t)(l0 + i) * lstride;
+            T* Kh = (T*)s.Kc + hb;
+            T* Vh = (T*)s.Vc + hb;
+#pragma unroll
+            for (int j = 0; j < W; ++j)
+                if (j < cnt) { Kh[do_k[j]] = kr[i][j]; Vh[do_v[j]] = vr[i][j]; }
+        }
+    }
+}
+
 // Draft list of head i, sequence b: the VADUSA_MAX_TOPK best ids of its logits,
 // descending, equal logits: lower id first (Sec. 2.1).
 // Up to 4096 logits sit in registers (16 per thread).  The 256 threads form 64 quads; the 64

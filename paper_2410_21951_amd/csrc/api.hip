@@ -313,7 +313,7 @@ static Dims make_dims(const vadusa_ctx* c, int B, int M) {
 // The launch-independent part of the step kernel's parameters.
 static StepParams base_params(const vadusa_ctx* c, const Dims& D) {
     StepParams P{};
-    P.D = D; P.s = c->s; P.big_min = c->big_min;
+    P.D = D; P.s = c->s; P.big_min = c->big_min; P.allq_min = c->allq_min;
     P.lw0 = c->layers[0]; P.dw0 = c->draft[0];
     P.lw_stride = c->layers.size() > 1 ? (size_t)((const char*)c->layers[1].Wqkv - (const char*)c->layers[0].Wqkv) : 0;
     P.dw_stride = c->draft.size() > 1 ? (size_t)((const char*)c->draft[1].W1 - (const char*)c->draft[0].W1) : 0;
@@ -366,7 +366,11 @@ extern "C" int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena
     c->errored = 0;
     c->persistent = getenv("VADUSA_PHASE_LAUNCHES") ? 0 : 1;
     c->profile = getenv("VADUSA_PHASE_CLOCK") ? std::max(1, atoi(getenv("VADUSA_PHASE_CLOCK"))) : 0;   // n: workgroup n - 1 records
-    c->big_min = getenv("VADUSA_BIG_MIN_UNITS") ? std::max(1, atoi(getenv("VADUSA_BIG_MIN_UNITS"))) : 256;
+    // 128 x 128 units from 129 of them on (more than half of the 256 compute units busy for one round: with fewer, the
+    // four times as many 64 x 64 units take two rounds of less than half the time each); whole-head attention units
+    // once there is one per compute unit
+    c->big_min = getenv("VADUSA_BIG_MIN_UNITS") ? std::max(1, atoi(getenv("VADUSA_BIG_MIN_UNITS"))) : 129;
+    c->allq_min = getenv("VADUSA_BIG_MIN_UNITS") ? c->big_min : 256;
     {
         int dev = 0;
         hipDeviceProp_t prop;

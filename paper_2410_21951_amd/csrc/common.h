@@ -271,7 +271,7 @@ struct vadusa_ctx {
     float* scores;               // same shape: perturbed scores that replace the logits in such a step
     int sampled;                 // the pending / last verification was a stochastic one
     int gtab_ready;              // the descriptor table of the layer maps has been written (after the weights are placed)
-    int big_min;                 // StepParams::big_min (256 = one unit per compute unit; environment VADUSA_BIG_MIN_UNITS, for tests of small shapes)
+    int big_min, allq_min;       // StepParams::big_min, allq_min (environment VADUSA_BIG_MIN_UNITS sets both, for tests of small shapes)
     uint32_t epoch;              // grid-barrier epoch reached so far
     int errored;                 // a step kernel gave up at a grid barrier: every call but vadusa_prefill refuses until that resets the context
     std::string err;
@@ -322,6 +322,7 @@ struct StepParams {
     DraftW dw0;
     size_t lw_stride, dw_stride;
     int big_min;        // many-row kernel: a map takes 128 x 128 units if it has at least this many of them
+    int allq_min;       // many-row kernel: an attention unit is a whole (sequence, head) if there are at least this many
     int topk_apart;     // 1: the last phase only compacts the KV cache; the draft lists come from the stand-alone top-k kernel
 };
 // Phases of the step kernel after the decoder layers, as offsets from H = 1 + 5 * n_layers.

@@ -101,13 +101,14 @@ __host__ __device__ inline int pad8(int a) { return (a + 7) & ~7; }
 
 int step_num_phases(int n_layers) { return 1 + 5 * n_layers + TP_COUNT; }
 
-// Maps of the many-row kernel large enough to give every compute unit a 128 x 128 output unit
-// (StepParams::big_min of them) take those (operands staged through LDS and shared by the four waves); smaller ones keep
-// the 64 x 64 units whose waves split the reduction.
+// Maps of the many-row kernel with at least StepParams::big_min 128 x 128 output units (more than half the compute
+// units) take those (operands staged through LDS and shared by the four waves); smaller ones keep the 64 x 64 units
+// whose waves split the reduction.  The base head (its epilogue stores single floats of rows that are not 16-byte
+// aligned, which a 128 x 128 unit does 64 times per lane) takes them only with one per compute unit (allq_min).
 __host__ __device__ inline bool wide_big(int R, int N, int min_units) { return cdiv(R, 128) * cdiv(N, 128) >= min_units; }
 // Attention units of the many-row kernel are whole (sequence, head)s once there is one per compute unit
 // (up to four query tiles: one per wave).
-__host__ __device__ inline bool attn_allq(const StepParams& P) { return P.wide && P.D.M <= 64 && P.D.B * P.D.nH >= P.big_min; }
+__host__ __device__ inline bool attn_allq(const StepParams& P) { return P.wide && P.D.M <= 64 && P.D.B * P.D.nH >= P.allq_min; }
 // Few-row kernel, maps with more than 32 rows whose width is a multiple of 32 (QKV, FFN1): units
 // of 32 rows x 32 columns instead of 64 x 16.  What bounds such a phase is the bytes the compute
 // units pull through L2 (every unit reads its rows of X and its columns of W over the whole K):
@@ -115,6 +116,13 @@ __host__ __device__ inline bool attn_allq(const StepParams& P) { return P.wide &
 __host__ __device__ inline bool sq_units(const StepParams& P, int N) { return !P.wide && P.D.B * P.D.M > 32 && N % 32 == 0; }
 // Units of the last phase that rank the draft heads' logits (none when a stand-alone kernel does it).
 __host__ __device__ inline int topk_units(const StepParams& P) { return P.topk_apart ? 0 : P.D.Hh * P.D.B; }
+// Layers per KV compaction unit (a unit: four heads of one sequence): one while all units of the step fit one round
+// of the 256 workgroups, more with more sequences, so that a workgroup still has a single unit.
+__host__ __device__ inline int commit_layers(const StepParams& P) {
+    const int per_layer = cdiv(P.D.nH, 4) * P.nseq;
+    const int lg = cdiv(P.D.Ly * per_layer, 256);
+    return lg < 1 ? 1 : lg > P.D.Ly ? P.D.Ly : lg;
+}
 __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     const Dims& D = P.D;
     const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
@@ -122,7 +130,7 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     if (P.wide && ph >= 1 && ph <= H && (ph == H || (ph - 1) % 5 != 1)) {
         // 64 x 64 output tiles: groups of four column tiles; 128 x 128: groups of eight
         const int N = ph == H ? D.V1 : (ph - 1) % 5 == 0 ? 3 * D.d : (ph - 1) % 5 == 3 ? D.F : D.d;
-        if (wide_big(R, N, P.big_min)) return pad8(cdiv(cdiv(N, 16), 8)) * cdiv(R, 128);
+        if (wide_big(R, N, ph == H ? P.allq_min : P.big_min)) return pad8(cdiv(cdiv(N, 16), 8)) * cdiv(R, 128);
         return pad8(cdiv(cdiv(N, 16), 4)) * RG;
     }
     if (ph < H) {
@@ -142,7 +150,7 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     case TP_FINAL: return P.nseq;
     case TP_COMMIT: return D.Hh * (D.d / 16) * RGb;
     case TP_DRAFT2: return D.Hh * cdiv(D.V1, 16) * RGb;
-    default: return topk_units(P) + D.Ly * cdiv(D.nH, 4) * P.nseq;   // TP_TOPK: draft lists, then KV compaction
+    default: return topk_units(P) + cdiv(D.Ly, commit_layers(P)) * cdiv(D.nH, 4) * P.nseq;   // TP_TOPK: draft lists, then KV compaction
     }
 }
 
@@ -321,7 +329,7 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
     int wrows = 64;   // rows per unit of the many-row kernel
     auto split = [&](int NT) {
         if (wide) {   // unit = (row block) * pad8(tile groups) + group of G column tiles
-            if (wide_big(R, g.N, P.big_min)) { g.G = 8; wrows = 128; }
+            if (wide_big(R, g.N, ph == H ? P.allq_min : P.big_min)) { g.G = 8; wrows = 128; }
             const int NG = cdiv(NT, g.G), NGp = pad8(NG), gidx = u % NGp;
             rb = u / NGp;
             nt = gidx * g.G;
@@ -1083,8 +1091,21 @@ __device__ __forceinline__ void gemm_unit42(int ph_, int u_, const uint32_t* gta
 // c + 32, c + 48 of a wave do (the layout of an MFMA result whose first operand was the weight tile), and for the
 // residual update every lane of the wave calls (its tile statistics are lane exchanges), `live` saying whether the
 // lane's outputs exist.
+// Cache row of row r of the QKV map: sequence and position, or a negative position if the row has none (beyond the
+// map's rows or the cache, or a finished sequence).  Asked once per row before the stores: the two loads are a trip to
+// L2 each, and between the write-through stores of an epilogue the compiler does not move or merge them.
+__device__ __forceinline__ void wide_kv_row(const GemmD& g, int r, int& kv_b, int& kv_pos) {
+    const Dims& D = sP.D;
+    const DevState& s = sP.s;
+    kv_b = 0; kv_pos = -1;
+    if (g.epi != SE_QKV || r >= g.R) return;
+    kv_b = r / D.M;
+    const int pos = ldg(s.L + kv_b) + (r - kv_b * D.M);
+    if (pos < D.maxpos && ldg(s.n_rows + kv_b) > 0) kv_pos = pos;
+}
 template <bool ACC = false, int EPI = -1>   // EPI >= 0: the map's epilogue as a compile-time constant (the caller has branched on it once)
-__device__ __forceinline__ void wide_store(const GemmD& g, int r, int n0, int tile, const float (&v)[4], const uint4& xr, bool live = true) {
+__device__ __forceinline__ void wide_store(const GemmD& g, int r, int n0, int tile, const float (&v)[4], const uint4& xr, bool live = true,
+                                           int kv_b = 0, int kv_pos = -1) {
     const StepParams& P = sP;
     const Dims& D = P.D;
     const DevState& s = P.s;
@@ -1122,17 +1143,16 @@ __device__ __forceinline__ void wide_store(const GemmD& g, int r, int n0, int ti
         case SE_QKV: {
             const uint64_t pk = (uint64_t)pack_bf16(v[0], v[1]) | ((uint64_t)pack_bf16(v[2], v[3]) << 32);
             if (n0 < D.d) { stw64(g.out + toff(r, n0, D.d >> 5), pk); break; }
-            const int b = r / D.M, node = r - b * D.M;
-            const int which = n0 / D.d - 1, cc = n0 % D.d, head = cc >> 6, dim = cc & 63;
-            const int pos = ldg(s.L + b) + node;
-            if (pos < D.maxpos && ldg(s.n_rows + b) > 0) {
-                const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
+            // key / value columns: row r is position kv_pos of sequence kv_b's cache (wide_kv_row; negative: no such row)
+            const int which = n0 >= 2 * D.d, cc = n0 - (which + 1) * D.d, head = cc >> 6, dim = cc & 63;
+            if (kv_pos >= 0) {
+                const size_t hb = ((((size_t)g.layer * D.Bmax + kv_b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
                 if (which) {
-                    bf16_t* vp = (bf16_t*)s.Vc + hb + vc_off(pos, dim);   // four dimensions of one position: four lanes of a value tile
+                    bf16_t* vp = (bf16_t*)s.Vc + hb + vc_off(kv_pos, dim);   // four dimensions of one position: four lanes of a value tile
 #pragma unroll
                     for (int j = 0; j < 4; ++j) stw16(vp + j * 8, f2bf(v[j]));
                 } else {
-                    stw64((bf16_t*)s.Kc + hb + kc_off(pos, dim), pk);   // four dimensions of one key: half of a lane's piece
+                    stw64((bf16_t*)s.Kc + hb + kc_off(kv_pos, dim), pk);   // four dimensions of one key: half of a lane's piece
                 }
             }
             break;
@@ -1312,8 +1332,81 @@ __device__ __forceinline__ void gemm_big_impl(const GemmD& g, int nt, int row0) 
         }
     }
     tp(g.ph, 3);
+    if (g.epi == SE_QKV && nt * 16 >= 2 * P.D.d) {
+        // A unit of value columns.  The value cache keeps eight consecutive positions of one dimension together
+        // (16 bytes), and a lane holds four dimensions of one position: stored from here the unit would be 64
+        // two-byte stores per lane.  The unit's values go through LDS instead ([dimension][row], rows padded to
+        // 130 so that a wave's dimensions fall into different banks) and leave as whole 16-byte pieces: a thread
+        // owns one dimension (tid & 127), each half of the workgroup every other piece of eight positions of every
+        // sequence that has rows in the unit; a piece that the unit's rows cover only in part (the sequence's
+        // length is not a multiple of eight, or its rows continue in another unit) is stored position by position.
+        const Dims& D = P.D;
+        constexpr int VT = 130;
+        bf16_t* vt = (bf16_t*)smem;
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) {
+            const int urow = 64 * wr + 16 * rt + lc;
+            const float mu = do_stats ? s_stat[urow] : 0.f;
+            const float rstd = do_stats ? s_stat[128 + urow] : 1.f;
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct)
+            {
+                float v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float a = acc[ct][rt][j];
+                    const float csj = __uint_as_float(j == 0 ? cs4[ct].x : j == 1 ? cs4[ct].y : j == 2 ? cs4[ct].z : cs4[ct].w);
+                    const float bj = __uint_as_float(j == 0 ? b4[ct].x : j == 1 ? b4[ct].y : j == 2 ? b4[ct].z : b4[ct].w);
+                    if (do_stats) a = rstd * (a - mu * csj);
+                    v[j] = a + bj;
+                }
+                const uint32_t p01 = pack_bf16(v[0], v[1]), p23 = pack_bf16(v[2], v[3]);
+                bf16_t* w = vt + (64 * wc + 16 * ct + 4 * gq) * VT + urow;
+                w[0] = (bf16_t)p01; w[VT] = (bf16_t)(p01 >> 16); w[2 * VT] = (bf16_t)p23; w[3 * VT] = (bf16_t)(p23 >> 16);
+            }
+        }
+        __syncthreads();
+        const int udim = tid & 127, half = wave >> 1;
+        const int col = nt * 16 + udim - 2 * D.d, head = col >> 6, dd = col & 63;
+        const bool col_ok = nt * 16 + udim < g.N;
+        const int r_end = row0 + 128 < g.R ? row0 + 128 : g.R;
+        const bf16_t* vrow = vt + udim * VT;
+        for (int b = row0 / D.M; b * D.M < r_end; ++b) {
+            const int n_lo = row0 > b * D.M ? row0 - b * D.M : 0, n_hi = r_end - b * D.M < D.M ? r_end - b * D.M : D.M;
+            if (ldg(s.n_rows + b) <= 0) continue;
+            const int L = ldg(s.L + b);
+            const int p_lo = L + n_lo, p_hi = L + n_hi < D.maxpos ? L + n_hi : D.maxpos;
+            if (p_hi <= p_lo) continue;
+            const size_t hb = ((((size_t)g.layer * D.Bmax + b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
+            const int ubase = b * D.M - L - row0;   // position p is row p + ubase of the unit
+            for (int o = (p_lo >> 3) + half; o <= ((p_hi - 1) >> 3); o += 2) {
+                const int p0 = o * 8;
+                uint32_t hw[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    int i = p0 + e + ubase;
+                    i = i < 0 ? 0 : i > 127 ? 127 : i;
+                    hw[e] = vrow[i];
+                }
+                bf16_t* dst = (bf16_t*)s.Vc + hb + vc_off(p0, dd);
+                if (!col_ok) continue;
+                if (p0 >= p_lo && p0 + 8 <= p_hi) {
+                    stw64(dst, (uint64_t)(hw[0] | (hw[1] << 16)) | ((uint64_t)(hw[2] | (hw[3] << 16)) << 32));
+                    stw64(dst + 4, (uint64_t)(hw[4] | (hw[5] << 16)) | ((uint64_t)(hw[6] | (hw[7] << 16)) << 32));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (p0 + e >= p_lo && p0 + e < p_hi) stw16(dst + e, (bf16_t)hw[e]);
+                }
+            }
+        }
+        return;
+    }
     // one copy of the loops per kind of epilogue, chosen once: inside them the kind is a compile-time constant, so
     // the 16 stores of a lane are straight-line code (no branch chain and no read of the parameter block per store)
+    int kv_b[NRT], kv_pos[NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) wide_kv_row(g, row0 + 64 * wr + 16 * rt + lc, kv_b[rt], kv_pos[rt]);
     auto finish = [&](auto kind) {
         constexpr int EPI = decltype(kind)::value;
 #pragma unroll
@@ -1342,7 +1435,7 @@ __device__ __forceinline__ void gemm_big_impl(const GemmD& g, int nt, int row0) 
                     v[j] = a + bj;
                 }
                 // the residual update's tile statistics are lane exchanges: every lane takes part, live or not
-                if (EPI == SE_RESID || live) wide_store<true, EPI>(g, r, n0, tile, v, xr4[ct], live);
+                if (EPI == SE_RESID || live) wide_store<true, EPI>(g, r, n0, tile, v, xr4[ct], live, kv_b[rt], kv_pos[rt]);
             }
         }
     };
@@ -1402,6 +1495,8 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
             if (g.epi == SE_RESID && er < g.R) xr4[ct] = ldg4(s.x + (size_t)er * g.N + n0);
         }
     }
+    int kv_b, kv_pos;
+    wide_kv_row(g, er, kv_b, kv_pos);
     float s1 = 0.f, s2 = 0.f, s3 = 0.f, c0 = 0.f;   // c0: shift of the tile means, see gemm_unit
     const int tiles = g.K >> 4;
     const bool do_stats = g.stats != nullptr;
@@ -1500,7 +1595,7 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
             if (do_stats) a = rstd * (a - mu * csj);
             v[j] = a + bj;
         }
-        wide_store(g, r, n0, nt + ct, v, xr4[ct]);
+        wide_store(g, r, n0, nt + ct, v, xr4[ct], true, kv_b, kv_pos);
     }
 }
 
@@ -1959,11 +2054,12 @@ __device__ __forceinline__ void final_unit(int u_) {
 __device__ __forceinline__ void commit_unit(int u_) {
     const int u = __builtin_amdgcn_readfirstlane(u_);
     const StepParams& P = sP;
-    // a unit is four heads of one (layer, sequence): one wave (64 head dimensions) per head
+    // a unit is four heads of one sequence over commit_layers(P) layers: one wave (64 head dimensions) per head
     const Dims& D = P.D;
-    const int HQ = cdiv(D.nH, 4);
-    const int head = (u % HQ) * 4 + (int)(threadIdx.x >> 6), b = (u / HQ) % P.nseq, layer = u / (HQ * P.nseq);
-    if (head < D.nH) dev_commit_kv<bf16_t>(D, P.s, layer, P.seq0 + b, head, threadIdx.x & 63);
+    const int HQ = cdiv(D.nH, 4), LG = commit_layers(P);
+    const int head = (u % HQ) * 4 + (int)(threadIdx.x >> 6), b = (u / HQ) % P.nseq, layer0 = u / (HQ * P.nseq) * LG;
+    const int nl = D.Ly - layer0 < LG ? D.Ly - layer0 : LG;
+    if (head < D.nH) dev_commit_kv_layers<bf16_t>(D, P.s, layer0, nl, P.seq0 + b, head, threadIdx.x & 63);
 }
 __device__ __forceinline__ void topk_unit(int u_) { const int u = __builtin_amdgcn_readfirstlane(u_); const StepParams& P = sP; dev_topk(P.D, P.s, u / P.D.B, u % P.D.B); }
 
