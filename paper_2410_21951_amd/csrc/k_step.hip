@@ -109,6 +109,15 @@ __host__ __device__ inline bool wide_big(int R, int N, int min_units) { return c
 // Attention units of the many-row kernel are whole (sequence, head)s once there is one per compute unit
 // (up to four query tiles: one per wave).
 __host__ __device__ inline bool attn_allq(const StepParams& P) { return P.wide && P.D.M <= 64 && P.D.B * P.D.nH >= P.allq_min; }
+// (sequence, head) pairs per whole-head attention unit: a tree of up to 32 (16) nodes has two (one) query tiles, so a
+// workgroup's four waves can take two (four) pairs, each wave a query tile over all its key blocks, as long as that
+// still leaves a unit for every compute unit; otherwise the waves that a pair does not need split its key blocks.
+__host__ __device__ inline int attn_ppu(const StepParams& P) {
+    const int n_qt = (P.D.M + 15) >> 4;
+    int ppu = n_qt >= 3 ? 1 : n_qt == 2 ? 2 : 4;
+    while (ppu > 1 && cdiv(P.D.B * P.D.nH, ppu) < P.allq_min) ppu >>= 1;
+    return ppu;
+}
 // Few-row kernel, maps with more than 32 rows whose width is a multiple of 32 (QKV, FFN1): units
 // of 32 rows x 32 columns instead of 64 x 16.  What bounds such a phase is the bytes the compute
 // units pull through L2 (every unit reads its rows of X and its columns of W over the whole K):
@@ -116,9 +125,10 @@ __host__ __device__ inline bool attn_allq(const StepParams& P) { return P.wide &
 __host__ __device__ inline bool sq_units(const StepParams& P, int N) { return !P.wide && P.D.B * P.D.M > 32 && N % 32 == 0; }
 // Units of the last phase that rank the draft heads' logits (none when a stand-alone kernel does it).
 __host__ __device__ inline int topk_units(const StepParams& P) { return P.topk_apart ? 0 : P.D.Hh * P.D.B; }
-// Layers per KV compaction unit (a unit: four heads of one sequence): one while all units of the step fit one round
-// of the 256 workgroups, more with more sequences, so that a workgroup still has a single unit.
+// Layers per KV compaction unit (a unit: four heads of one sequence): one in the few-row kernels and while all units of
+// the step fit one round of the 256 workgroups, more with more sequences, so that a workgroup still has a single unit.
 __host__ __device__ inline int commit_layers(const StepParams& P) {
+    if (!P.wide) return 1;
     const int per_layer = cdiv(P.D.nH, 4) * P.nseq;
     const int lg = cdiv(P.D.Ly * per_layer, 256);
     return lg < 1 ? 1 : lg > P.D.Ly ? P.D.Ly : lg;
@@ -136,7 +146,7 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     if (ph < H) {
         switch ((ph - 1) % 5) {
         case 0: return sq_units(P, 3 * D.d) ? pad8(3 * D.d / 32) * cdiv(R, P.mid ? 64 : 32) : pad8(3 * D.d / 16) * RG;
-        case 1: return attn_allq(P) ? pad8(D.B * D.nH) : pad8(D.B * D.nH) * cdiv(D.M, 16);
+        case 1: return attn_allq(P) ? pad8(cdiv(D.B * D.nH, attn_ppu(P))) : pad8(D.B * D.nH) * cdiv(D.M, 16);
         case 2: return pad8(D.d / 16) * (P.mid ? cdiv(R, 32) : RB);
         case 3: return sq_units(P, D.F) ? pad8(D.F / 32) * cdiv(R, P.mid ? 64 : 32) : pad8(D.F / 16) * RG;
         default: return pad8(D.d / 16) * (P.mid ? cdiv(R, 32) : RB);
@@ -1622,15 +1632,24 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     // one XCD (workgroup i is on XCD i mod 8) and share its L2 for that head's K / V rows
     const int BH = pad8(D.B * D.nH);
     int bh, qt, h, b;
-    // ALLQ: with three or four query tiles a wave takes one; with two, two waves share a tile's key
-    // blocks; with one, all four do (wpq = waves per query tile)
+    // ALLQ: the workgroup's four waves are 4 / wpq tile slots of wpq waves each (wpq = waves per query tile, which
+    // split the tile's key blocks); slot t is query tile t % qts of the unit's pair t / qts.  With three or four
+    // query tiles a unit is one pair and a wave takes a tile; with two tiles (one tile) a unit is up to two (four)
+    // pairs (attn_ppu).
     const int n_qt = (D.M + 15) >> 4;
-    const int wpq = !ALLQ ? 4 : n_qt >= 3 ? 1 : n_qt == 2 ? 2 : 4;
-    if (ALLQ) { bh = u; qt = wave / wpq; }
+    const int ppu = ALLQ ? attn_ppu(P) : 1, qts = n_qt >= 3 ? 4 : n_qt;
+    const int wpq = !ALLQ ? 4 : 4 / (qts * ppu);
+    bool live = true;   // ALLQ: the wave's slot has a pair and a query tile
+    if (ALLQ) {
+        const int t = wave / wpq;
+        bh = u * ppu + t / qts;
+        qt = t % qts;
+        live = bh < D.B * D.nH && qt * 16 < D.M;
+        if (!live) { if (wpq == 1) return; bh = 0; qt = 0; }   // (wpq > 1: a workgroup barrier follows, the wave stays)
+    }
     else if ((BH & (BH - 1)) == 0) { bh = u & (BH - 1); qt = u >> __builtin_ctz(BH); }   // no division in the usual case
     else { bh = u % BH; qt = u / BH; }
-    if (bh >= D.B * D.nH) return;
-    if (ALLQ && qt * 16 >= D.M) return;   // three query tiles: the fourth wave has none (wpq = 1: no workgroup barrier follows)
+    if (!ALLQ && bh >= D.B * D.nH) return;
     if ((D.nH & (D.nH - 1)) == 0) { h = bh & (D.nH - 1); b = bh >> __builtin_ctz(D.nH); }
     else { h = bh % D.nH; b = bh / D.nH; }
     // everything the unit needs before its first key block is requested at once: row count,
@@ -1651,15 +1670,19 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     const uint32_t mword[4] = {mw.x, mw.y, mw.z, mw.w};
     bf16_t* att = (bf16_t*)s.att + (size_t)layer * s.act_stride;
     if (n_rows == 0) {
-        if (ALLQ) {
+        if (ALLQ) {   // (the first wave of the slot stores the zeros; with wpq > 1 the waves go on to the merge's barriers)
+            if (live && wave % wpq == 0) {
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-                if (qt * 16 + c < D.M) stw64(att + toff(b * D.M + qt * 16 + c, h * 64 + dt * 16 + 4 * gq, D.d >> 5), 0ull);
+                for (int dt = 0; dt < 4; ++dt)
+                    if (qt * 16 + c < D.M) stw64(att + toff(b * D.M + qt * 16 + c, h * 64 + dt * 16 + 4 * gq, D.d >> 5), 0ull);
+            }
+            if (wpq == 1) return;
+            live = false;
+        } else {
+            const int q = tid >> 4, d0 = (tid & 15) * 4, nd = qt * 16 + q;
+            if (nd < D.M) stw64(att + toff(b * D.M + nd, h * 64 + d0, D.d >> 5), 0ull);
             return;
         }
-        const int q = tid >> 4, d0 = (tid & 15) * 4, nd = qt * 16 + q;
-        if (nd < D.M) stw64(att + toff(b * D.M + nd, h * 64 + d0, D.d >> 5), 0ull);
-        return;
     }
     const int T = min(L + D.M, D.maxpos);
     const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + h) * kv_cap(D.maxpos)) * 64;
@@ -1670,7 +1693,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     f32x4_t O[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) O[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-    const int nblk = (T + 31) >> 5;
+    const int nblk = live ? (T + 31) >> 5 : 0;   // a wave without a tile to compute takes no key block
     // operands of one 32-key block: K rows of the two 16-key tiles (two k-steps each), V^T tiles
     // (the cache keeps them as the MFMA operands themselves: eight contiguous KiB per block; rows of the last block
     // beyond the sequence's end exist, the cache holds whole blocks, and are masked out below)
@@ -1796,11 +1819,14 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
                   (uint64_t)pack_bf16(o[0], o[1]) | ((uint64_t)pack_bf16(o[2], o[3]) << 32));
     }
     else {
-        // merge the waves of each query tile (one tile with four waves, or ALLQ: 4 / wpq tiles)
+        // merge the waves of each tile slot (4 / wpq slots; slot t: pair t / qts of the unit, query tile t % qts)
         const int tiles_here = 4 / wpq;
         for (int t = 0; t < tiles_here; ++t) {
             const int q = tid >> 4, d0 = (tid & 15) * 4, w0 = t * wpq;
-            const int nd = t * 16 + q;
+            const int bh_t = u * ppu + t / qts, nd = (t % qts) * 16 + q;
+            if (bh_t >= D.B * D.nH) continue;
+            const int h = bh_t % D.nH, b = bh_t / D.nH;   // (shadow the wave's own pair)
+            if ((b < ST_SEQ_CACHE ? s_seqRows[b] : ldg(s.n_rows + b)) == 0) continue;   // zeros already stored
             float mstar = sm_m[w0 * 16 + q];
 #pragma unroll
             for (int w = 1; w < 4; ++w)
@@ -2051,15 +2077,23 @@ __device__ __forceinline__ void final_unit(int u_) {
     const StepParams& P = sP;
     dev_finalize<bf16_t>(P.D, P.s, P.seq0 + u, P.prefill_mode, P.ignore_eos, 1);
 }
+template <bool WIDE>
 __device__ __forceinline__ void commit_unit(int u_) {
     const int u = __builtin_amdgcn_readfirstlane(u_);
     const StepParams& P = sP;
-    // a unit is four heads of one sequence over commit_layers(P) layers: one wave (64 head dimensions) per head
+    // a unit is four heads of one sequence over commit_layers(P) layers (one in the few-row kernels): one wave (64 head
+    // dimensions) per head
     const Dims& D = P.D;
-    const int HQ = cdiv(D.nH, 4), LG = commit_layers(P);
-    const int head = (u % HQ) * 4 + (int)(threadIdx.x >> 6), b = (u / HQ) % P.nseq, layer0 = u / (HQ * P.nseq) * LG;
-    const int nl = D.Ly - layer0 < LG ? D.Ly - layer0 : LG;
-    if (head < D.nH) dev_commit_kv_layers<bf16_t>(D, P.s, layer0, nl, P.seq0 + b, head, threadIdx.x & 63);
+    const int HQ = cdiv(D.nH, 4);
+    if constexpr (WIDE) {
+        const int LG = commit_layers(P);
+        const int head = (u % HQ) * 4 + (int)(threadIdx.x >> 6), b = (u / HQ) % P.nseq, layer0 = u / (HQ * P.nseq) * LG;
+        const int nl = D.Ly - layer0 < LG ? D.Ly - layer0 : LG;
+        if (head < D.nH) dev_commit_kv_layers<bf16_t>(D, P.s, layer0, nl, P.seq0 + b, head, threadIdx.x & 63);
+    } else {
+        const int head = (u % HQ) * 4 + (int)(threadIdx.x >> 6), b = (u / HQ) % P.nseq, layer = u / (HQ * P.nseq);
+        if (head < D.nH) dev_commit_kv<bf16_t>(D, P.s, layer, P.seq0 + b, head, threadIdx.x & 63);
+    }
 }
 __device__ __forceinline__ void topk_unit(int u_) { const int u = __builtin_amdgcn_readfirstlane(u_); const StepParams& P = sP; dev_topk(P.D, P.s, u / P.D.B, u % P.D.B); }
 
@@ -2105,7 +2139,7 @@ __device__ __forceinline__ void run_unit(int ph, int u, const uint32_t* gtab) {
     case K_EDGE: edge_unit(u); break;
     case K_SELECT: select_unit(u); break;
     case K_FINAL: final_unit(u); break;
-    case K_COMMIT: commit_unit(u - topk_units(P)); break;
+    case K_COMMIT: commit_unit<WIDE>(u - topk_units(P)); break;
     default: topk_unit(u); break;
     }
 }

@@ -430,6 +430,27 @@ def test_many_row_unit_kinds_on_ragged_shapes(monkeypatch):
     assert s.compared >= 2
 
 
+@pytest.mark.parametrize("nodes,caps,batch", [(32, (6, 6, 6), 9), (12, (4, 3, 2), 24)])
+def test_many_row_attention_units_of_several_pairs(monkeypatch, nodes, caps, batch):
+    """Whole-head attention units of the many-row kernel for trees of one or two query tiles: a unit takes four or
+    two (sequence, head) pairs, a wave per query tile.  Forced on for a small batch whose pair count (27, 72 with
+    three attention heads) leaves the last unit short of pairs (27 = 13 x 2 + 1) or not (72 = 18 x 4)."""
+    monkeypatch.setenv("VADUSA_BIG_MIN_UNITS", "1")
+    cfg = small_cfg("bf16", layers=2, d=192, heads=3, V=300, maxpos=160)
+    _say(f"many-row attention units of several pairs, {nodes}-node tree, batch {batch}")
+    W = make_weights(cfg, 19, std=STD["bf16"], ln_jitter=0.1)
+    rng = np.random.default_rng(59)
+    text, prompt = rand_tokens(cfg, rng, batch, (3, 9), (20, 75))
+    tree = make_tree(nodes, caps)
+    ls = _lock(cfg, W, text, prompt, nodes)
+    for tau in (1, 3):
+        ls.step(tree, tau)
+    ls.check_kv(layers=[0, 1])
+    s = ls.stats
+    _say(f"  compared {s.compared}/{s.steps} ties {s.tie_root}/{s.tie_list}/{s.tie_edge} logit err {s.max_logit_err:.2e}")
+    assert s.compared >= 1
+
+
 @pytest.mark.parametrize("dtype,chunk", [("fp32", 160), ("bf16", 160), ("bf16", 512)])
 def test_prefill_in_long_passes(dtype, chunk):
     """vadusa_config.prefill_chunk: the prompt runs through the decoder in passes of up to that many
