@@ -136,7 +136,7 @@ __host__ __device__ inline int commit_layers(const StepParams& P) {
 __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     const Dims& D = P.D;
     const int R = D.B * D.M, RG = cdiv(R, 64), RB = cdiv(R, 16), H = 1 + 5 * D.Ly;
-    if (ph == 0) return R;
+    if (ph == 0) return P.wide ? cdiv(R, 4) : R;
     if (P.wide && ph >= 1 && ph <= H && (ph == H || (ph - 1) % 5 != 1)) {
         // 64 x 64 output tiles: groups of four column tiles; 128 x 128: groups of eight
         const int N = ph == H ? D.V1 : (ph - 1) % 5 == 0 ? 3 * D.d : (ph - 1) % 5 == 3 ? D.F : D.d;
@@ -228,12 +228,18 @@ __device__ bool grid_sync(uint32_t epoch, int ph) {
 // embed (phase 0): one unit per row.  Writes x (fp32), its bf16 copy and the
 // per-tile row statistics.
 // ---------------------------------------------------------------------------
+// WIDE (many-row kernel): a unit is four rows, one per wave, so that a workgroup has four rows' chains of dependent
+// loads (row count, tree tables, token, embedding rows) in flight at once instead of one.
+template <bool WIDE>
 __device__ __forceinline__ void embed_unit(int r_) {
-    const int r = __builtin_amdgcn_readfirstlane(r_);
     const StepParams& P = sP;
     const Dims& D = P.D;
     const DevState& s = P.s;
-    const int b = r / D.M, n = r % D.M, tid = threadIdx.x;
+    const int r = WIDE ? __builtin_amdgcn_readfirstlane(r_) * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))
+                       : __builtin_amdgcn_readfirstlane(r_);
+    if (WIDE && r >= D.B * D.M) return;
+    constexpr int NTH = WIDE ? 64 : 256;   // threads per row
+    const int b = r / D.M, n = r % D.M, tid = WIDE ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
     int rows;
     if (P.prefill_mode) rows = ldg(s.n_rows + b);
     else rows = s.finished[b] ? 0 : D.M;
@@ -262,7 +268,7 @@ __device__ __forceinline__ void embed_unit(int r_) {
     bf16_t* xb = s.xb;                      // slot 0, tiled
     float* st = s.stats;                    // slot 0
     const int R = D.B * D.M;
-    for (int c0 = tid * 4; c0 < D.d; c0 += 1024) {
+    for (int c0 = tid * 4; c0 < D.d; c0 += NTH * 4) {
         float v[4];
         const uint2 ev = ldg2(e + c0), pv = ldg2(p + c0);
         v[0] = bf2f((bf16_t)ev.x) + bf2f((bf16_t)pv.x);
@@ -2127,7 +2133,7 @@ __device__ __forceinline__ void run_unit(int ph, int u, const uint32_t* gtab) {
         }
     }
     switch (kind) {
-    case K_EMBED: embed_unit(u); break;
+    case K_EMBED: embed_unit<WIDE>(u); break;
     case K_ATTN:
         // (the few-row kernels run their attention units from the kernel's loop: attn_prepare / attn_few)
         if constexpr (WIDE) { if (attn_allq(P)) attn_unit<true, CAUSAL>(ph, u); else attn_unit<false, CAUSAL>(ph, u); }
@@ -2174,7 +2180,7 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
     const uint32_t* gtab = WIDE ? nullptr : uniform_ptr(P.s.gtab);
     for (int ph = P.ph_lo; ph < P.ph_hi; ++ph) {
         tp(ph, 0);
-        const int nu = ph == 0 ? P.D.B * P.D.M : ph < H ? s_nu[(ph - 1) % 5] : s_nu[5 + ph - H];
+        const int nu = ph == 0 ? (WIDE ? cdiv(P.D.B * P.D.M, 4) : P.D.B * P.D.M) : ph < H ? s_nu[(ph - 1) % 5] : s_nu[5 + ph - H];
         const bool few_attn = !WIDE && ph > 0 && ph < H && (ph - 1) % 5 == 1;
         for (int u = blockIdx.x; u < nu; u += gridDim.x) {
             if constexpr (!WIDE) {
