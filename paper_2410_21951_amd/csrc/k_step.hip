@@ -1425,6 +1425,60 @@ __device__ __forceinline__ void gemm_big_impl(const GemmD& g, int nt, int row0) 
     for (int rt = 0; rt < NRT; ++rt) wide_kv_row(g, row0 + 64 * wr + 16 * rt + lc, kv_b[rt], kv_pos[rt]);
     auto finish = [&](auto kind) {
         constexpr int EPI = decltype(kind)::value;
+        if constexpr (EPI == SE_GELU || EPI == SE_QKV) {
+            // bf16 outputs in 16-byte pieces (eight consecutive columns of a row: a lane's piece of an operand tile, or
+            // of a key tile of the cache).  A lane holds four columns, the lane 16 further on the other four of the
+            // piece: two row tiles at a time, the lanes of the even 16-lane rows hand over their half of the second
+            // tile's piece and get the other half of the first tile's (one row swap per register), so that every lane
+            // stores one whole piece instead of two halves: half as many store requests.
+            const Dims& D = P.D;
+#pragma unroll
+            for (int rp = 0; rp < NRT / 2; ++rp) {
+                const int urow0 = 64 * wr + 32 * rp + lc;   // the pair's rows: urow0 and urow0 + 16
+                float mu[2], rstd[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    mu[h] = do_stats ? s_stat[urow0 + 16 * h] : 0.f;
+                    rstd[h] = do_stats ? s_stat[128 + urow0 + 16 * h] : 1.f;
+                }
+                const int mine = gq & 1;   // which of the two rows this lane stores
+                const int r = row0 + urow0 + 16 * mine;
+                const int my_b = mine ? kv_b[2 * rp + 1] : kv_b[2 * rp], my_pos = mine ? kv_pos[2 * rp + 1] : kv_pos[2 * rp];
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct) {
+                    const int tile = nt + 4 * wc + ct;
+                    uint32_t w[2][2];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        float v[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            float a = acc[ct][2 * rp + h][j];
+                            const float csj = __uint_as_float(j == 0 ? cs4[ct].x : j == 1 ? cs4[ct].y : j == 2 ? cs4[ct].z : cs4[ct].w);
+                            const float bj = __uint_as_float(j == 0 ? b4[ct].x : j == 1 ? b4[ct].y : j == 2 ? b4[ct].z : b4[ct].w);
+                            if (do_stats) a = rstd[h] * (a - mu[h] * csj);
+                            v[j] = EPI == SE_GELU ? gelu_s(a + bj) : a + bj;
+                        }
+                        w[h][0] = pack_bf16(v[0], v[1]);
+                        w[h][1] = pack_bf16(v[2], v[3]);
+                    }
+                    // first row's halves of the odd lane rows <-> second row's halves of the even lane rows
+                    const vadusa_u32x2 s0 = __builtin_amdgcn_permlane16_swap(w[0][0], w[1][0], false, false);
+                    const vadusa_u32x2 s1 = __builtin_amdgcn_permlane16_swap(w[0][1], w[1][1], false, false);
+                    const uint4 piece = make_uint4(s0.x, s1.x, s0.y, s1.y);   // columns np .. np + 7 of row r
+                    const int np = tile * 16 + 8 * (gq >> 1);
+                    if (r >= g.R || tile >= NT) continue;
+                    if (EPI == SE_GELU) stw128(g.out + toff(r, np, g.N >> 5), piece);
+                    else if (np < D.d) stw128(g.out + toff(r, np, D.d >> 5), piece);
+                    else if (my_pos >= 0) {   // key columns (a unit of value columns went the other way above)
+                        const int cc = np - D.d, head = cc >> 6, dim = cc & 63;
+                        const size_t hb = ((((size_t)g.layer * D.Bmax + my_b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
+                        stw128((bf16_t*)s.Kc + hb + kc_off(my_pos, dim), piece);
+                    }
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int rt = 0; rt < NRT; ++rt) {
             const int urow = 64 * wr + 16 * rt + lc, r = row0 + urow;

@@ -148,16 +148,17 @@ static inline int emu_dpp_mask(int ctrl) {
 #define __builtin_amdgcn_update_dpp(old, v, ctrl, rm, bm, bc) \
     (EMU_MARK, (int)emu_shfl_xor32((uint32_t)(v), emu_dpp_mask(ctrl)))
 
-// Row swaps of gfx950 (v_permlane16_swap / v_permlane32_swap) as the kernels use them, with both operands the same
-// value: the first result holds the value of the lane in the even row (lower half), the second that of the lane in
-// the odd row (upper half).
+// Row swaps of gfx950 (v_permlane16_swap / v_permlane32_swap): the first operand's odd rows (upper halves) change
+// places with the second operand's even rows (lower halves); a row is 16 lanes (a half 32).  First result: the new
+// first operand (a lane of an odd row holds the second operand of the lane `bit` below), second result: the new second
+// operand (a lane of an even row holds the first operand of the lane `bit` above).
 typedef unsigned int emu_u32x2 __attribute__((ext_vector_type(2)));
 static inline emu_u32x2 emu_permlane_swap(uint32_t a, uint32_t b, int bit) {
-    (void)b;   // only called with a == b
     const int lane = (int)(threadIdx.x & 63);
+    const uint32_t b_below = emu_shfl_idx32(b, lane & ~bit), a_above = emu_shfl_idx32(a, lane | bit);
     emu_u32x2 r;
-    r.x = emu_shfl_idx32(a, lane & ~bit);
-    r.y = emu_shfl_idx32(a, lane | bit);
+    r.x = (lane & bit) ? b_below : a;
+    r.y = (lane & bit) ? b : a_above;
     return r;
 }
 #define __builtin_amdgcn_permlane16_swap(a, b, fi, bc) (EMU_MARK, emu_permlane_swap((a), (b), 16))
