@@ -1646,13 +1646,8 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
     __syncthreads();
 
     const int rt = erow >> 4, rr = erow & 15, r = er;
-    if (r >= g.R) return;
     const float mu = do_stats ? s_stat[erow] : 0.f, rstd = do_stats ? s_stat[64 + erow] : 1.f;
-#pragma unroll
-    for (int ct = 0; ct < NCT; ++ct) {
-        const int n0 = (nt + ct) * 16 + (tid & 3) * 4;
-        if (!tile_ok[ct] || n0 >= g.N) continue;
-        float v[4];
+    auto outputs = [&](int ct, float (&v)[4]) {   // the thread's four outputs of column tile ct
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int col = (tid & 3) * 4 + j;
@@ -1665,6 +1660,62 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
             if (do_stats) a = rstd * (a - mu * csj);
             v[j] = a + bj;
         }
+    };
+    const bool qk_unit = g.epi == SE_QKV && (nt + NCT) * 16 <= 2 * D.d;   // query or key columns only
+    if ((g.epi == SE_GELU || g.epi == SE_RESID || qk_unit) && g.N % 16 == 0) {
+        // bf16 outputs leave as whole 16-byte pieces (eight consecutive columns of a row): a thread holds four columns
+        // of every tile, its neighbour the other four of the piece; two tiles at a time, the even thread hands over its
+        // half of the second tile's piece and gets the other half of the first tile's, and stores that piece whole
+        // (the odd thread the second tile's): half as many store requests.  The residual stream's four floats go out
+        // as one 16-byte store as well.  Every thread takes part in the lane exchanges, with or without a row.
+        const bool odd = tid & 1;
+#pragma unroll
+        for (int cp = 0; cp < NCT / 2; ++cp) {
+            uint32_t w[2][2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int ct = 2 * cp + h, tile = nt + ct, n0 = tile * 16 + (tid & 3) * 4;
+                float v[4];
+                outputs(ct, v);
+                if (g.epi == SE_GELU) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = gelu_s(v[j]);
+                } else if (g.epi == SE_RESID) {
+                    v[0] += __uint_as_float(xr4[ct].x); v[1] += __uint_as_float(xr4[ct].y);
+                    v[2] += __uint_as_float(xr4[ct].z); v[3] += __uint_as_float(xr4[ct].w);
+                    const bool live = r < g.R && tile_ok[ct];
+                    if (live) stw128(s.x + (size_t)r * g.N + n0, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
+                    // the statistics of the tile's 16 columns come from the four threads of the row
+                    const float mean = quad_sum(v[0] + v[1] + v[2] + v[3]) * (1.f / 16.f);
+                    const float m2 = quad_sum((v[0] - mean) * (v[0] - mean) + (v[1] - mean) * (v[1] - mean) +
+                                              (v[2] - mean) * (v[2] - mean) + (v[3] - mean) * (v[3] - mean));
+                    if (live && (tid & 3) == 0) stwf2(g.stats_out + ((size_t)tile * g.R + r) * 2, mean, m2);
+                }
+                w[h][0] = pack_bf16(v[0], v[1]);
+                w[h][1] = pack_bf16(v[2], v[3]);
+            }
+            const uint32_t t0 = (uint32_t)dpp_perm<0xB1>((int)(odd ? w[0][0] : w[1][0]));   // the neighbour's half of this thread's piece
+            const uint32_t t1 = (uint32_t)dpp_perm<0xB1>((int)(odd ? w[0][1] : w[1][1]));
+            const uint4 piece = odd ? make_uint4(t0, t1, w[1][0], w[1][1]) : make_uint4(w[0][0], w[0][1], t0, t1);
+            const int ct = 2 * cp + (odd ? 1 : 0), np = (nt + ct) * 16 + ((tid & 3) >> 1) * 8;
+            if (r >= g.R || !tile_ok[ct]) continue;
+            if (g.epi != SE_QKV) stw128(g.out + toff(r, np, g.N >> 5), piece);
+            else if (np < D.d) stw128(g.out + toff(r, np, D.d >> 5), piece);
+            else if (kv_pos >= 0) {
+                const int cc = np - D.d, head = cc >> 6, dim = cc & 63;
+                const size_t hb = ((((size_t)g.layer * D.Bmax + kv_b) * D.nH + head) * kv_cap(D.maxpos)) * 64;
+                stw128((bf16_t*)s.Kc + hb + kc_off(kv_pos, dim), piece);
+            }
+        }
+        return;
+    }
+    if (r >= g.R) return;
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+        const int n0 = (nt + ct) * 16 + (tid & 3) * 4;
+        if (!tile_ok[ct] || n0 >= g.N) continue;
+        float v[4];
+        outputs(ct, v);
         wide_store(g, r, n0, nt + ct, v, xr4[ct], true, kv_b, kv_pos);
     }
 }
