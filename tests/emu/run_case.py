@@ -56,6 +56,30 @@ if dtype == "bf16-72rows":
     assert s.compared >= 1
     sys.stdout.flush()
     os._exit(0)
+if dtype == "bf16-256rows":
+    # 256 rows (8 sequences x 32 nodes): the many-row kernel, its 128 x 128 units forced on for these small maps (value
+    # columns through LDS as 16-byte pieces with ragged cache positions, query / key / GELU outputs as pieces swapped
+    # between lanes 16 apart, a last column block of 64 of the 192-wide FFN), 64 x 64 units for the residual maps and
+    # the vocabulary map, whole-head attention units of two (sequence, head) pairs, four rows per embedding unit,
+    # compaction units over layers.
+    os.environ["VADUSA_BIG_MIN_UNITS"] = "1"
+    cfg = ModelConfig(n_layers=1, d_model=64, n_heads=1, head_dim=64, d_ffn=192, speech_vocab=71, text_vocab=20,
+                      n_draft_heads=2, max_positions=64, dtype="bf16")
+    W = make_weights(cfg, 91, std=0.05)
+    rng = np.random.default_rng(92)
+    text = [rng.integers(0, cfg.text_vocab, int(rng.integers(1, 4))).astype(np.int32) for _ in range(8)]
+    prompt = [rng.integers(0, cfg.speech_vocab, int(rng.integers(3, 12))).astype(np.int32) for _ in range(8)]
+    tree = make_tree(32, (6, 6))
+    t0 = time.time()
+    ls = Lockstep(cfg, W, text, prompt, 32)
+    ls.step(tree, 2)
+    ls.check_kv(layers=[0])
+    s = ls.stats
+    print(f"emulated {dtype}: compared {s.compared}/{s.steps} logit err {s.max_logit_err:.2e} "
+          f"ties {s.tie_root}/{s.tie_list}/{s.tie_edge} in {time.time() - t0:.0f} s", flush=True)
+    assert s.compared >= 1
+    sys.stdout.flush()
+    os._exit(0)
 if dtype == "bf16-giveup":
     # the failure path: the host raises the error word of a kernel that gave up at a grid barrier; the next
     # synchronising call reports it, later calls refuse, a prefill recovers and decodes the same tokens

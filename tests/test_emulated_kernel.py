@@ -3,8 +3,10 @@ execution model (tests/emu), in lockstep with the oracle: checks index arithmeti
 flow and bounds (the arena sits between guard pages and starts out filled with garbage)
 without a GPU.  The smallest legal model (d = 64, one head), where two of a workgroup's four
 waves have no k-steps of a linear map at all; one case with 40 rows and two layers (32 x 32
-units of QKV and FFN1 with a ragged second row block, per-layer advance of the descriptor table); and the
-failure path of a step kernel that gave up at a grid barrier (error word raised from the host)."""
+units of QKV and FFN1 with a ragged second row block, per-layer advance of the descriptor table); one with 72 rows
+(the kernel variant for 65 to 255 rows); one with 256 rows (the many-row kernel: 128 x 128 and 64 x 64 units with
+their 16-byte pieces, whole-head attention units of two pairs); and the failure path of a step kernel that gave up
+at a grid barrier (error word raised from the host)."""
 import os
 import shutil
 import subprocess
@@ -27,7 +29,7 @@ def emu_lib(tmp_path_factory):
     shutil.rmtree(str(out), ignore_errors=True)
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "fp32", "bf16-40rows", "bf16-72rows", "bf16-giveup"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp32", "bf16-40rows", "bf16-72rows", "bf16-256rows", "bf16-giveup"])
 def test_emulated_step_matches_oracle(emu_lib, dtype):
     r = subprocess.run([sys.executable, os.path.join(HERE, "emu", "run_case.py"), emu_lib, dtype],
                        stdout=subprocess.PIPE, stderr=subprocess.STDOUT, timeout=600, text=True)
