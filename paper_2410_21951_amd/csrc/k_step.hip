@@ -1725,12 +1725,14 @@ __device__ __forceinline__ void gemm_wide_unit(int ph_, int u_) {
 // sequence.  Keys: cache positions [0, L) and the rows of this forward at
 // L + m where the query's mask bit m is set.  The four waves take 32-key blocks
 // round-robin with a private online softmax (S^T = K Q^T, O^T += V^T P^T on
-// MFMA), then merge through LDS.  K is kept [pos][64], V is kept [64][pos].
+// MFMA), then merge through LDS.  The cache keeps K and V^T in blocks of 32 keys, each already in the
+// layout of the MFMA operands (kc_off / vc_off in common.h).
 // ---------------------------------------------------------------------------
-// ALLQ (many-row kernel, at least one (sequence, head) per compute unit): a unit is a whole
-// (sequence, head); wave w takes query tile w over all key blocks, so the four waves read the
-// same K / V blocks (once from L2, then from the compute unit's L1), nothing is merged across
-// waves, and the result goes from the accumulators straight to memory.
+// ALLQ (many-row kernel, at least one (sequence, head) per compute unit): a unit is one or more whole
+// (sequence, head) pairs (attn_ppu); a wave takes a query tile over all its key blocks, so the waves of a pair
+// read the same K / V blocks (once from L2, then from the compute unit's L1), nothing is merged across
+// waves, and the result goes from the accumulators straight to memory.  (Where pairs are too few for that,
+// the waves that a pair's query tiles do not need split the tiles' key blocks and merge through LDS.)
 template <bool ALLQ, bool CAUSAL>
 __device__ __forceinline__ void attn_unit(int ph_, int u_) {
     const int layer = (__builtin_amdgcn_readfirstlane(ph_) - 1) / 5, u = __builtin_amdgcn_readfirstlane(u_);
