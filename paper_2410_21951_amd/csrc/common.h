@@ -69,12 +69,15 @@ __device__ __forceinline__ void stw64(void* p, uint64_t v) {
     __hip_atomic_store((VADUSA_GLOBAL uint64_t*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 // 16 bytes at once (no atomic type is that wide: the store instruction itself, with the same agent-scope bit; the
-// compiler does not count it among the outstanding memory operations, which only makes its later waits stricter)
+// compiler does not count it among the outstanding memory operations, which only makes its later waits stricter).
+// A store of more than 8 bytes reads its data registers a little after it issues, and a vector instruction that
+// overwrites them must keep two wait states' distance: the compiler inserts those after the stores it knows, not
+// after inline assembly, so they are part of the statement.
 __device__ __forceinline__ void stw128(void* p, uint4 v) {
 #if defined(__HIP_DEVICE_COMPILE__)
     typedef uint32_t u32x4_st __attribute__((ext_vector_type(4)));
     const u32x4_st d = {v.x, v.y, v.z, v.w};
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(d) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(d) : "memory");
 #else
     *(uint4*)p = v;
 #endif
