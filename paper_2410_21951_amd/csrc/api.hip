@@ -243,7 +243,6 @@ static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vecto
     st.xb = (bf16_t*)cv.take(nslots * Rp * d * 2);
     st.stats = (float*)cv.take(nslots * st.stats_stride * 4);
     st.bar = (uint32_t*)cv.take((size_t)VADUSA_BAR_WORDS * 4);
-    st.kerr = (int32_t*)cv.take(4 * 4);
     st.tprof = (long long*)cv.take(1024 * 8);
     st.gtab = (const uint32_t*)cv.take((size_t)5 * VADUSA_GREC_WORDS * 4);
     st.layers_dev = (const LayerW*)cv.take(sizeof(LayerW) * c.n_layers);
@@ -258,12 +257,15 @@ static size_t layout(const vadusa_config& c, char* base, DevState* s, std::vecto
     st.rdraft = cv.take(Hh * Bp * d * e);
     st.zdraft = (float*)cv.take(Hh * B * V1 * 4);
     auto ints = [&](size_t n) { return (int32_t*)cv.take(n * 4); };
-    st.L = ints(B); st.root = ints(B); st.finished = ints(B);
+    // What a step hands back to the host sits in one block, so that one copy fetches it: the error word (4 words),
+    // accepted lengths, committed lengths, accepted tokens (result_block_words)
+    int32_t* res = ints(4 + 2 * B + B * (VADUSA_MAX_DRAFT_HEADS + 1));
+    st.kerr = res; st.acc_len = res + 4; st.L = res + 4 + B; st.acc_tok = res + 4 + 2 * B;
+    st.root = ints(B); st.finished = ints(B);
     st.draft_topk = ints(B * Hh * VADUSA_MAX_TOPK);
     st.tok = ints(R); st.n_rows = ints(B); st.edge_ok = ints(R);
     st.path = ints(B * (VADUSA_MAX_DRAFT_HEADS + 2));
     st.out_tok = ints(B * P); st.n_out = ints(B);
-    st.acc_tok = ints(B * (VADUSA_MAX_DRAFT_HEADS + 1)); st.acc_len = ints(B);
     st.chunk_tok = ints(R);
     st.override_topk = ints(B * Hh * VADUSA_MAX_TOPK);
     for (int t = 0; t < 2; ++t) {
@@ -509,10 +511,7 @@ static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode,
 }
 
 // After a synchronisation: did a kernel give up at a grid barrier?
-static int check_kerr(vadusa_ctx* c) {
-    if (!c->cfg.dtype) return VADUSA_OK;
-    int32_t k = 0;
-    HIP_TRY(c, hipMemcpy(&k, c->s.kerr, 4, hipMemcpyDeviceToHost));
+static int kerr_seen(vadusa_ctx* c, int32_t k) {
     if (k) {
         // The launch that gave up left the barrier counters and the decoding state half-way: nothing the context
         // holds can be trusted until vadusa_prefill has reset it (see recover()).
@@ -520,6 +519,12 @@ static int check_kerr(vadusa_ctx* c) {
         return fail(c, VADUSA_EHIP, "the step kernel timed out at a grid barrier; vadusa_prefill resets the context");
     }
     return VADUSA_OK;
+}
+static int check_kerr(vadusa_ctx* c) {
+    if (!c->cfg.dtype) return VADUSA_OK;
+    int32_t k = 0;
+    HIP_TRY(c, hipMemcpy(&k, c->s.kerr, 4, hipMemcpyDeviceToHost));
+    return kerr_seen(c, k);
 }
 
 // Every call except vadusa_prefill, vadusa_load_weights and vadusa_destroy refuses a context whose kernel gave up.
@@ -875,13 +880,15 @@ static int step_impl(vadusa_ctx* c, const vadusa_tree_spec* tree, int32_t tau, c
     if (rc) return rc;
     if (accepted_tok) {
         const int B = c->batch, W = VADUSA_MAX_DRAFT_HEADS + 1, Hh1 = c->cfg.n_draft_heads + 1;
-        std::vector<int32_t> tok((size_t)B * W), len(B), L(B);
+        // one copy for everything the host reads after a step (every separate copy is a trip of tens of microseconds)
+        std::vector<int32_t> blk(4 + 2 * (size_t)c->cfg.max_batch + (size_t)c->cfg.max_batch * W);
+        HIP_TRY(c, hipMemcpyAsync(blk.data(), c->s.kerr, blk.size() * 4, hipMemcpyDeviceToHost, c->stream));
         HIP_TRY(c, hipStreamSynchronize(c->stream));
-        rc = check_kerr(c);
+        rc = kerr_seen(c, c->cfg.dtype ? blk[0] : 0);
         if (rc) return rc;
-        HIP_TRY(c, hipMemcpy(tok.data(), c->s.acc_tok, tok.size() * 4, hipMemcpyDeviceToHost));
-        HIP_TRY(c, hipMemcpy(len.data(), c->s.acc_len, B * 4, hipMemcpyDeviceToHost));
-        HIP_TRY(c, hipMemcpy(L.data(), c->s.L, B * 4, hipMemcpyDeviceToHost));
+        const int32_t* len = blk.data() + 4;
+        const int32_t* L = len + c->cfg.max_batch;
+        const int32_t* tok = L + c->cfg.max_batch;
         for (int b = 0; b < B; ++b) {
             accepted_len[b] = len[b];
             for (int j = 0; j < Hh1; ++j) accepted_tok[(size_t)b * Hh1 + j] = j < len[b] ? tok[(size_t)b * W + j] : -1;
