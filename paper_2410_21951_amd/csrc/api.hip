@@ -501,11 +501,15 @@ static int run_phases(vadusa_ctx* c, const Dims& D, int table, int prefill_mode,
     P.table = table; P.prefill_mode = prefill_mode; P.tau = tau;
     P.ignore_eos = c->cfg.ignore_eos; P.ph_lo = lo; P.ph_hi = hi; P.persistent = c->persistent; P.profile = c->profile; P.wide = D.B * D.M >= 256; P.mid = !P.wide && D.B * D.M > 64;
     P.epoch = c->epoch; P.seq0 = seq0; P.nseq = nseq; P.topk_apart = topk_apart;
+    {
+        const int Hp = 1 + 5 * D.Ly;
+        P.fuse_select = c->persistent && !prefill_mode && lo <= Hp + TP_SELECT && hi > Hp + TP_FINAL;
+    }
     if (!c->gtab_ready) P.s.gtab = nullptr;
     hipError_t e;
     launch_step(P, c->n_cus, c->stream, &e);
     if (e != hipSuccess) return fail(c, VADUSA_EHIP, "step kernel launch failed: %s", hipGetErrorString(e));
-    if (c->persistent) c->epoch += (uint32_t)(hi - lo - 1);
+    if (c->persistent) { const int live = step_live_phases(P); c->epoch += (uint32_t)(live > 0 ? live - 1 : 0); }
     if (topk_apart) launch_topk(D, c->s, seq0, nseq, c->stream);
     return VADUSA_OK;
 }

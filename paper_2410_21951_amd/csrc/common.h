@@ -43,6 +43,14 @@ __device__ __forceinline__ T* uniform_ptr(T* p) {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
     return (T*)(((uint64_t)hi << 32) | lo);
 }
+// Makes a loaded value count as used (the load stays, and is waited for here) without storing it anywhere.
+__device__ __forceinline__ void keep_alive(uint32_t v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("" : : "v"(v));
+#else
+    (void)v;
+#endif
+}
 // 8- and 16-byte loads (HIP's uint2 / uint4 / float2 are classes: their copy would go back to a generic reference)
 typedef uint32_t vadusa_u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t vadusa_u32x2 __attribute__((ext_vector_type(2)));
@@ -338,12 +346,16 @@ struct StepParams {
     int big_min;        // many-row kernel: a map takes 128 x 128 units if it has at least this many of them
     int allq_min;       // many-row kernel: an attention unit is a whole (sequence, head) if there are at least this many
     int topk_apart;     // 1: the last phase only compacts the KV cache; the draft lists come from the stand-alone top-k kernel
+    int fuse_select;    // 1: the continuation units choose their sequence's path themselves (the selection phase has no units)
 };
 // Phases of the step kernel after the decoder layers, as offsets from H = 1 + 5 * n_layers.
 // TP_COMMIT: first map of the draft heads; TP_TOPK: draft lists and, beside them (most workgroups
 // are idle in that phase), the compaction of the KV cache.
 enum { TP_HEAD = 0, TP_EDGES, TP_SELECT, TP_FINAL, TP_COMMIT, TP_DRAFT2, TP_TOPK, TP_COUNT };
 int step_num_phases(int n_layers);
+// Phases of [ph_lo, ph_hi) that have units: a phase without units is skipped together with its grid barrier, so a
+// persistent launch passes this many barriers less one.
+int step_live_phases(const StepParams& p);
 // words of DevState::bar, the grid barrier's counters (16 of them, 64 words apart)
 #define VADUSA_BAR_WORDS 4096
 // One record per kind of layer phase: everything about a linear map that does not depend on the

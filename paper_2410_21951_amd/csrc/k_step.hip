@@ -156,12 +156,19 @@ __host__ __device__ inline int phase_units(const StepParams& P, int ph) {
     switch (ph - H) {
     case TP_HEAD: return pad8(cdiv(D.V1, 16)) * RG;
     case TP_EDGES: return P.prefill_mode ? 0 : cdiv(R, 4);
-    case TP_SELECT: return P.prefill_mode ? 0 : P.nseq;
+    case TP_SELECT: return (P.prefill_mode || P.fuse_select) ? 0 : P.nseq;
     case TP_FINAL: return P.nseq;
     case TP_COMMIT: return D.Hh * (D.d / 16) * RGb;
     case TP_DRAFT2: return D.Hh * cdiv(D.V1, 16) * RGb;
     default: return topk_units(P) + cdiv(D.Ly, commit_layers(P)) * cdiv(D.nH, 4) * P.nseq;   // TP_TOPK: draft lists, then KV compaction
     }
+}
+
+int step_live_phases(const StepParams& p) {
+    const int H = 1 + 5 * p.D.Ly;
+    int n = 0;
+    for (int ph = p.ph_lo; ph < p.ph_hi; ++ph) n += (ph < H || phase_units(p, ph) > 0) ? 1 : 0;
+    return n;
 }
 
 // Timing points of one workgroup (StepParams::profile - 1; device clock, 100 MHz): tprof[phase][k]; k = 0 phase start,
@@ -438,6 +445,13 @@ __device__ __forceinline__ bool describe_gemm(int ph, int u, GemmD& g, int& nt, 
 // before the first MFMA, so a unit pays one memory latency per chunk.  Partial
 // sums are combined in wave order through LDS.
 // ---------------------------------------------------------------------------
+// Where lane l's four accumulator floats of a 16 x 16 tile sit in a reduction buffer (in units of 16 bytes).  A
+// thread of the 64-row epilogues reads, for one of its four columns, word (row & 3) of lane (row >> 2) * 16 + column:
+// with the lanes in order the 64 reads of a wave fall into 8 of the 32 banks; with bits 3-5 of the lane folded
+// onto bits 0-2 they cover all of them, and a wave's 16-byte writes stay a permutation inside each group of eight.
+__device__ __forceinline__ int red_slot(int l) {
+    return l ^ ((l >> 3) & 7);
+}
 template <int NRT>
 __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab) {
     // arguments arrive in vector registers: make them (and all that follows from them) scalar
@@ -606,7 +620,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) red[((wave * NRT + rt) * 64 + lane) * 4 + i] = acc[rt][i];
+        for (int i = 0; i < 4; ++i) red[((wave * NRT + rt) * 64 + (NRT == 4 ? red_slot(lane) : lane)) * 4 + i] = acc[rt][i];
     __syncthreads();
     tp(g.ph, 3);   // partial sums exchanged
 
@@ -619,7 +633,7 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int col = (tid & 3) * 4 + j;
-                const int src = ((rt * 64) + (rr >> 2) * 16 + col) * 4 + (rr & 3);
+                const int src = ((rt * 64) + red_slot((rr >> 2) * 16 + col)) * 4 + (rr & 3);
                 float a = red[src];
 #pragma unroll
                 for (int w = 1; w < 4; ++w) a += red[w * 1024 + src];
@@ -844,7 +858,7 @@ __device__ __forceinline__ void gemm_unit22(int ph_, int u_, const uint32_t* gta
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) red[((wave * 4 + rt * 2 + ct) * 64 + lane) * 4 + i] = acc[rt][ct][i];
+            for (int i = 0; i < 4; ++i) red[((wave * 4 + rt * 2 + ct) * 64 + red_slot(lane)) * 4 + i] = acc[rt][ct][i];
     __syncthreads();
     tp(g.ph, 3);
     {
@@ -855,7 +869,7 @@ __device__ __forceinline__ void gemm_unit22(int ph_, int u_, const uint32_t* gta
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int col = (ecg & 3) * 4 + j;
-                const int src = (((rt * 2 + ct) * 64) + (rr >> 2) * 16 + col) * 4 + (rr & 3);
+                const int src = (((rt * 2 + ct) * 64) + red_slot((rr >> 2) * 16 + col)) * 4 + (rr & 3);
                 float a = red[src];
 #pragma unroll
                 for (int w = 1; w < 4; ++w) a += red[w * 1024 + src];
@@ -1046,7 +1060,7 @@ __device__ __forceinline__ void gemm_unit42(int ph_, int u_, const uint32_t* gta
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) red[((wave * 8 + rt * 2 + ct) * 64 + lane) * 4 + i] = acc[rt][ct][i];
+            for (int i = 0; i < 4; ++i) red[((wave * 8 + rt * 2 + ct) * 64 + red_slot(lane)) * 4 + i] = acc[rt][ct][i];
     __syncthreads();
     tp(g.ph, 3);
 #pragma unroll
@@ -1058,7 +1072,7 @@ __device__ __forceinline__ void gemm_unit42(int ph_, int u_, const uint32_t* gta
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int col = (ecg & 3) * 4 + j;
-                const int src = (((rt * 2 + ct) * 64) + (rr >> 2) * 16 + col) * 4 + (rr & 3);
+                const int src = (((rt * 2 + ct) * 64) + red_slot((rr >> 2) * 16 + col)) * 4 + (rr & 3);
                 float a = red[src];
 #pragma unroll
                 for (int w = 1; w < 4; ++w) a += red[w * 2048 + src];
@@ -2147,8 +2161,11 @@ __device__ __forceinline__ void attn_few(const AttnPrep& A) {
     tp(A.ph, 3);
     l_run = rows_sum(l_run);
     // merge the four waves: sm_m / sm_l [wave][query], sm_o [wave][dim][query]
+    // (rows of 17 floats: the merge below reads a dimension's 16 queries' worth 64 floats apart, which at 16 floats
+    // per row would put a wave's 64 reads into four banks)
+    constexpr int SO = 17;
     float* sm_o = (float*)smem;
-    float* sm_m = sm_o + 4 * 64 * 16;
+    float* sm_m = sm_o + 4 * 64 * SO;
     float* sm_l = sm_m + 64;
     __syncthreads();
     tp(A.ph, 7);
@@ -2156,7 +2173,7 @@ __device__ __forceinline__ void attn_few(const AttnPrep& A) {
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sm_o[(wave * 64 + dt * 16 + 4 * gq + i) * 16 + c] = O[dt][i];
+        for (int i = 0; i < 4; ++i) sm_o[(wave * 64 + dt * 16 + 4 * gq + i) * SO + c] = O[dt][i];
     __syncthreads();
     {
         const int q = tid >> 4, d0 = (tid & 15) * 4, nd = qt * 16 + q;
@@ -2172,13 +2189,53 @@ __device__ __forceinline__ void attn_few(const AttnPrep& A) {
         for (int j = 0; j < 4; ++j) {
             float a = 0.f;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) a += f[w] * sm_o[(w * 64 + d0 + j) * 16 + q];
+            for (int w = 0; w < 4; ++w) a += f[w] * sm_o[(w * 64 + d0 + j) * SO + q];
             o[j] = a * inv;
         }
         if (nd < D.M)
             stw64(att + toff(b * D.M + nd, h * 64 + d0, D.d >> 5),
                   (uint64_t)pack_bf16(o[0], o[1]) | ((uint64_t)pack_bf16(o[2], o[3]) << 32));
     }
+}
+
+// Workgroups without a unit in a QKV phase pull the committed part of the key / value cache that the
+// coming attention phase will stream into the L2 of the XCD whose attention units read it (Sec. 2.2: the
+// committed cache does not depend on the step's rows).  Workgroup i runs on XCD i mod 8 and the attention units of
+// (sequence, head) pair p on XCD p mod 8; the idle workgroups of an XCD split that XCD's pairs and each pair's
+// blocks among themselves.  Only blocks that lie wholly below the committed length are touched: a block the
+// step's rows are written into must not be in any L2 before the barrier (the attention units read it with plain
+// loads).  One 4-byte load per 128-byte line; the value is not used.
+__device__ __forceinline__ void warm_kv(int ph_, int nu_) {
+    const int ph = __builtin_amdgcn_readfirstlane(ph_), nu = __builtin_amdgcn_readfirstlane(nu_);
+    const StepParams& P = sP;
+    const Dims& D = P.D;
+    const DevState& s = P.s;
+    const int first = (nu + 7) & ~7;
+    const int slot = ((int)blockIdx.x - first) >> 3, nslots = ((int)gridDim.x - first) >> 3;
+    if ((int)blockIdx.x < first || (gridDim.x & 7) != 0) return;
+    const int per_xcd = pad8(D.B * D.nH) >> 3;
+    const int nparts = nslots / per_xcd;
+    if (nparts == 0) return;
+    const int bh = ((int)blockIdx.x & 7) + 8 * (slot % per_xcd), part = slot / per_xcd;
+    if (part >= nparts || bh >= D.B * D.nH) return;
+    const int b = bh / D.nH, h = bh - b * D.nH;
+    if (b >= ST_SEQ_CACHE || s_seqRows[b] == 0) return;
+    const int nfull = __builtin_amdgcn_readfirstlane(min(s_seqL[b], D.maxpos) >> 5);
+    const int layer = (ph - 1) / 5;
+    const size_t hb = ((((size_t)layer * D.Bmax + b) * D.nH + h) * kv_cap(D.maxpos)) * 64;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;
+    // a block is 4 KiB of K and 4 KiB of V^T: lanes 0-31 take the lines of K, lanes 32-63 those of V^T
+    const char* base = (const char*)(lane < 32 ? uniform_ptr((const bf16_t*)s.Kc + hb) : uniform_ptr((const bf16_t*)s.Vc + hb)) + (lane & 31) * 128;
+    const int stride = nparts * 4;
+    uint32_t acc = 0;
+    for (int blk = part + nparts * wave; blk < nfull; blk += 4 * stride) {
+        const uint32_t v0 = ldg((const uint32_t*)(base + (size_t)blk * 4096));
+        const uint32_t v1 = ldg((const uint32_t*)(base + (size_t)min(blk + stride, nfull - 1) * 4096));
+        const uint32_t v2 = ldg((const uint32_t*)(base + (size_t)min(blk + 2 * stride, nfull - 1) * 4096));
+        const uint32_t v3 = ldg((const uint32_t*)(base + (size_t)min(blk + 3 * stride, nfull - 1) * 4096));
+        acc ^= v0 ^ v1 ^ v2 ^ v3;
+    }
+    keep_alive(acc);
 }
 
 // ---------------------------------------------------------------------------
@@ -2202,6 +2259,14 @@ __device__ __forceinline__ void select_unit(int u_) { const int u = __builtin_am
 __device__ __forceinline__ void final_unit(int u_) {
     const int u = __builtin_amdgcn_readfirstlane(u_);
     const StepParams& P = sP;
+    if (P.fuse_select) {
+        // Sec. 2.3's choice and the continuation concern one sequence each: one unit does both when a launch runs
+        // both (one grid barrier and one phase of a single busy workgroup per sequence less).  The path goes through
+        // memory as before (the compaction units read it there): acknowledged before the continuation reads it.
+        dev_select(P.D, P.s, P.seq0 + u, P.ignore_eos);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
     dev_finalize<bf16_t>(P.D, P.s, P.seq0 + u, P.prefill_mode, P.ignore_eos, 1);
 }
 template <bool WIDE>
@@ -2299,9 +2364,14 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
     // the few-row kernel takes the launch-independent part of a layer map's descriptor from the
     // context's table (null: derived per unit)
     const uint32_t* gtab = WIDE ? nullptr : uniform_ptr(P.s.gtab);
+    // phases after the layers that have no units (acceptance phases of a prefill pass, the selection phase when the
+    // continuation units choose the path) are skipped with their barriers: last_ph = the last phase that runs
+    int last_ph = P.ph_hi - 1;
+    while (last_ph >= H && last_ph > P.ph_lo && s_nu[5 + last_ph - H] == 0) --last_ph;
     for (int ph = P.ph_lo; ph < P.ph_hi; ++ph) {
-        tp(ph, 0);
         const int nu = ph == 0 ? (WIDE ? cdiv(P.D.B * P.D.M, 4) : P.D.B * P.D.M) : ph < H ? s_nu[(ph - 1) % 5] : s_nu[5 + ph - H];
+        if (ph >= H && nu == 0) continue;
+        tp(ph, 0);
         const bool few_attn = !WIDE && ph > 0 && ph < H && (ph - 1) % 5 == 1;
         for (int u = blockIdx.x; u < nu; u += gridDim.x) {
             if constexpr (!WIDE) {
@@ -2317,8 +2387,11 @@ __global__ __launch_bounds__(256) void k_step(StepParams Parg) {
             }
             __syncthreads();
         }
+        if constexpr (!WIDE && !CAUSAL) {
+            if (ph > 0 && ph < H && (ph - 1) % 5 == 0 && (int)blockIdx.x >= nu && P.persistent) warm_kv(ph, nu);
+        }
         tp(ph, 1);
-        if (P.persistent && ph + 1 < P.ph_hi) {
+        if (P.persistent && ph < last_ph) {
             ++epoch;
             if (!grid_sync(epoch, ph)) return;
         }
