@@ -66,6 +66,7 @@ __device__ inline int block_argbest(const float* __restrict__ z, int n, float pv
     __syncthreads();
     bv = sv[0]; bi = si[0];
     for (int w = 1; w < 4; ++w) if (before(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+    if (bi == 0x7fffffff) bi = 0;   // no entry qualifies (a row of NaN): still an index of the row
     if (best_val) *best_val = bv;
     return bi;
 }

@@ -36,6 +36,7 @@ __global__ void k_embed(Dims D, DevState s, int prefill_mode, int table) {
         pos = s.L[b] + dep;
         if (n == 0) tok = s.root[b];
         else tok = s.draft_topk[((size_t)b * D.Hh + (dep - 1)) * VADUSA_MAX_TOPK + s.t_rank[table][n]];
+        if ((unsigned)tok >= (unsigned)D.V1) tok = 0;   // rows of NaN logits have no arg-max and no draft lists: stay inside the table
         E = (const T*)s.E_speech;
     }
     if (pos >= D.maxpos) pos = D.maxpos - 1;   // never reached: the host checks capacity first

@@ -265,6 +265,9 @@ __device__ __forceinline__ void embed_unit(int r_) {
             pos = ldg(s.L + b) + dep;
             tok = n == 0 ? s.root[b]
                          : s.draft_topk[((size_t)b * D.Hh + (dep - 1)) * VADUSA_MAX_TOPK + s.t_rank[P.table][n]];
+            // a row of logits without a largest entry (all NaN) leaves the arg-max and the draft lists without an
+            // answer: whatever they hold then, the row read below is one of the table's
+            if ((unsigned)tok >= (unsigned)D.V1) tok = 0;
         }
         if (pos >= D.maxpos) pos = D.maxpos - 1;   // the host checks capacity before launching
     }
@@ -1927,15 +1930,17 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
         return;
     }
     // merge the four waves: sm_m / sm_l [wave][query], sm_o [wave][dim][query]
+    constexpr int SO = 16;   // floats per row of sm_o (rows of 17 as in attn_few, and the 64 x 64 unit's reduction buffer with
+                             // folded lane bits, measured slower in this kernel: 1172 -> 1178 / 1174 us per step at batch 16)
     float* sm_o = (float*)smem;
-    float* sm_m = sm_o + 4 * 64 * 16;
+    float* sm_m = sm_o + 4 * 64 * SO;
     float* sm_l = sm_m + 64;
     __syncthreads();
     if (gq == 0) { sm_m[wave * 16 + c] = m_run; sm_l[wave * 16 + c] = l_run; }
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sm_o[(wave * 64 + dt * 16 + 4 * gq + i) * 16 + c] = O[dt][i];
+        for (int i = 0; i < 4; ++i) sm_o[(wave * 64 + dt * 16 + 4 * gq + i) * SO + c] = O[dt][i];
     __syncthreads();
     if constexpr (!ALLQ)
     {
@@ -1952,7 +1957,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
         for (int j = 0; j < 4; ++j) {
             float a = 0.f;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) a += f[w] * sm_o[(w * 64 + d0 + j) * 16 + q];
+            for (int w = 0; w < 4; ++w) a += f[w] * sm_o[(w * 64 + d0 + j) * SO + q];
             o[j] = a * inv;
         }
         if (nd < D.M)
@@ -1985,7 +1990,7 @@ __device__ __forceinline__ void attn_unit(int ph_, int u_) {
                 float a = 0.f;
 #pragma unroll
                 for (int w = 0; w < 4; ++w)
-                    if (w < wpq) a += f[w] * sm_o[((w0 + w) * 64 + d0 + j) * 16 + q];
+                    if (w < wpq) a += f[w] * sm_o[((w0 + w) * 64 + d0 + j) * SO + q];
                 o[j] = a * inv;
             }
             if (nd < D.M)

@@ -112,6 +112,31 @@ if dtype == "bf16-giveup":
     print("emulated give-up path: reported, refused, recovered", flush=True)
     sys.stdout.flush()
     os._exit(0)
+if dtype in ("bf16-nan", "fp32-nan"):
+    # A model whose logits are all NaN (a NaN in the final LayerNorm's scale): no row has a largest entry, so the
+    # arg-max and the draft lists have nothing to return.  The step must still stay inside its buffers (the arena sits
+    # between guard pages) and hand back token ids of the vocabulary.
+    from paper_2410_21951_amd import Vadusa, TreeArrays
+    cfg = ModelConfig(n_layers=1, d_model=64, n_heads=1, head_dim=64, d_ffn=128, speech_vocab=70, text_vocab=20,
+                      n_draft_heads=2, max_positions=64, dtype=dtype[:4])
+    W = make_weights(cfg, 71, std=0.08)
+    W["lnf_g"] = W["lnf_g"].copy()
+    W["lnf_g"][3] = np.nan
+    rng = np.random.default_rng(74)
+    text = [rng.integers(0, cfg.text_vocab, 3).astype(np.int32)]
+    prompt = [rng.integers(0, cfg.speech_vocab, 9).astype(np.int32)]
+    t = make_tree(8, (3, 2))
+    tree = TreeArrays(t.parent, t.rank)
+    dev = Vadusa(cfg, max_batch=1, max_tree_nodes=8, ignore_eos=True)
+    dev.load_weights(W)
+    dev.prefill(text, prompt)
+    for i in range(3):
+        out = dev.step(tree, 1 + i % 2)
+        for toks in out:
+            assert all(0 <= int(v) <= cfg.speech_vocab for v in toks), toks
+    print("emulated NaN logits: stayed in bounds", flush=True)
+    sys.stdout.flush()
+    os._exit(0)
 cfg = ModelConfig(n_layers=1, d_model=64, n_heads=1, head_dim=64, d_ffn=128, speech_vocab=70, text_vocab=20,
                   n_draft_heads=2, max_positions=64, dtype=dtype)
 W = make_weights(cfg, 71, std=0.08)
