@@ -7,14 +7,17 @@
 //   1+5l .. 5+5l      layer l: QKV, attention, out-projection, FFN1, FFN2
 //   H = 1+5*Ly        base head (logits of every node; Algorithm 1 line 1)
 //   H+1               acceptance: Algorithm 1 on every edge, one wave per edge
-//   H+2               Sec. 2.3 path choice per sequence
+//   H+2               Sec. 2.3 path choice per sequence (a phase of its own only in a launch that ends with it;
+//                     otherwise the continuation unit chooses the path, and a phase without units is skipped
+//                     together with its barrier)
 //   H+3               continuation from the last accepted node (Sec. 2.1)
-//   H+4               KV compaction to the accepted path || draft heads, first map
+//   H+4               draft heads, first map
 //   H+5               draft heads, vocabulary map
-//   H+6               draft top-k lists
+//   H+6               draft top-k lists || KV compaction to the accepted path
 //
 // Linear maps stream pre-tiled bf16 weights straight from HBM into the B
-// operand of v_mfma_f32_16x16x32_bf16; activations are staged in LDS.
+// operand of v_mfma_f32_16x16x32_bf16 and the activations (kept in memory in A-operand tiles) from L2
+// likewise; the many-row kernel's 128 x 128 units stage both through LDS.
 // LayerNorm is folded into the map that follows it:
 //   LN(x) W^T = rstd * (x (g*W)^T - mu * colsum(g*W)) + (beta W^T + bias),
 // so the map reads the bf16 copy of the raw residual stream and applies the
@@ -31,7 +34,8 @@
 // read before in this launch (one activation slot per layer), so a plain cached
 // load after the barrier can only miss and fetch the fresh line.  Values that
 // are re-read after having been cached (L, the residual row of the accepted
-// node) are loaded at agent scope.
+// node) are loaded at agent scope.  (Hence warm_kv, which reads cache blocks ahead of the attention phase,
+// touches only blocks that no row of the step is written into.)
 #include <algorithm>
 #include <cstdlib>
 
