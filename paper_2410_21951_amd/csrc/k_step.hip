@@ -504,14 +504,12 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
         if (g.colsum) cs4 = ldg4(g.colsum + n0);
         if (g.bias) b4 = ldg4(g.bias + n0);
         if (g.epi == SE_QKV && nt * 16 >= D.d) {
-            const int r = row0 + (tid >> 2);
+            const int r = row0 + (tid >> 2) < g.R ? row0 + (tid >> 2) : g.R - 1;   // no branch on the row: see gemm_unit22
             kv_which = (nt * 16) / D.d - 1;            // workgroup-uniform: 0 keys, 1 values
             kv_cc = (nt * 16) % D.d;
-            if (r < g.R) {
-                kv_b = r / D.M;
-                kv_L = ldg(s.L + kv_b);
-                kv_rows = ldg(s.n_rows + kv_b);
-            }
+            kv_b = r / D.M;
+            kv_L = s_seqL[kv_b];                       // (a few-row kernel has fewer than 256 rows, so all its sequences are cached)
+            kv_rows = s_seqRows[kv_b];
         }
     } else {
         const int n = nt * 16 + (tid & 15);
@@ -773,14 +771,15 @@ __device__ __forceinline__ void gemm_unit22(int ph_, int u_, const uint32_t* gta
     if (g.bias) b4 = ldg4(g.bias + n0);
     int kv_b = 0, kv_L = 0, kv_rows = 0, kv_which = 0, kv_cc = 0;
     if (g.epi == SE_QKV && nt * 16 >= D.d) {
-        const int r = row0 + erow;
+        // (no branch on the row: behind a divergent branch the compiler waits for every load that is under way, here
+        // the column sums and bias just requested, before the statistics and operands are asked for; the sequence's
+        // length and row count come from the copy in LDS, not from memory)
+        const int r = row0 + erow < g.R ? row0 + erow : g.R - 1;
         kv_which = (nt * 16) / D.d - 1;
         kv_cc = (nt * 16) % D.d;
-        if (r < g.R) {
-            kv_b = r / D.M;
-            kv_L = ldg(s.L + kv_b);
-            kv_rows = ldg(s.n_rows + kv_b);
-        }
+        kv_b = r / D.M;
+        kv_L = s_seqL[kv_b];          // (this unit runs with up to 64 rows, so at most 64 sequences: all of them cached)
+        kv_rows = s_seqRows[kv_b];
     }
     // LayerNorm statistics of the unit's 32 rows: four threads per row (threads 0..127)
     float s1 = 0.f, s2 = 0.f, s3 = 0.f, c0 = 0.f;   // c0: shift of the tile means, see gemm_unit
@@ -970,12 +969,10 @@ __device__ __forceinline__ void gemm_unit42(int ph_, int u_, const uint32_t* gta
         kv_cc = (nt * 16) % D.d;
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
-            const int r = row0 + 32 * hh + erow;
-            if (r < g.R) {
-                kv_b[hh] = r / D.M;
-                kv_L[hh] = ldg(s.L + kv_b[hh]);
-                kv_rows[hh] = ldg(s.n_rows + kv_b[hh]);
-            }
+            const int r = row0 + 32 * hh + erow < g.R ? row0 + 32 * hh + erow : g.R - 1;   // no branch on the row: see gemm_unit22
+            kv_b[hh] = r / D.M;
+            kv_L[hh] = s_seqL[kv_b[hh]];
+            kv_rows[hh] = s_seqRows[kv_b[hh]];
         }
     }
     // LayerNorm statistics of the unit's 64 rows: four threads per row
