@@ -140,7 +140,8 @@ int vadusa_create(const vadusa_config* cfg, void* arena, size_t arena_bytes,
  *   VADUSA_PHASE_LAUNCHES       one kernel launch per phase of the bf16 step instead of one
  *                               persistent launch with grid barriers
  *   VADUSA_COOPERATIVE_LAUNCH   launch the persistent kernel cooperatively
- *   VADUSA_PHASE_CLOCK=n        record the timing points of VADUSA_DBG_PHASE_CLOCK in workgroup n - 1
+ *   VADUSA_PHASE_CLOCK=n        record the timing points of VADUSA_DBG_PHASE_CLOCK in workgroup n - 1 (only the
+ *                               library built with -DVADUSA_CLOCK_BUILD, libvadusa_clock.so, has them)
  *   VADUSA_BIG_MIN_UNITS=n      many-row kernel (>= 256 rows): a linear map takes 128 x 128 output
  *                               units, and attention whole (sequence, head) units, from n such
  *                               units on (default 256 = one per compute unit); lets tests
@@ -290,7 +291,9 @@ enum {
                                     the bf16 step kernel: [p][0] start of phase p, [p][1] its own units done,
                                     [p][2..] points inside a unit, [127][0] end of the kernel.  Recorded only by
                                     contexts created while the environment variable VADUSA_PHASE_CLOCK is set
-                                    (each point costs a few hundred ns); zero otherwise */
+                                    (each point costs a few hundred ns); zero otherwise.  The points are compiled
+                                    into libvadusa_clock.so only (switched off they still cost the step 4 %);
+                                    the ordinary library returns VADUSA_ESTATE */
     VADUSA_DBG_SCORES     = 11  /* float [batch][M][V+1]: the perturbed scores (s - log(-log u) on the nucleus,
                                     -inf elsewhere) of the last stochastic verification; VADUSA_ESTATE if the
                                     last verification was a deterministic one */

@@ -7,6 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvadusa.so")
+LIB_CLOCK = os.path.join(HERE, "libvadusa_clock.so")   # the same library with the step kernel's timing points compiled in
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -amdgpu-sched-strategy=max-ilp: the step kernel runs one wave per SIMD, so the scheduler's default
@@ -22,14 +23,16 @@ def sources():
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
-def build(verbose=False):
-    """Compile every .hip file and link the shared library.  Always recompiles."""
+def build(verbose=False, clock=False):
+    """Compile every .hip file and link the shared library.  Always recompiles.
+    clock=True builds libvadusa_clock.so (timing points of VADUSA_PHASE_CLOCK compiled in) instead."""
     objs = []
     procs = []
-    os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
+    bdir = os.path.join(HERE, "_build_clock" if clock else "_build")
+    os.makedirs(bdir, exist_ok=True)
     for src in sources():
-        obj = os.path.join(HERE, "_build", os.path.basename(src) + ".o")
-        cmd = [HIPCC] + FLAGS + ["-c", src, "-o", obj]
+        obj = os.path.join(bdir, os.path.basename(src) + ".o")
+        cmd = [HIPCC] + FLAGS + (["-DVADUSA_CLOCK_BUILD"] if clock else []) + ["-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
@@ -43,10 +46,12 @@ def build(verbose=False):
             raise RuntimeError(f"hipcc failed on {src}:\n{text}")
         if verbose and text.strip():
             print(text)
-    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
+    lib = LIB_CLOCK if clock else LIB
+    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib] + objs
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv, clock=True))

@@ -958,7 +958,11 @@ extern "C" int vadusa_debug_read(vadusa_ctx* c, int32_t what, void* host, size_t
     case VADUSA_DBG_ROOT: src = s.root; need = B * 4; break;
     case VADUSA_DBG_EDGE_OK: src = s.edge_ok; need = B * M * 4; break;
     case VADUSA_DBG_FINISHED: src = s.finished; need = B * 4; break;
-    case VADUSA_DBG_PHASE_CLOCK: src = s.tprof; need = 1024 * 8; break;
+    case VADUSA_DBG_PHASE_CLOCK:
+#ifndef VADUSA_CLOCK_BUILD
+        return fail(c, VADUSA_ESTATE, "this library was built without timing points: use libvadusa_clock.so");
+#endif
+        src = s.tprof; need = 1024 * 8; break;
     case VADUSA_DBG_H_NODES: {
         need = B * M * d * 4;
         if (bytes != need) return fail(c, VADUSA_EINVAL, "expected %zu bytes", need);

@@ -176,10 +176,16 @@ int step_live_phases(const StepParams& p) {
 }
 
 // Timing points of one workgroup (StepParams::profile - 1; device clock, 100 MHz): tprof[phase][k]; k = 0 phase start,
-// 1 own units done, 2.. points inside a unit.  Read back through vadusa_debug_read.
+// 1 own units done, 2.. points inside a unit.  Read back through vadusa_debug_read.  They exist only in the library
+// built with -DVADUSA_CLOCK_BUILD (libvadusa_clock.so): a point that is switched off still costs a read of the
+// parameter block, a compare and a branch, nine of them per phase: 20 us per step at valle_b1.
 __device__ __forceinline__ void tp(int ph, int k) {
+#ifdef VADUSA_CLOCK_BUILD
     const StepParams& P = sP;
     if (P.profile && (int)blockIdx.x == P.profile - 1 && threadIdx.x == 0 && ph < 128) P.s.tprof[ph * 8 + k] = wall_clock64();
+#else
+    (void)ph; (void)k;
+#endif
 }
 
 // ---------------------------------------------------------------------------

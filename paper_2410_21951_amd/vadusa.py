@@ -17,6 +17,7 @@ MAX_TOPK = 16
 MAX_DRAFT_HEADS = 8
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libvadusa.so")
+_LIB_CLOCK_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libvadusa_clock.so")
 _lib = None
 
 
@@ -78,7 +79,8 @@ def load_library(path=None):
     global _lib
     if _lib is not None and path is None:
         return _lib
-    p = path or os.environ.get("VADUSA_LIB") or _LIB_PATH   # VADUSA_LIB: another build of the same library
+    # VADUSA_LIB: another build of the same library; with VADUSA_PHASE_CLOCK set, the build that has the timing points
+    p = path or os.environ.get("VADUSA_LIB") or (_LIB_CLOCK_PATH if os.environ.get("VADUSA_PHASE_CLOCK") else _LIB_PATH)
     if not os.path.exists(p):
         raise FileNotFoundError(f"{p} not found: build it with `python -m paper_2410_21951_amd.build`")
     lib = C.CDLL(p)
