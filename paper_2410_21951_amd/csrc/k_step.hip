@@ -204,11 +204,13 @@ __device__ __forceinline__ void tp(int ph, int k) {
 // All counters grow monotonically (epoch = number of barriers so far).
 // Bounded: after ST_SPIN_LIMIT polls, or when another workgroup has raised the
 // error flag, the workgroup gives up and the kernel ends (the host reports it).
+// Inlined: as a called function (the kernel's only call) it cost the step 10 us: what is live at
+// the end of a phase was parked in lanes of a vector register around each of the 66 calls.
 // ---------------------------------------------------------------------------
 #define BAR_GROUPS 8
 #define BAR_TOPS 8
 #define BAR_STRIDE 64   // words between counters
-__device__ bool grid_sync(uint32_t epoch, int ph) {
+__device__ __forceinline__ bool grid_sync(uint32_t epoch, int ph) {
     const StepParams& P = sP;
     __shared__ int s_ok;
     // The workgroup barrier does not wait for global stores (only for LDS traffic): every thread
