@@ -27,6 +27,16 @@ def test_every_declared_symbol_is_exported(lib):
         assert getattr(lib, name) is not None
 
 
+def test_the_library_with_timing_points_exports_the_same_symbols():
+    """libvadusa_clock.so (the step kernel's timing points compiled in; the binding loads it when
+    VADUSA_PHASE_CLOCK is set) is the same library otherwise."""
+    path = V._LIB_CLOCK_PATH
+    assert os.path.exists(path), "build it with `python -m paper_2410_21951_amd.build`"
+    clock = V.load_library(path)
+    for name in V.EXPORTS:
+        assert getattr(clock, name) is not None
+
+
 def _cfg(model, **kw):
     c = V.make_config(model, kw.pop("max_batch", 1), kw.pop("max_tree_nodes", 64))
     for k, v in kw.items():
