@@ -563,13 +563,16 @@ __device__ __forceinline__ void gemm_unit(int ph_, int u_, const uint32_t* gtab)
     const bool stats_early = do_stats && tiles <= 64;
     float2 sv[16];
     if (stats_early) {
+        // addresses as the statistics' base (the same for the workgroup: scalar registers) plus a 32-bit byte offset per
+        // thread and tile: no 64-bit multiplication per load (with one wave per SIMD, seventeen of them cost 0.6 us)
         const int r = row0 + (tid >> 2);
-        const float2* sp = (const float2*)g.stats + (r < g.R ? r : 0);
-        c0 = ldgf2(sp).x;
+        const char* sb = (const char*)uniform_ptr(g.stats);
+        const uint32_t roff = (uint32_t)(r < g.R ? r : 0) * 8u, tstride = (uint32_t)g.R * 8u;
+        c0 = ldgf2(sb + roff).x;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int t = (tid & 3) + 4 * j;
-            sv[j] = ldgf2(sp + (size_t)(t < tiles ? t : 0) * g.R);
+            sv[j] = ldgf2(sb + (roff + (uint32_t)(t < tiles ? t : 0) * tstride));
         }
     }
     // the first pass always runs: a wave without k-steps (K < 128) loads nothing in it but still
@@ -796,13 +799,16 @@ __device__ __forceinline__ void gemm_unit22(int ph_, int u_, const uint32_t* gta
     const bool stats_early = do_stats && tiles <= 64;
     float2 sv[16];
     if (stats_early) {
+        // addresses as the statistics' base (the same for the workgroup: scalar registers) plus a 32-bit byte offset per
+        // thread and tile: no 64-bit multiplication per load (with one wave per SIMD, seventeen of them cost 0.6 us)
         const int r = row0 + (tid >> 2);
-        const float2* sp = (const float2*)g.stats + (r < g.R ? r : 0);
-        c0 = ldgf2(sp).x;
+        const char* sb = (const char*)uniform_ptr(g.stats);
+        const uint32_t roff = (uint32_t)(r < g.R ? r : 0) * 8u, tstride = (uint32_t)g.R * 8u;
+        c0 = ldgf2(sb + roff).x;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int t = (tid & 3) + 4 * j;
-            sv[j] = ldgf2(sp + (size_t)(t < tiles ? t : 0) * g.R);
+            sv[j] = ldgf2(sb + (roff + (uint32_t)(t < tiles ? t : 0) * tstride));
         }
     }
     for (int kb = ks_lo; kb == ks_lo || kb < ks_hi; kb += CH) {
@@ -990,13 +996,16 @@ __device__ __forceinline__ void gemm_unit42(int ph_, int u_, const uint32_t* gta
     const bool stats_early = do_stats && tiles <= 64;
     float2 sv[16];
     if (stats_early) {
+        // addresses as the statistics' base (the same for the workgroup: scalar registers) plus a 32-bit byte offset per
+        // thread and tile: no 64-bit multiplication per load (with one wave per SIMD, seventeen of them cost 0.6 us)
         const int r = row0 + (tid >> 2);
-        const float2* sp = (const float2*)g.stats + (r < g.R ? r : 0);
-        c0 = ldgf2(sp).x;
+        const char* sb = (const char*)uniform_ptr(g.stats);
+        const uint32_t roff = (uint32_t)(r < g.R ? r : 0) * 8u, tstride = (uint32_t)g.R * 8u;
+        c0 = ldgf2(sb + roff).x;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int t = (tid & 3) + 4 * j;
-            sv[j] = ldgf2(sp + (size_t)(t < tiles ? t : 0) * g.R);
+            sv[j] = ldgf2(sb + (roff + (uint32_t)(t < tiles ? t : 0) * tstride));
         }
     }
     for (int kb = ks_lo; kb == ks_lo || kb < ks_hi; kb += CH) {
